@@ -1,0 +1,125 @@
+/*
+ * orc — the CPU oracle of the batched pixel-observation renderer.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This is a plain, slow, single-threaded
+ * rasterizer that defines what the GPU library must compute.  It is linked by
+ * nothing in the product path: only the test-suite, the smoke check and the
+ * benchmark's "cpu_baseline" leg load it.  It shares no source, header, table
+ * or helper with the HIP library.
+ *
+ * The paper (PixelBrax, sections 1 and 2) fixes only WHAT is produced: one
+ * small RGB observation per parallel environment per step, rendered from the
+ * simulator's rigid-body poses on the accelerator, optionally with a colour
+ * distractor (the whole frame's colour bias changes at every step) or a video
+ * distractor (frame t of a device-resident video is overlaid at step t), all
+ * randomness drawn from an explicit seeded generator.  It says nothing about
+ * geometry, camera, raster rules or precision; those conventions are this
+ * build's reading and are written out, step by step, in orc.cpp.
+ *
+ * Pins (tests/test_oracle_*.py): mesh counts, closedness, orientation and
+ * volume; camera orthonormality and centre projection; axis-aligned quad
+ * pixel counts and watertightness; convex cover count; front set == back set;
+ * exact rational point-in-triangle; permutation invariance; analytic and
+ * Moller-Trumbore ray casts; horizon row; shade extremes; RNG bijectivity and
+ * statistics; distractor identities.
+ * Parity unpinned: agreement of orc_philox with the published Philox-4x32-10
+ * known-answer vectors (none are available offline; the method only needs a
+ * reproducible, well-mixed counter-based generator, which the pins do check).
+ */
+#ifndef ORC_H
+#define ORC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ORC_ID_GROUND 0xFFFFFFFEu
+#define ORC_ID_BG     0xFFFFFFFFu
+
+/* primitive kinds */
+#define ORC_CAPSULE 0u
+#define ORC_SPHERE  1u
+#define ORC_BOX     2u
+
+/* distractor modes (paper section 2: "color" or "video") */
+#define ORC_DIS_NONE  0u
+#define ORC_DIS_COLOR 1u
+#define ORC_DIS_VIDEO 2u
+
+typedef struct orc_scene orc_scene;
+
+/* Scene parameters, all host memory, all copied.
+ *   kinds[K], shapes[K*4] (a,b,c,h), rgbs[K*3], n_lon[K], n_lat[K]
+ *   cam[9]    = fov_y_deg, offset xyz, up xyz, z_near, z_far
+ *   light[5]  = direction-toward-light xyz, ambient, diffuse
+ *   ground[4] = enabled (0/1), cell size, grey0, grey1
+ *   bg[3]     = background rgb
+ * Returns NULL on invalid input. */
+orc_scene* orc_scene_create(uint32_t width, uint32_t height, uint32_t n_bodies, uint32_t root_body,
+                            const uint32_t* kinds, const float* shapes, const float* rgbs,
+                            const uint32_t* n_lon, const uint32_t* n_lat,
+                            const float* cam, const float* light, const float* ground, const float* bg);
+void orc_scene_destroy(orc_scene* s);
+
+/* total template vertices / triangles */
+void orc_scene_counts(const orc_scene* s, uint32_t* n_verts, uint32_t* n_tris);
+
+/* Template mesh: unit vertices (ux,uy,uz,s)[V*4], index triples [T*3] (global
+ * vertex ids), unit normals [T*3] (body frame), colour multiplier [T], owning
+ * body of each triangle [T] and of each vertex [V].  Any pointer may be NULL. */
+void orc_scene_mesh(const orc_scene* s, float* uverts, uint32_t* tris, float* normals, float* mul,
+                    uint32_t* tri_body, uint32_t* vert_body);
+
+/* Camera constants: Rv[9] (rows right, up, forward), f, cx[W], cy[H], gs[2], l[3]. */
+void orc_scene_camera(const orc_scene* s, float* Rv, float* f, float* cx, float* cy, float* gs, float* l);
+
+/* Vertex stage for ONE frame: poses[K*7] = (px,py,pz,qw,qx,qy,qz) per body,
+ * shapes[K*4] or NULL (scene shapes).  Writes snapped X[V], Y[V] (8 sub-pixel
+ * bits), reversed depth D[V] and rejected[V] (1 = fails the near/guard test;
+ * X,Y,D are then 0).  eye[3] (may be NULL) receives the camera position. */
+void orc_vertex_stage(const orc_scene* s, const float* poses, const float* shapes,
+                      int32_t* X, int32_t* Y, float* D, uint8_t* rejected, float* eye);
+
+/* Raster + z-test of an arbitrary snapped triangle soup (no scene needed).
+ *   order: permutation of [0,n_tris) giving the submission order, or NULL
+ *   cull:  0 = keep front faces (the renderer's rule), 1 = keep back faces
+ *          instead, 2 = full-image candidate loop instead of the bbox loop
+ *          (front faces)
+ * Outputs (each may be NULL): ids[H*W] winning triangle id or ORC_ID_BG,
+ * depth_bits[H*W] float bits of the winning depth (0 where background),
+ * cover[H*W] number of kept triangles covering each pixel centre. */
+void orc_raster(uint32_t width, uint32_t height, uint32_t n_verts, const int32_t* X, const int32_t* Y,
+                const float* D, const uint8_t* rejected, uint32_t n_tris, const uint32_t* tris,
+                const uint32_t* order, uint32_t cull, uint32_t* ids, uint32_t* depth_bits, uint32_t* cover);
+
+/* Distractor parameters for orc_render. */
+typedef struct {
+    uint32_t mode;
+    uint64_t seed;
+    float scale_lo, scale_hi, offset_lo, offset_hi; /* colour mode */
+    const uint8_t* video;                           /* video mode: [n_frames,H,W,3], host */
+    uint32_t n_frames;
+    float alpha;
+    const uint32_t* env_offset;                     /* [B] or NULL -> drawn from the generator */
+} orc_distractor;
+
+/* Full path: poses[B,S,K,7], shapes[B,K,4] or NULL, frames[B,S,H,W,3] out,
+ * ids[B,S,H,W] out or NULL, depth_bits[B,S,H,W] out or NULL.  env0 is the
+ * global index of the first environment (the generator is keyed by global
+ * environment index).  order = optional triangle submission order. */
+int orc_render(const orc_scene* s, const float* poses, const float* shapes, uint32_t B, uint32_t S,
+               uint32_t step0, uint32_t env0, const orc_distractor* dis, const uint32_t* order,
+               uint8_t* frames, uint32_t* ids, uint32_t* depth_bits);
+
+/* Counter-based generator: 10 rounds of the 4x32 multiply/xor network on
+ * counter (c0..c3) under the 64-bit key `seed`; out[4]. */
+void orc_philox(uint64_t seed, uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t* out);
+/* 24-bit uniform in [0,1) from one 32-bit word. */
+float orc_u01(uint32_t x);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

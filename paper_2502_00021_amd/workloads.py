@@ -1,0 +1,277 @@
+"""Seeded synthetic workloads standing in for the paper's Brax environments and DAVIS videos.
+
+The paper renders HalfCheetah / Ant / Walker2d / Humanoid states produced by
+the Brax simulator and overlays DAVIS-2017 videos (section 2).  Neither is
+available offline, so these generators emit articulated-primitive scenes and a
+moving-disc video with the same shapes and structure: a kinematic chain, a
+quadruped, a humanoid tree, a humanoid plus obstacle with a 3-step frame stack.
+
+This module only prepares INPUTS (scene descriptions as plain dicts, fp32 pose
+arrays, uint8 video).  It contains none of the renderer's arithmetic and is the
+one module shared by the HIP path's tests/bench and the CPU oracle's tests.
+All arrays come from numpy.random.default_rng(250200021 + cfg).
+"""
+import numpy as np
+
+SEED_BASE = 250200021
+
+
+def default_scene(width, height, bodies, root_body=0):
+    return dict(
+        width=width, height=height, bodies=bodies, root_body=root_body,
+        fov_y_deg=60.0, cam_offset=(-2.5, 0.0, 1.0), cam_up=(0.0, 0.0, 1.0),
+        z_near=0.1, z_far=50.0,
+        light_dir=(-0.4, -0.3, 0.85), ambient=0.3, diffuse=0.7,
+        ground_enabled=True, ground_cell=1.0, ground_grey=(0.35, 0.65),
+        background_rgb=(0.55, 0.70, 0.90),
+    )
+
+
+def capsule(r, h, rgb, n_lon=12, n_lat=6):
+    return dict(kind="capsule", shape=(float(r), float(r), float(r), float(h)),
+                rgb=tuple(float(c) for c in rgb), n_lon=n_lon, n_lat=n_lat)
+
+
+def sphere(r, rgb, n_lon=16, n_lat=8):
+    return dict(kind="sphere", shape=(float(r), float(r), float(r), 0.0),
+                rgb=tuple(float(c) for c in rgb), n_lon=n_lon, n_lat=n_lat)
+
+
+def box(ex, ey, ez, rgb, n=4):
+    return dict(kind="box", shape=(float(ex), float(ey), float(ez), 0.0),
+                rgb=tuple(float(c) for c in rgb), n_lon=n, n_lat=0)
+
+
+# ------------------------------------------------------------------ quaternion helpers (w,x,y,z), float64
+
+def q_mul(a, b):
+    aw, ax, ay, az = a[..., 0], a[..., 1], a[..., 2], a[..., 3]
+    bw, bx, by, bz = b[..., 0], b[..., 1], b[..., 2], b[..., 3]
+    return np.stack([aw * bw - ax * bx - ay * by - az * bz,
+                     aw * bx + ax * bw + ay * bz - az * by,
+                     aw * by - ax * bz + ay * bw + az * bx,
+                     aw * bz + ax * by - ay * bx + az * bw], axis=-1)
+
+
+def q_axis_angle(axis, angle):
+    axis = np.asarray(axis, dtype=np.float64)
+    angle = np.asarray(angle, dtype=np.float64)
+    axis = np.broadcast_to(axis, angle.shape + (3,))
+    h = 0.5 * angle
+    return np.concatenate([np.cos(h)[..., None], axis * np.sin(h)[..., None]], axis=-1)
+
+
+def q_rotate(q, v):
+    w, x, y, z = q[..., 0], q[..., 1], q[..., 2], q[..., 3]
+    vx, vy, vz = v[..., 0], v[..., 1], v[..., 2]
+    tx = 2.0 * (y * vz - z * vy)
+    ty = 2.0 * (z * vx - x * vz)
+    tz = 2.0 * (x * vy - y * vx)
+    return np.stack([vx + w * tx + (y * tz - z * ty),
+                     vy + w * ty + (z * tx - x * tz),
+                     vz + w * tz + (x * ty - y * tx)], axis=-1)
+
+
+def q_normalize(q):
+    return q / np.linalg.norm(q, axis=-1, keepdims=True)
+
+
+def random_quats(rng, shape):
+    return q_normalize(rng.standard_normal(tuple(shape) + (4,)))
+
+
+def _pose(pos, quat):
+    return np.concatenate([pos, q_normalize(quat)], axis=-1).astype(np.float32)
+
+
+EZ = np.array([0.0, 0.0, 1.0])
+
+
+# ------------------------------------------------------------------ the five configurations
+
+def cfg1(B=16):
+    """16 envs, 32x32, ground + 4 free-floating capsules (8 longitudes x 4 latitudes per hemisphere)."""
+    rng = np.random.default_rng(SEED_BASE + 1)
+    K = 4
+    r = rng.uniform(0.03, 0.08, K)
+    h = rng.uniform(0.1, 0.3, K)
+    rgb = rng.uniform(0.2, 0.9, (K, 3))
+    bodies = [capsule(r[k], h[k], rgb[k], 8, 4) for k in range(K)]
+    pos = np.stack([rng.uniform(-0.5, 0.5, (B, 1, K)), rng.uniform(-0.5, 0.5, (B, 1, K)),
+                    rng.uniform(0.2, 0.8, (B, 1, K))], axis=-1)
+    quat = random_quats(rng, (B, 1, K))
+    return dict(name="cfg1-capsules-32", desc=default_scene(32, 32, bodies), poses=_pose(pos, quat),
+                shapes=None, distractor=None, step0=0)
+
+
+def cfg2(B=256):
+    """256 envs, 64x64, planar 7-capsule kinematic chain in the world Y-Z plane."""
+    rng = np.random.default_rng(SEED_BASE + 2)
+    K = 7
+    h = rng.uniform(0.1, 0.25, K)
+    rgb = rng.uniform(0.2, 0.9, (K, 3))
+    bodies = [capsule(0.046, h[k], rgb[k], 12, 6) for k in range(K)]
+    theta = rng.uniform(-0.8, 0.8, (B, K))
+    cum = np.cumsum(theta, axis=1)
+    pos = np.zeros((B, 1, K, 3))
+    quat = np.zeros((B, 1, K, 4))
+    start = None
+    for i in range(K):
+        q = q_axis_angle(np.array([1.0, 0.0, 0.0]), cum[:, i])
+        axis = q_rotate(q, np.broadcast_to(EZ, (B, 3)))
+        if i == 0:
+            centre = np.broadcast_to(np.array([0.0, 0.0, 1.0]), (B, 3)).copy()
+        else:
+            centre = start + h[i] * axis
+        start = centre + h[i] * axis
+        pos[:, 0, i] = centre
+        quat[:, 0, i] = q
+    return dict(name="cfg2-chain-64", desc=default_scene(64, 64, bodies), poses=_pose(pos, quat),
+                shapes=None, distractor=None, step0=0)
+
+
+def cfg3(B=4096):
+    """4096 envs, 64x64, quadruped: sphere torso + 4 two-link legs; colour distractor."""
+    rng = np.random.default_rng(SEED_BASE + 3)
+    rgb = rng.uniform(0.2, 0.9, (9, 3))
+    bodies = [sphere(0.25, rgb[0], 16, 8)] + [capsule(0.05, 0.15, rgb[1 + k], 12, 6) for k in range(8)]
+    K = 9
+    hl = 0.15
+    yaw = rng.uniform(0.0, 2.0 * np.pi, B)
+    ang = rng.uniform(-1.0, 1.0, (B, 4, 2))
+    q_root = q_axis_angle(EZ, yaw)
+    root = np.broadcast_to(np.array([0.0, 0.0, 0.75]), (B, 3))
+    pos = np.zeros((B, 1, K, 3))
+    quat = np.zeros((B, 1, K, 4))
+    pos[:, 0, 0] = root
+    quat[:, 0, 0] = q_root
+    hips = [(0.18, 0.18, -0.1), (0.18, -0.18, -0.1), (-0.18, 0.18, -0.1), (-0.18, -0.18, -0.1)]
+    ey = np.array([0.0, 1.0, 0.0])
+    for leg in range(4):
+        hip = root + q_rotate(q_root, np.broadcast_to(np.array(hips[leg]), (B, 3)))
+        q1 = q_mul(q_root, q_axis_angle(ey, ang[:, leg, 0]))
+        d1 = -q_rotate(q1, np.broadcast_to(EZ, (B, 3)))
+        q2 = q_mul(q_root, q_axis_angle(ey, ang[:, leg, 0] + ang[:, leg, 1]))
+        d2 = -q_rotate(q2, np.broadcast_to(EZ, (B, 3)))
+        knee = hip + 2.0 * hl * d1
+        pos[:, 0, 1 + 2 * leg] = hip + hl * d1
+        quat[:, 0, 1 + 2 * leg] = q1
+        pos[:, 0, 2 + 2 * leg] = knee + hl * d2
+        quat[:, 0, 2 + 2 * leg] = q2
+    dis = dict(mode="color", seed=SEED_BASE + 3, scale=(0.5, 1.5), offset=(-0.2, 0.2))
+    return dict(name="cfg3-quadruped-64", desc=default_scene(64, 64, bodies), poses=_pose(pos, quat),
+                shapes=None, distractor=dis, step0=0)
+
+
+def _humanoid_scene(rng):
+    """Scene-level humanoid parameters: 13 capsules (torso + 4 limbs x 3 links) + head sphere = 14 bodies."""
+    rgb = rng.uniform(0.2, 0.9, (14, 3))
+    radii = rng.uniform(0.04, 0.09, (4, 3))
+    arm_h = rng.uniform(0.08, 0.14, (2, 3))
+    leg_h = rng.uniform(0.12, 0.20, (2, 3))
+    half = np.concatenate([arm_h, leg_h], axis=0)  # limb order: L arm, R arm, L leg, R leg
+    axes = q_normalize(rng.standard_normal((4, 3, 3)))
+    bodies = [capsule(0.09, 0.22, rgb[0], 12, 6), sphere(0.10, rgb[1], 16, 8)]
+    for limb in range(4):
+        for k in range(3):
+            bodies.append(capsule(radii[limb, k], half[limb, k], rgb[2 + limb * 3 + k], 12, 6))
+    anchors = np.array([(0.0, 0.22, 0.2), (0.0, -0.22, 0.2), (0.0, 0.1, -0.25), (0.0, -0.1, -0.25)])
+    return bodies, half, axes, anchors
+
+
+def _humanoid_fk(q_root, root, angles, half, axes, anchors):
+    """angles [N,4,3] -> positions [N,14,3], quaternions [N,14,4]."""
+    N = angles.shape[0]
+    pos = np.zeros((N, 14, 3))
+    quat = np.zeros((N, 14, 4))
+    pos[:, 0] = root
+    quat[:, 0] = q_root
+    pos[:, 1] = root + q_rotate(q_root, np.broadcast_to(np.array([0.0, 0.0, 0.38]), (N, 3)))
+    quat[:, 1] = q_root
+    for limb in range(4):
+        start = root + q_rotate(q_root, np.broadcast_to(anchors[limb], (N, 3)))
+        q = q_root
+        for k in range(3):
+            q = q_mul(q, q_axis_angle(axes[limb, k], angles[:, limb, k]))
+            d = -q_rotate(q, np.broadcast_to(EZ, (N, 3)))
+            idx = 2 + limb * 3 + k
+            pos[:, idx] = start + half[limb, k] * d
+            quat[:, idx] = q
+            start = start + 2.0 * half[limb, k] * d
+    return pos, quat
+
+
+def make_video(rng, n_frames, H, W):
+    """Synthetic distractor video [n,H,W,3] uint8: dark random-grey background + 6 moving random-colour discs."""
+    grey = rng.integers(10, 50, (H, W, 1))
+    video = np.broadcast_to(grey, (n_frames, H, W, 3)).astype(np.uint8).copy()
+    yy, xx = np.mgrid[0:H, 0:W]
+    for _ in range(6):
+        rad = rng.uniform(6.0, 18.0)
+        colour = rng.integers(0, 256, 3).astype(np.uint8)
+        p0 = rng.uniform(0.0, [W, H])
+        vel = rng.uniform(-3.0, 3.0, 2)
+        for t in range(n_frames):
+            cx, cy = (p0 + vel * t) % np.array([W, H])
+            dx = np.minimum(np.abs(xx - cx), W - np.abs(xx - cx))
+            dy = np.minimum(np.abs(yy - cy), H - np.abs(yy - cy))
+            video[t][dx * dx + dy * dy <= rad * rad] = colour
+    return video
+
+
+def cfg4(B=16384):
+    """16384 envs, 84x84, humanoid tree (14 bodies); 64-frame video distractor on background and ground."""
+    rng = np.random.default_rng(SEED_BASE + 4)
+    bodies, half, axes, anchors = _humanoid_scene(rng)
+    video = make_video(rng, 64, 84, 84)
+    yaw = rng.uniform(0.0, 2.0 * np.pi, B)
+    angles = rng.uniform(-1.0, 1.0, (B, 4, 3))
+    q_root = q_axis_angle(EZ, yaw)
+    root = np.broadcast_to(np.array([0.0, 0.0, 1.25]), (B, 3))
+    pos, quat = _humanoid_fk(q_root, root, angles, half, axes, anchors)
+    dis = dict(mode="video", seed=SEED_BASE + 4, video=video, alpha=0.5, env_offset=None)
+    return dict(name="cfg4-humanoid-84-video", desc=default_scene(84, 84, bodies),
+                poses=_pose(pos[:, None], quat[:, None]), shapes=None, distractor=dis, step0=0)
+
+
+def cfg5(B=65536, S=3):
+    """65536 envs x 3 steps, 64x64, humanoid + per-env checker box; colour distractor; frame stack."""
+    rng = np.random.default_rng(SEED_BASE + 5)
+    bodies, half, axes, anchors = _humanoid_scene(rng)
+    box_rgb = rng.uniform(0.2, 0.9, 3)
+    bodies = bodies + [box(0.2, 0.2, 0.2, box_rgb, 4)]
+    K = 15
+    yaw = rng.uniform(0.0, 2.0 * np.pi, B)
+    q_root = q_axis_angle(EZ, yaw)
+    root = np.broadcast_to(np.array([0.0, 0.0, 1.25]), (B, 3))
+    size = rng.uniform(0.2, 0.6, (B, 3))
+    ext = 0.5 * size
+    box_pos = np.stack([rng.uniform(0.6, 1.6, B), rng.uniform(-0.8, 0.8, B), ext[:, 2]], axis=-1)
+    box_q = q_axis_angle(EZ, rng.uniform(0.0, 2.0 * np.pi, B))
+    angles = rng.uniform(-1.0, 1.0, (B, 4, 3))
+    pos = np.zeros((B, S, K, 3))
+    quat = np.zeros((B, S, K, 4))
+    for s in range(S):
+        if s > 0:
+            angles = angles + rng.normal(0.0, 0.05, (B, 4, 3))
+        p, q = _humanoid_fk(q_root, root, angles, half, axes, anchors)
+        pos[:, s, :14] = p
+        quat[:, s, :14] = q
+        pos[:, s, 14] = box_pos
+        quat[:, s, 14] = box_q
+    shapes = np.zeros((B, K, 4), np.float32)
+    for k in range(14):
+        shapes[:, k] = np.asarray(bodies[k]["shape"], np.float32)
+    shapes[:, 14, :3] = ext.astype(np.float32)
+    dis = dict(mode="color", seed=SEED_BASE + 5, scale=(0.5, 1.5), offset=(-0.2, 0.2))
+    return dict(name="cfg5-humanoid-box-64-stack3", desc=default_scene(64, 64, bodies),
+                poses=_pose(pos, quat), shapes=shapes, distractor=dis, step0=0)
+
+
+CONFIGS = {1: cfg1, 2: cfg2, 3: cfg3, 4: cfg4, 5: cfg5}
+
+
+def make(cfg, B=None):
+    """Workload `cfg` in 1..5, optionally at a reduced (or enlarged) environment count."""
+    fn = CONFIGS[int(cfg)]
+    return fn() if B is None else fn(B)
