@@ -1,0 +1,161 @@
+/*
+ * pxr — batched pixel-observation renderer for one AMD MI355X (gfx950).
+ *
+ * C ABI of the hot path that PixelBrax (arXiv 2502.00021) moves onto the
+ * accelerator: for each of B parallel environments and each of S steps, turn
+ * the simulator's rigid-body poses into one small RGB observation without the
+ * frame ever leaving the device (paper section 1), optionally with a colour or
+ * a video distractor fused into the renderer (paper section 2) and with all
+ * randomness drawn from an explicit seeded generator (paper sections 1-2).
+ *
+ * All functions return a PXR_* status code, never throw or abort across the
+ * ABI, and leave out-parameters untouched on error.  pxr_last_error() gives a
+ * human-readable reason for the last failure on the calling thread.
+ *
+ * Pointers named d_* are DEVICE pointers owned by the caller; everything else
+ * is host memory.  The library owns only the pxr_scene and the device-side
+ * constants it uploads at creation.
+ */
+#ifndef PXR_H
+#define PXR_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pxr_scene pxr_scene; /* opaque, owned by the library */
+
+enum { PXR_OK = 0, PXR_ERR_INVALID_ARG = 1, PXR_ERR_UNSUPPORTED = 2, PXR_ERR_OOM = 3, PXR_ERR_DEVICE = 4 };
+enum { PXR_CAPSULE = 0, PXR_SPHERE = 1, PXR_BOX = 2 };
+enum { PXR_DISTRACT_NONE = 0, PXR_DISTRACT_COLOR = 1, PXR_DISTRACT_VIDEO = 2 };
+
+/* Winning-id values that are not triangles. */
+#define PXR_ID_GROUND 0xFFFFFFFEu
+#define PXR_ID_BG     0xFFFFFFFFu
+
+/* One rigid body = one primitive, tessellated once at scene creation.
+ *   shape: capsule (r,r,r,h): radius r, half-length h of the segment along local +Z
+ *          sphere  (r,r,r,0)
+ *          box     (ex,ey,ez,0): half-extents
+ *          The posed local vertex is (shape[0]*ux, shape[1]*uy, shape[2]*uz + s*shape[3]) for the
+ *          unit-shape template vertex (ux,uy,uz) with cap selector s.
+ *   n_lon, n_lat: capsule/sphere: longitudes, latitude steps PER HEMISPHERE
+ *          (capsule 4*n_lon*n_lat triangles, sphere 2*n_lon*(2*n_lat-1));
+ *          box: n_lon = cells per face edge (12*n_lon^2 triangles, checker
+ *          colour multiplier 1 / 0.5 per cell), n_lat ignored. */
+typedef struct {
+    uint32_t type;
+    float shape[4];
+    float rgb[3];
+    uint32_t n_lon, n_lat;
+} pxr_body_desc;
+
+/* Scene = what is common to all environments: image size, bodies, camera rig,
+ * light, ground, background.  The camera sits at (root body position +
+ * cam_offset) in WORLD axes and looks at the root body; pinhole, fov_y_deg
+ * vertical field of view.  light_dir points TOWARD the light.  The ground is
+ * the plane z = 0 with a two-grey checkerboard of ground_cell metres. */
+typedef struct {
+    uint32_t width, height, n_bodies, root_body;
+    const pxr_body_desc* bodies; /* host, borrowed for the call only */
+    float fov_y_deg, cam_offset[3], cam_up[3], z_near, z_far;
+    float light_dir[3], ambient, diffuse;
+    uint32_t ground_enabled;
+    float ground_cell, ground_grey[2];
+    float background_rgb[3];
+} pxr_scene_desc;
+
+/* Distractor state (paper section 2: "color" or "video", mutually exclusive).
+ *   COLOR: per (env, step) and per channel, scale ~ U[scale_lo,scale_hi) and
+ *          offset ~ U[offset_lo,offset_hi) from the counter-based generator
+ *          keyed by (seed, env, step); every pixel becomes clamp(c*scale+offset, 0, 1).
+ *   VIDEO: d_video is a device-resident uint8 [n_frames,H,W,3] clip; env e at
+ *          step t shows frame (env_offset[e] + t) mod n_frames, alpha-blended
+ *          onto pixels whose winner is the ground or the background.
+ *          d_env_offset: device uint32 [B] (indexed by the env's position in
+ *          the batch), or NULL = drawn from the generator.  Both buffers are
+ *          caller-owned and must stay alive while bound. */
+typedef struct {
+    uint32_t mode;
+    uint64_t seed;
+    float scale_lo, scale_hi, offset_lo, offset_hi;
+    const uint8_t* d_video;
+    uint32_t n_frames;
+    float alpha;
+    const uint32_t* d_env_offset;
+} pxr_distractor_desc;
+
+/* Build a scene on the current HIP device: validate, tessellate, derive the
+ * camera constants, upload (one allocation, one synchronous copy).  Host only,
+ * not on the hot path.
+ * Errors: INVALID_ARG (null pointer, root_body out of range, unknown body
+ * type, non-finite or non-positive parameter, degenerate camera);
+ * UNSUPPORTED (width or height outside [8,128], n_bodies outside [1,64], more
+ * than 65535 vertices or triangles, tessellation counts outside [3,64]x[1,32]
+ * (box [1,16]), or a frame that does not fit the 160 KB of LDS of one
+ * compute unit); OOM; DEVICE. */
+int pxr_create_scene(const pxr_scene_desc* desc, pxr_scene** out);
+
+/* Free the scene and its device constants.  The caller must have synchronised
+ * every stream that still renders from it.  NULL is accepted. */
+int pxr_destroy_scene(pxr_scene* s);
+
+/* Bind (or with d == NULL / mode NONE, unbind) the distractor that later
+ * pxr_render_batch calls fuse into their final per-pixel pass (paper section
+ * 2: distractors live inside the renderer).  Host only; launches nothing.
+ * Errors: INVALID_ARG (unknown mode, non-finite range, VIDEO with null
+ * d_video or n_frames == 0 or alpha outside [0,1]). */
+int pxr_apply_distractor(pxr_scene* s, const pxr_distractor_desc* d);
+
+/* Render B environments x S steps = B*S frames (the hot path; paper section 1:
+ * one pixel observation per parallel environment per step, on the device).
+ *   d_poses  [B,S,K,7] fp32: position xyz, unit quaternion wxyz (body -> world)
+ *   d_shapes [B,K,4]   fp32 per-environment shapes, or NULL = the scene's
+ *   step0    step index of s = 0 (frame s of the call is step step0 + s; it
+ *            keys the generator and selects the video frame)
+ *   env0     global index of the batch's first environment (keys the generator,
+ *            so a shard renders the same bytes as the whole batch would)
+ *   d_frames [B,S,H,W,3] uint8, R,G,B, row-major, written completely
+ *   d_ids    [B,S,H,W] uint32 winning triangle id / PXR_ID_GROUND / PXR_ID_BG,
+ *            or NULL
+ *   hip_stream  hipStream_t to enqueue on; NULL = the default stream
+ * Only enqueues and returns: no synchronisation, no host<->device copy, no
+ * allocation.  Pose VALUES are not validated: a vertex behind the near plane,
+ * far outside the image or non-finite removes its triangles from the frame.
+ * Alignment: d_poses, d_shapes, d_frames 4 bytes, d_ids 16 bytes.
+ * Errors: INVALID_ARG (null scene/poses/frames, B*S == 0, B*S > 2^31-1,
+ * step0 + S or env0 + B overflow, misaligned buffer); DEVICE (launch failure). */
+int pxr_render_batch(pxr_scene* s, const float* d_poses, const float* d_shapes, uint32_t B, uint32_t S,
+                     uint32_t step0, uint32_t env0, uint8_t* d_frames, uint32_t* d_ids, void* hip_stream);
+
+/* Scene facts for callers and tests: total template vertices and triangles,
+ * dynamic LDS bytes per frame workgroup, threads per workgroup.  Any out
+ * pointer may be NULL. */
+int pxr_scene_info(const pxr_scene* s, uint32_t* n_verts, uint32_t* n_tris, uint32_t* lds_bytes,
+                   uint32_t* block_threads);
+
+/* Override the threads per frame workgroup (256, 512 or 1024); 0 restores the
+ * default.  A tuning knob for benchmarks; output does not depend on it. */
+int pxr_set_block_threads(pxr_scene* s, uint32_t threads);
+
+/* Host-only introspection: run the scene builder of pxr_create_scene without
+ * touching a device and copy out its tables, so that the tessellation and the
+ * camera constants can be checked on a machine without a GPU.  Any output
+ * pointer may be NULL.  Same validation errors as pxr_create_scene.
+ *   vtmpl     [V*4] ux,uy,uz and a word holding body<<2 | (s+1)
+ *   tri_idx   [T*2] v0 | v1<<16 ,  v2 | body<<16
+ *   tri_shade [T*4] unit normal in the body frame, colour multiplier
+ *   cxcy      [W+H] ray slopes of the pixel-centre columns, then rows
+ *   consts    [16]  right[3], up[3], forward[3], focal, ground shade[2], light[3], LDS bytes */
+int pxr_host_tables(const pxr_scene_desc* desc, uint32_t* n_verts, uint32_t* n_tris, float* vtmpl, uint32_t* tri_idx,
+                    float* tri_shade, float* cxcy, float* consts);
+
+/* Reason for the last failure on this thread; valid until the next call on it. */
+const char* pxr_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

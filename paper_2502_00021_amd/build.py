@@ -1,0 +1,41 @@
+"""Compile libpxr.so (the C-ABI HIP library) for gfx950 with hipcc, in-tree."""
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libpxr.so")
+SOURCES = ["api.cpp", "scene.cpp", "render.hip"]
+
+# -ffp-contract=off: the order and fusion of fp32 operations is part of the
+# output contract (coverage is decided by integers derived from these floats),
+# so fusions are written out as fmaf and the compiler must not add its own.
+# packed-fp32-ops is switched off for the device pass (see the platform notes).
+HIPFLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
+            "-fno-fast-math", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+            "-Wall", "-Wextra", "-Wno-unused-parameter", "-x", "hip"]
+
+
+def stale():
+    if not os.path.exists(LIB):
+        return True
+    t = os.path.getmtime(LIB)
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(ROOT, "include", "pxr.h")]
+    return any(os.path.getmtime(d) > t for d in deps)
+
+
+def build(force=True, verbose=False, extra=()):
+    if not force and not stale():
+        return LIB
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, *HIPFLAGS, *extra, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+           *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.check_call(cmd)
+    return LIB
+
+
+if __name__ == "__main__":
+    build(verbose=True)

@@ -1,0 +1,217 @@
+// C ABI of libpxr (declared in include/pxr.h): argument checking, scene
+// lifetime, distractor binding and the launch of the render kernel.
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "pxr_internal.h"
+
+struct pxr_scene {
+    pxr::SceneConsts sc{};
+    pxr::DistractConsts dc{};
+    void* d_arena = nullptr;
+    int device = 0;
+    uint32_t block_threads = 0;
+    uint32_t default_threads = 0;
+};
+
+namespace {
+
+thread_local std::string g_last_error;
+
+int fail(int code, const std::string& msg) {
+    g_last_error = msg;
+    return code;
+}
+
+uint32_t pick_block_threads(const pxr::SceneConsts& sc) {
+    // As many waves per compute unit as the 160 KB of LDS allow: with few
+    // resident workgroups each one has to bring its own latency hiding.
+    const uint32_t groups_per_cu = (160u * 1024u) / (sc.lds_total ? sc.lds_total : 1u);
+    if (groups_per_cu >= 4) return 256;
+    if (groups_per_cu >= 2) return 512;
+    return 1024;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* pxr_last_error(void) { return g_last_error.c_str(); }
+
+int pxr_create_scene(const pxr_scene_desc* desc, pxr_scene** out) {
+    if (!desc || !out) return fail(PXR_ERR_INVALID_ARG, "pxr_create_scene: null argument");
+    pxr::HostScene hs;
+    std::string err;
+    int rc = pxr::build_host_scene(*desc, hs, err);
+    if (rc != PXR_OK) return fail(rc, "pxr_create_scene: " + err);
+
+    pxr_scene* s = new (std::nothrow) pxr_scene();
+    if (!s) return fail(PXR_ERR_OOM, "pxr_create_scene: host allocation failed");
+    s->sc = hs.c;
+    if (hipGetDevice(&s->device) != hipSuccess) {
+        delete s;
+        return fail(PXR_ERR_DEVICE, "pxr_create_scene: no HIP device");
+    }
+
+    // one arena, 256-byte aligned sub-tables, one synchronous upload
+    struct Part {
+        const void* src;
+        size_t bytes;
+        size_t off;
+    };
+    Part parts[5] = {{hs.vtmpl.data(), hs.vtmpl.size() * 4, 0},
+                     {hs.tri_idx.data(), hs.tri_idx.size() * 4, 0},
+                     {hs.tri_shade.data(), hs.tri_shade.size() * 4, 0},
+                     {hs.body_const.data(), hs.body_const.size() * 4, 0},
+                     {hs.cxcy.data(), hs.cxcy.size() * 4, 0}};
+    size_t total = 0;
+    for (Part& p : parts) {
+        p.off = total;
+        total += (p.bytes + 255) / 256 * 256;
+    }
+    std::vector<unsigned char> staging(total, 0);
+    for (const Part& p : parts) std::memcpy(staging.data() + p.off, p.src, p.bytes);
+    hipError_t hrc = hipMalloc(&s->d_arena, total);
+    if (hrc != hipSuccess) {
+        delete s;
+        return fail(hrc == hipErrorOutOfMemory ? PXR_ERR_OOM : PXR_ERR_DEVICE,
+                    std::string("pxr_create_scene: hipMalloc failed: ") + hipGetErrorString(hrc));
+    }
+    hrc = hipMemcpy(s->d_arena, staging.data(), total, hipMemcpyHostToDevice);
+    if (hrc != hipSuccess) {
+        (void)hipFree(s->d_arena);
+        delete s;
+        return fail(PXR_ERR_DEVICE, std::string("pxr_create_scene: upload failed: ") + hipGetErrorString(hrc));
+    }
+    const unsigned char* base = static_cast<const unsigned char*>(s->d_arena);
+    s->sc.vtmpl = reinterpret_cast<const float*>(base + parts[0].off);
+    s->sc.tri_idx = reinterpret_cast<const uint32_t*>(base + parts[1].off);
+    s->sc.tri_shade = reinterpret_cast<const float*>(base + parts[2].off);
+    s->sc.body_const = reinterpret_cast<const float*>(base + parts[3].off);
+    s->sc.cxcy = reinterpret_cast<const float*>(base + parts[4].off);
+
+    rc = pxr::prepare_kernels(s->sc.lds_total, err);
+    if (rc != PXR_OK) {
+        (void)hipFree(s->d_arena);
+        delete s;
+        return fail(rc, "pxr_create_scene: " + err);
+    }
+    s->default_threads = s->block_threads = pick_block_threads(s->sc);
+    s->dc.mode = PXR_DISTRACT_NONE;
+    *out = s;
+    return PXR_OK;
+}
+
+int pxr_destroy_scene(pxr_scene* s) {
+    if (!s) return PXR_OK;
+    const hipError_t hrc = hipFree(s->d_arena);
+    delete s;
+    if (hrc != hipSuccess) return fail(PXR_ERR_DEVICE, std::string("pxr_destroy_scene: hipFree failed: ") + hipGetErrorString(hrc));
+    return PXR_OK;
+}
+
+int pxr_apply_distractor(pxr_scene* s, const pxr_distractor_desc* d) {
+    if (!s) return fail(PXR_ERR_INVALID_ARG, "pxr_apply_distractor: null scene");
+    pxr::DistractConsts dc{};
+    dc.mode = PXR_DISTRACT_NONE;
+    if (d && d->mode != PXR_DISTRACT_NONE) {
+        dc.seed_lo = (uint32_t)d->seed;
+        dc.seed_hi = (uint32_t)(d->seed >> 32);
+        if (d->mode == PXR_DISTRACT_COLOR) {
+            if (!std::isfinite(d->scale_lo) || !std::isfinite(d->scale_hi) || !std::isfinite(d->offset_lo) ||
+                !std::isfinite(d->offset_hi))
+                return fail(PXR_ERR_INVALID_ARG, "pxr_apply_distractor: non-finite colour range");
+            dc.mode = PXR_DISTRACT_COLOR;
+            dc.scale_lo = d->scale_lo;
+            dc.scale_span = d->scale_hi - d->scale_lo;
+            dc.offset_lo = d->offset_lo;
+            dc.offset_span = d->offset_hi - d->offset_lo;
+        } else if (d->mode == PXR_DISTRACT_VIDEO) {
+            if (!d->d_video || d->n_frames == 0)
+                return fail(PXR_ERR_INVALID_ARG, "pxr_apply_distractor: video mode needs d_video and n_frames > 0");
+            if (!(d->alpha >= 0.0f && d->alpha <= 1.0f))
+                return fail(PXR_ERR_INVALID_ARG, "pxr_apply_distractor: alpha must lie in [0,1]");
+            if ((reinterpret_cast<uintptr_t>(d->d_video) & 3u) || (reinterpret_cast<uintptr_t>(d->d_env_offset) & 3u))
+                return fail(PXR_ERR_INVALID_ARG, "pxr_apply_distractor: d_video and d_env_offset must be 4-byte aligned");
+            dc.mode = PXR_DISTRACT_VIDEO;
+            dc.video = d->d_video;
+            dc.n_frames = d->n_frames;
+            dc.alpha = d->alpha;
+            dc.env_offset = d->d_env_offset;
+        } else {
+            return fail(PXR_ERR_INVALID_ARG, "pxr_apply_distractor: unknown mode");
+        }
+    }
+    s->dc = dc;
+    return PXR_OK;
+}
+
+int pxr_render_batch(pxr_scene* s, const float* d_poses, const float* d_shapes, uint32_t B, uint32_t S, uint32_t step0,
+                     uint32_t env0, uint8_t* d_frames, uint32_t* d_ids, void* hip_stream) {
+    if (!s || !d_poses || !d_frames) return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch: null scene, poses or frames");
+    if (B == 0 || S == 0) return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch: B and S must be positive");
+    const uint64_t n_frames = (uint64_t)B * (uint64_t)S;
+    if (n_frames > 0x7FFFFFFFull) return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch: B*S exceeds 2^31-1 frames");
+    if ((uint64_t)step0 + S > 0x100000000ull) return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch: step0 + S overflows 32 bits");
+    if ((uint64_t)env0 + B > 0x100000000ull) return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch: env0 + B overflows 32 bits");
+    if ((reinterpret_cast<uintptr_t>(d_poses) & 3u) || (reinterpret_cast<uintptr_t>(d_shapes) & 3u) ||
+        (reinterpret_cast<uintptr_t>(d_frames) & 3u) || (reinterpret_cast<uintptr_t>(d_ids) & 15u))
+        return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch: poses/shapes/frames must be 4-byte and ids 16-byte aligned");
+    std::string err;
+    const int rc = pxr::launch_render(s->sc, s->dc, d_poses, d_shapes, (uint32_t)n_frames, S, step0, env0, d_frames, d_ids,
+                                      s->block_threads, hip_stream, err);
+    if (rc != PXR_OK) return fail(rc, "pxr_render_batch: " + err);
+    return PXR_OK;
+}
+
+int pxr_scene_info(const pxr_scene* s, uint32_t* n_verts, uint32_t* n_tris, uint32_t* lds_bytes, uint32_t* block_threads) {
+    if (!s) return fail(PXR_ERR_INVALID_ARG, "pxr_scene_info: null scene");
+    if (n_verts) *n_verts = s->sc.V;
+    if (n_tris) *n_tris = s->sc.T;
+    if (lds_bytes) *lds_bytes = s->sc.lds_total;
+    if (block_threads) *block_threads = s->block_threads;
+    return PXR_OK;
+}
+
+int pxr_host_tables(const pxr_scene_desc* desc, uint32_t* n_verts, uint32_t* n_tris, float* vtmpl, uint32_t* tri_idx,
+                    float* tri_shade, float* cxcy, float* consts) {
+    if (!desc) return fail(PXR_ERR_INVALID_ARG, "pxr_host_tables: null desc");
+    pxr::HostScene hs;
+    std::string err;
+    const int rc = pxr::build_host_scene(*desc, hs, err);
+    if (rc != PXR_OK) return fail(rc, "pxr_host_tables: " + err);
+    if (n_verts) *n_verts = hs.c.V;
+    if (n_tris) *n_tris = hs.c.T;
+    if (vtmpl) std::memcpy(vtmpl, hs.vtmpl.data(), hs.vtmpl.size() * 4);
+    if (tri_idx) std::memcpy(tri_idx, hs.tri_idx.data(), hs.tri_idx.size() * 4);
+    if (tri_shade) std::memcpy(tri_shade, hs.tri_shade.data(), hs.tri_shade.size() * 4);
+    if (cxcy) std::memcpy(cxcy, hs.cxcy.data(), hs.cxcy.size() * 4);
+    if (consts) {
+        for (int i = 0; i < 3; ++i) {
+            consts[i] = hs.c.Rt[i];
+            consts[3 + i] = hs.c.Up[i];
+            consts[6 + i] = hs.c.Fw[i];
+            consts[12 + i] = hs.c.l[i];
+        }
+        consts[9] = hs.c.f;
+        consts[10] = hs.c.gs[0];
+        consts[11] = hs.c.gs[1];
+        consts[15] = (float)hs.c.lds_total;
+    }
+    return PXR_OK;
+}
+
+int pxr_set_block_threads(pxr_scene* s, uint32_t threads) {
+    if (!s) return fail(PXR_ERR_INVALID_ARG, "pxr_set_block_threads: null scene");
+    if (threads == 0) threads = s->default_threads;
+    if (threads != 256 && threads != 512 && threads != 1024)
+        return fail(PXR_ERR_INVALID_ARG, "pxr_set_block_threads: must be 256, 512 or 1024");
+    s->block_threads = threads;
+    return PXR_OK;
+}
+
+}  // extern "C"

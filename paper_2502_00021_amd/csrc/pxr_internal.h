@@ -1,0 +1,90 @@
+// Internal layout shared by the host-side scene builder and the HIP kernels of
+// libpxr.  Nothing here is visible through the C ABI (include/pxr.h).
+#ifndef PXR_INTERNAL_H
+#define PXR_INTERNAL_H
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "pxr.h"
+
+namespace pxr {
+
+// Sentinel stored in the snapped-X array for a vertex that failed the
+// near-plane / guard-band test; any triangle touching it is dropped.
+constexpr int32_t kRejectedX = INT32_MIN;
+
+// A surviving triangle whose clamped pixel range holds at most this many
+// pixel centres (and whose fixed-point extent is below 2^15) is rasterised by
+// one lane; anything bigger is spread over a whole wavefront.
+constexpr uint32_t kSmallMaxPixels = 16;
+
+// Per-body record kept in LDS for the duration of one frame (floats).
+//   [0..8]  M  = view rotation * body rotation, row-major
+//   [9..11] t  = body origin in view space
+//   [12..14] lb = light direction in the body frame
+//   [15]    pad
+//   [16..19] shape (a,b,c,h)
+//   [20..22] rgb, [23] pad
+constexpr uint32_t kBodyStride = 24;
+
+// Everything the kernel needs that is constant for a scene.  Passed by value
+// as the kernel argument (lands in SGPRs / scalar loads).
+struct SceneConsts {
+    // camera rows (right, up, forward), eye offset, focal length in pixels
+    float Rt[3], Up[3], Fw[3], off[3];
+    float f, halfW, halfH, z_near, z_far;
+    // light, ground, background
+    float l[3], ambient, diffuse;
+    float cell, gs[2], bg[3];
+    uint32_t ground_on, cell_is_one;
+    // sizes
+    uint32_t W, H, npix, K, root, V, T;
+    uint32_t magicW;  // ceil(2^32 / W): p / W == mulhi(p, magicW) for p < 2^14 * 2^7
+    // device tables
+    const float* vtmpl;       // [V][4]  ux,uy,uz, bits = body<<2 | (s+1)
+    const uint32_t* tri_idx;  // [T][2]  v0 | v1<<16 ,  v2 | body<<16
+    const float* tri_shade;   // [T][4]  unit normal (body frame), colour multiplier
+    const float* body_const;  // [K][8]  shape a,b,c,h ; rgb r,g,b,0
+    const float* cxcy;        // [W+H]   pixel-centre ray slopes
+    // LDS carve-up (byte offsets into the dynamic segment)
+    uint32_t lds_keys, lds_vx, lds_vy, lds_vd, lds_body, lds_list, lds_cxcy, lds_misc, lds_total;
+};
+
+// Distractor state bound by pxr_apply_distractor.
+struct DistractConsts {
+    uint32_t mode;
+    uint32_t seed_lo, seed_hi;
+    float scale_lo, scale_span, offset_lo, offset_span;
+    const uint8_t* video;
+    uint32_t n_frames;
+    float alpha;
+    const uint32_t* env_offset;
+};
+
+// Host-side result of tessellation + camera derivation.
+struct HostScene {
+    SceneConsts c{};
+    std::vector<float> vtmpl;
+    std::vector<uint32_t> tri_idx;
+    std::vector<float> tri_shade;
+    std::vector<float> body_const;
+    std::vector<float> cxcy;
+};
+
+// scene.cpp: validates `desc`, fills `hs` (device pointers and LDS offsets are
+// left for the caller).  Returns a PXR_* code and a message on failure.
+int build_host_scene(const pxr_scene_desc& desc, HostScene& hs, std::string& err);
+
+// render.hip: enqueue one batch.  `block_threads` in {256,512,1024}.
+int launch_render(const SceneConsts& sc, const DistractConsts& dc, const float* d_poses, const float* d_shapes,
+                  uint32_t n_frames, uint32_t S, uint32_t step0, uint32_t env0, uint8_t* d_frames, uint32_t* d_ids,
+                  uint32_t block_threads, void* stream, std::string& err);
+
+// render.hip: raise the dynamic-LDS limit of every kernel instantiation once.
+int prepare_kernels(uint32_t lds_bytes, std::string& err);
+
+}  // namespace pxr
+
+#endif

@@ -1,0 +1,339 @@
+// Host-side scene builder of libpxr: validation, tessellation of the unit
+// primitives, camera / light / ground constants.  Runs once per scene, never
+// on the hot path.  (The paper leaves geometry, camera and shading
+// conventions open; the conventions here are this library's definition of a
+// "scene of posed primitives" and are documented with the C ABI.)
+//
+// Numerical contract: every table is evaluated in double from the float
+// inputs with libm, each entry rounded to fp32 exactly once.
+
+#include <cmath>
+#include <cstring>
+
+#include "pxr_internal.h"
+
+namespace pxr {
+namespace {
+
+constexpr double kPi = 3.14159265358979323846;
+
+struct Vec3d {
+    double x, y, z;
+};
+
+inline Vec3d sub(const Vec3d& a, const Vec3d& b) { return {a.x - b.x, a.y - b.y, a.z - b.z}; }
+inline Vec3d cross(const Vec3d& a, const Vec3d& b) {
+    return {a.y * b.z - a.z * b.y, a.z * b.x - a.x * b.z, a.x * b.y - a.y * b.x};
+}
+inline double norm(const Vec3d& a) { return std::sqrt(a.x * a.x + a.y * a.y + a.z * a.z); }
+
+inline float as_float(uint32_t u) {
+    float f;
+    std::memcpy(&f, &u, 4);
+    return f;
+}
+
+// Collects one body's mesh in body-local numbering; flushed into the scene
+// tables with the body's vertex base added.
+struct BodyMesh {
+    std::vector<Vec3d> pos;     // unit-shape positions (double)
+    std::vector<int> cap;       // cap selector s in {+1,0,-1}
+    std::vector<uint32_t> idx;  // 3 per triangle, local
+    std::vector<Vec3d> nrm;     // per triangle
+    std::vector<float> mul;     // per triangle
+
+    void tri(uint32_t a, uint32_t b, uint32_t c, const Vec3d& n, float m = 1.0f) {
+        idx.push_back(a);
+        idx.push_back(b);
+        idx.push_back(c);
+        nrm.push_back(n);
+        mul.push_back(m);
+    }
+    Vec3d face_normal(uint32_t a, uint32_t b, uint32_t c) const {
+        Vec3d n = cross(sub(pos[b], pos[a]), sub(pos[c], pos[a]));
+        double len = norm(n);
+        return {n.x / len, n.y / len, n.z / len};
+    }
+};
+
+// Latitude rings of a capsule or sphere, top to bottom.
+struct RingSpec {
+    double theta;
+    bool equator;  // sin = 1, cos = 0 exactly
+    int cap;
+};
+
+// Capsule: poles + 2*M rings (the two equators coincide on the unit sphere and
+// are pulled apart by the cap selector).  Sphere: poles + 2*M-1 rings.
+void tessellate_round(BodyMesh& m, uint32_t L, uint32_t M, bool capsule) {
+    std::vector<RingSpec> rings;
+    if (capsule) {
+        for (uint32_t k = 1; k <= M; ++k) rings.push_back({((double)k * (kPi / 2.0)) / (double)M, k == M, +1});
+        for (uint32_t k = 0; k < M; ++k) rings.push_back({kPi / 2.0 + ((double)k * (kPi / 2.0)) / (double)M, k == 0, -1});
+    } else {
+        for (uint32_t k = 1; k < 2 * M; ++k) rings.push_back({((double)k * kPi) / (double)(2 * M), k == M, 0});
+    }
+    const uint32_t R = (uint32_t)rings.size();
+    const uint32_t n_verts = R * L + 2;
+    m.pos.resize(n_verts);
+    m.cap.resize(n_verts);
+    m.pos[0] = {0.0, 0.0, 1.0};
+    m.cap[0] = capsule ? +1 : 0;
+    m.pos[n_verts - 1] = {0.0, 0.0, -1.0};
+    m.cap[n_verts - 1] = capsule ? -1 : 0;
+    for (uint32_t r = 0; r < R; ++r) {
+        const double s = rings[r].equator ? 1.0 : std::sin(rings[r].theta);
+        const double c = rings[r].equator ? 0.0 : std::cos(rings[r].theta);
+        for (uint32_t j = 0; j < L; ++j) {
+            const double phi = ((2.0 * kPi) * (double)j) / (double)L;
+            m.pos[1 + r * L + j] = {s * std::cos(phi), s * std::sin(phi), c};
+            m.cap[1 + r * L + j] = rings[r].cap;
+        }
+    }
+    auto at = [L](uint32_t r, uint32_t j) { return 1 + r * L + (j == L ? 0 : j); };
+    // top fan
+    for (uint32_t j = 0; j < L; ++j) m.tri(0, at(0, j), at(0, j + 1), m.face_normal(0, at(0, j), at(0, j + 1)));
+    // bands between consecutive rings: upper-left, lower-left, lower-right / upper-left, lower-right, upper-right
+    for (uint32_t r = 0; r + 1 < R; ++r) {
+        const bool cylinder = capsule && rings[r].cap != rings[r + 1].cap;
+        for (uint32_t j = 0; j < L; ++j) {
+            const uint32_t ul = at(r, j), ur = at(r, j + 1), ll = at(r + 1, j), lr = at(r + 1, j + 1);
+            if (cylinder) {
+                const double phi = ((2.0 * kPi) * ((double)j + 0.5)) / (double)L;
+                const Vec3d n{std::cos(phi), std::sin(phi), 0.0};
+                m.tri(ul, ll, lr, n);
+                m.tri(ul, lr, ur, n);
+            } else {
+                m.tri(ul, ll, lr, m.face_normal(ul, ll, lr));
+                m.tri(ul, lr, ur, m.face_normal(ul, lr, ur));
+            }
+        }
+    }
+    // bottom fan
+    const uint32_t south = n_verts - 1;
+    for (uint32_t j = 0; j < L; ++j)
+        m.tri(at(R - 1, j), south, at(R - 1, j + 1), m.face_normal(at(R - 1, j), south, at(R - 1, j + 1)));
+}
+
+// Box faces +x,-x,+y,-y,+z,-z with (u,v) axes such that u x v = outward normal.
+void tessellate_box(BodyMesh& m, uint32_t n) {
+    struct Face {
+        int axis;
+        double sign;
+        int u, v;
+    };
+    const Face faces[6] = {{0, +1.0, 1, 2}, {0, -1.0, 2, 1}, {1, +1.0, 2, 0}, {1, -1.0, 0, 2}, {2, +1.0, 0, 1}, {2, -1.0, 1, 0}};
+    const uint32_t side = n + 1;
+    for (int f = 0; f < 6; ++f) {
+        const uint32_t base = (uint32_t)m.pos.size();
+        for (uint32_t iv = 0; iv < side; ++iv)
+            for (uint32_t iu = 0; iu < side; ++iu) {
+                double p[3];
+                p[faces[f].axis] = faces[f].sign;
+                p[faces[f].u] = -1.0 + (2.0 * (double)iu) / (double)n;
+                p[faces[f].v] = -1.0 + (2.0 * (double)iv) / (double)n;
+                m.pos.push_back({p[0], p[1], p[2]});
+                m.cap.push_back(0);
+            }
+        double nn[3] = {0.0, 0.0, 0.0};
+        nn[faces[f].axis] = faces[f].sign;
+        const Vec3d normal{nn[0], nn[1], nn[2]};
+        for (uint32_t cv = 0; cv < n; ++cv)
+            for (uint32_t cu = 0; cu < n; ++cu) {
+                const uint32_t p00 = base + cv * side + cu;
+                const uint32_t p10 = p00 + 1, p01 = p00 + side, p11 = p01 + 1;
+                const float checker = ((cu ^ cv) & 1u) ? 0.5f : 1.0f;
+                m.tri(p00, p10, p11, normal, checker);
+                m.tri(p00, p11, p01, normal, checker);
+            }
+    }
+}
+
+bool finite_all(const float* p, int n) {
+    for (int i = 0; i < n; ++i)
+        if (!std::isfinite(p[i])) return false;
+    return true;
+}
+
+}  // namespace
+
+int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
+    SceneConsts& c = hs.c;
+    if (d.width < 8 || d.width > 128 || d.height < 8 || d.height > 128) {
+        err = "width and height must lie in [8,128]";
+        return PXR_ERR_UNSUPPORTED;
+    }
+    if (d.n_bodies < 1 || d.n_bodies > 64) {
+        err = "n_bodies must lie in [1,64]";
+        return PXR_ERR_UNSUPPORTED;
+    }
+    if (!d.bodies) {
+        err = "bodies is null";
+        return PXR_ERR_INVALID_ARG;
+    }
+    if (d.root_body >= d.n_bodies) {
+        err = "root_body out of range";
+        return PXR_ERR_INVALID_ARG;
+    }
+    if (!std::isfinite(d.fov_y_deg) || !(d.fov_y_deg > 0.0f) || !(d.fov_y_deg < 180.0f) || !finite_all(d.cam_offset, 3) ||
+        !finite_all(d.cam_up, 3) || !std::isfinite(d.z_near) || !std::isfinite(d.z_far) || !(d.z_near > 0.0f) ||
+        !(d.z_far > d.z_near)) {
+        err = "camera parameters must be finite with 0 < fov < 180 and 0 < z_near < z_far";
+        return PXR_ERR_INVALID_ARG;
+    }
+    if (!finite_all(d.light_dir, 3) || !std::isfinite(d.ambient) || !std::isfinite(d.diffuse) || d.ambient < 0.0f ||
+        d.diffuse < 0.0f) {
+        err = "light parameters must be finite and non-negative";
+        return PXR_ERR_INVALID_ARG;
+    }
+    if (!std::isfinite(d.ground_cell) || !(d.ground_cell > 0.0f) || !finite_all(d.ground_grey, 2) ||
+        !finite_all(d.background_rgb, 3)) {
+        err = "ground / background parameters must be finite, ground_cell > 0";
+        return PXR_ERR_INVALID_ARG;
+    }
+
+    c.W = d.width;
+    c.H = d.height;
+    c.npix = d.width * d.height;
+    c.K = d.n_bodies;
+    c.root = d.root_body;
+    c.magicW = (uint32_t)((0x100000000ull + d.width - 1) / d.width);
+
+    // ---- meshes
+    uint32_t vbase = 0, tbase = 0;
+    hs.body_const.assign((size_t)d.n_bodies * 8, 0.0f);
+    for (uint32_t b = 0; b < d.n_bodies; ++b) {
+        const pxr_body_desc& bd = d.bodies[b];
+        if (!finite_all(bd.shape, 4) || !finite_all(bd.rgb, 3)) {
+            err = "body " + std::to_string(b) + ": non-finite shape or colour";
+            return PXR_ERR_INVALID_ARG;
+        }
+        BodyMesh m;
+        if (bd.type == PXR_CAPSULE || bd.type == PXR_SPHERE) {
+            if (bd.n_lon < 3 || bd.n_lon > 64 || bd.n_lat < 1 || bd.n_lat > 32) {
+                err = "body " + std::to_string(b) + ": n_lon must lie in [3,64] and n_lat in [1,32]";
+                return PXR_ERR_UNSUPPORTED;
+            }
+            tessellate_round(m, bd.n_lon, bd.n_lat, bd.type == PXR_CAPSULE);
+        } else if (bd.type == PXR_BOX) {
+            if (bd.n_lon < 1 || bd.n_lon > 16) {
+                err = "body " + std::to_string(b) + ": box cells per edge must lie in [1,16]";
+                return PXR_ERR_UNSUPPORTED;
+            }
+            tessellate_box(m, bd.n_lon);
+        } else {
+            err = "body " + std::to_string(b) + ": unknown primitive type";
+            return PXR_ERR_INVALID_ARG;
+        }
+        const uint32_t nv = (uint32_t)m.pos.size(), nt = (uint32_t)m.mul.size();
+        if (vbase + nv > 65535u || tbase + nt > 65535u) {
+            err = "scene exceeds 65535 vertices or triangles";
+            return PXR_ERR_UNSUPPORTED;
+        }
+        for (uint32_t v = 0; v < nv; ++v) {
+            hs.vtmpl.push_back((float)m.pos[v].x);
+            hs.vtmpl.push_back((float)m.pos[v].y);
+            hs.vtmpl.push_back((float)m.pos[v].z);
+            hs.vtmpl.push_back(as_float((b << 2) | (uint32_t)(m.cap[v] + 1)));
+        }
+        for (uint32_t t = 0; t < nt; ++t) {
+            const uint32_t v0 = vbase + m.idx[3 * t], v1 = vbase + m.idx[3 * t + 1], v2 = vbase + m.idx[3 * t + 2];
+            hs.tri_idx.push_back(v0 | (v1 << 16));
+            hs.tri_idx.push_back(v2 | (b << 16));
+            hs.tri_shade.push_back((float)m.nrm[t].x);
+            hs.tri_shade.push_back((float)m.nrm[t].y);
+            hs.tri_shade.push_back((float)m.nrm[t].z);
+            hs.tri_shade.push_back(m.mul[t]);
+        }
+        for (int i = 0; i < 4; ++i) hs.body_const[(size_t)b * 8 + i] = bd.shape[i];
+        for (int i = 0; i < 3; ++i) hs.body_const[(size_t)b * 8 + 4 + i] = bd.rgb[i];
+        vbase += nv;
+        tbase += nt;
+    }
+    c.V = vbase;
+    c.T = tbase;
+
+    // ---- camera: forward looks from the eye to the root, right = forward x up
+    const Vec3d off{d.cam_offset[0], d.cam_offset[1], d.cam_offset[2]};
+    const Vec3d up{d.cam_up[0], d.cam_up[1], d.cam_up[2]};
+    const double off_len = norm(off);
+    if (!(off_len > 0.0)) {
+        err = "cam_offset must be non-zero";
+        return PXR_ERR_INVALID_ARG;
+    }
+    const Vec3d fw{-off.x / off_len, -off.y / off_len, -off.z / off_len};
+    Vec3d rt = cross(fw, up);
+    const double rt_len = norm(rt);
+    if (!(rt_len > 1e-6 * norm(up))) {
+        err = "cam_up is zero or parallel to the viewing direction";
+        return PXR_ERR_INVALID_ARG;
+    }
+    rt = {rt.x / rt_len, rt.y / rt_len, rt.z / rt_len};
+    const Vec3d upv = cross(rt, fw);
+    const double rtv[3] = {rt.x, rt.y, rt.z}, upa[3] = {upv.x, upv.y, upv.z}, fwa[3] = {fw.x, fw.y, fw.z};
+    for (int i = 0; i < 3; ++i) {
+        c.Rt[i] = (float)rtv[i];
+        c.Up[i] = (float)upa[i];
+        c.Fw[i] = (float)fwa[i];
+        c.off[i] = d.cam_offset[i];
+    }
+    const double half_w = (double)d.width / 2.0, half_h = (double)d.height / 2.0;
+    const double focal = half_h / std::tan(((double)d.fov_y_deg * kPi / 180.0) / 2.0);
+    c.f = (float)focal;
+    c.halfW = (float)half_w;
+    c.halfH = (float)half_h;
+    c.z_near = d.z_near;
+    c.z_far = d.z_far;
+    hs.cxcy.resize(d.width + d.height);
+    for (uint32_t i = 0; i < d.width; ++i) hs.cxcy[i] = (float)((((double)i + 0.5) - half_w) / focal);
+    for (uint32_t j = 0; j < d.height; ++j) hs.cxcy[d.width + j] = (float)(-(((double)j + 0.5) - half_h) / focal);
+
+    // ---- light, ground, background
+    const Vec3d ld{d.light_dir[0], d.light_dir[1], d.light_dir[2]};
+    const double ld_len = norm(ld);
+    if (!(ld_len > 0.0)) {
+        err = "light_dir must be non-zero";
+        return PXR_ERR_INVALID_ARG;
+    }
+    c.l[0] = (float)(ld.x / ld_len);
+    c.l[1] = (float)(ld.y / ld_len);
+    c.l[2] = (float)(ld.z / ld_len);
+    c.ambient = d.ambient;
+    c.diffuse = d.diffuse;
+    c.ground_on = d.ground_enabled ? 1u : 0u;
+    c.cell = d.ground_cell;
+    c.cell_is_one = d.ground_cell == 1.0f ? 1u : 0u;
+    const double lz = ld.z / ld_len;
+    const double lit = (double)d.ambient + (double)d.diffuse * (lz > 0.0 ? lz : 0.0);
+    c.gs[0] = (float)((double)d.ground_grey[0] * lit);
+    c.gs[1] = (float)((double)d.ground_grey[1] * lit);
+    for (int i = 0; i < 3; ++i) c.bg[i] = d.background_rgb[i];
+
+    // ---- LDS carve-up of one frame workgroup
+    auto align = [](uint32_t x, uint32_t a) { return (x + a - 1) / a * a; };
+    uint32_t o = 0;
+    c.lds_keys = o;
+    o += c.npix * 8;
+    c.lds_vx = o;
+    o += c.V * 4;
+    c.lds_vy = o;
+    o += c.V * 4;
+    c.lds_vd = o;
+    o += c.V * 4;
+    c.lds_body = o;
+    o += c.K * kBodyStride * 4;
+    c.lds_cxcy = o;
+    o += (c.W + c.H) * 4;
+    c.lds_misc = o;
+    o += 32 * 4;
+    c.lds_list = o;
+    o += align(c.T * 2, 8);
+    c.lds_total = align(o, 16);
+    if (c.lds_total > 160u * 1024u) {
+        err = "scene needs " + std::to_string(c.lds_total) + " bytes of LDS per frame; the limit is 163840";
+        return PXR_ERR_UNSUPPORTED;
+    }
+    return PXR_OK;
+}
+
+}  // namespace pxr

@@ -1,0 +1,220 @@
+"""ctypes binding of libpxr.so — argument marshalling only; every step runs in the HIP library.
+
+Mirrors include/pxr.h one to one: create_scene / destroy_scene /
+apply_distractor / render_batch (+ scene_info, set_block_threads,
+host_tables).  PyTorch is used only to hold device memory and name the stream.
+There is no fallback: a missing library or a failing call raises.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpxr.so")
+
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_OOM, ERR_DEVICE = range(5)
+ID_GROUND = 0xFFFFFFFE
+ID_BG = 0xFFFFFFFF
+KINDS = {"capsule": 0, "sphere": 1, "box": 2}
+MODES = {"none": 0, "color": 1, "video": 2}
+
+
+class PxrError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__(f"pxr error {code}: {message}")
+        self.code = code
+
+
+class BodyDesc(C.Structure):
+    _fields_ = [("type", C.c_uint32), ("shape", C.c_float * 4), ("rgb", C.c_float * 3),
+                ("n_lon", C.c_uint32), ("n_lat", C.c_uint32)]
+
+
+class SceneDesc(C.Structure):
+    _fields_ = [("width", C.c_uint32), ("height", C.c_uint32), ("n_bodies", C.c_uint32), ("root_body", C.c_uint32),
+                ("bodies", C.POINTER(BodyDesc)),
+                ("fov_y_deg", C.c_float), ("cam_offset", C.c_float * 3), ("cam_up", C.c_float * 3),
+                ("z_near", C.c_float), ("z_far", C.c_float),
+                ("light_dir", C.c_float * 3), ("ambient", C.c_float), ("diffuse", C.c_float),
+                ("ground_enabled", C.c_uint32), ("ground_cell", C.c_float), ("ground_grey", C.c_float * 2),
+                ("background_rgb", C.c_float * 3)]
+
+
+class DistractorDesc(C.Structure):
+    _fields_ = [("mode", C.c_uint32), ("seed", C.c_uint64),
+                ("scale_lo", C.c_float), ("scale_hi", C.c_float), ("offset_lo", C.c_float), ("offset_hi", C.c_float),
+                ("d_video", C.c_void_p), ("n_frames", C.c_uint32), ("alpha", C.c_float),
+                ("d_env_offset", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """Load libpxr.so (built in-tree by __graft_entry__.build / paper_2502_00021_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` first")
+        L = C.CDLL(LIB_PATH)
+        vp, u32 = C.c_void_p, C.c_uint32
+        L.pxr_create_scene.argtypes = [C.POINTER(SceneDesc), C.POINTER(vp)]
+        L.pxr_destroy_scene.argtypes = [vp]
+        L.pxr_apply_distractor.argtypes = [vp, C.POINTER(DistractorDesc)]
+        L.pxr_render_batch.argtypes = [vp, vp, vp, u32, u32, u32, u32, vp, vp, vp]
+        L.pxr_scene_info.argtypes = [vp, vp, vp, vp, vp]
+        L.pxr_set_block_threads.argtypes = [vp, u32]
+        L.pxr_host_tables.argtypes = [C.POINTER(SceneDesc), vp, vp, vp, vp, vp, vp, vp]
+        L.pxr_last_error.restype = C.c_char_p
+        for name in ("pxr_create_scene", "pxr_destroy_scene", "pxr_apply_distractor", "pxr_render_batch",
+                     "pxr_scene_info", "pxr_set_block_threads", "pxr_host_tables"):
+            getattr(L, name).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != OK:
+        raise PxrError(rc, lib().pxr_last_error().decode())
+
+
+def make_scene_desc(desc):
+    """Plain-dict scene description (see workloads.default_scene) -> (SceneDesc, keep-alive list)."""
+    bodies = desc["bodies"]
+    arr = (BodyDesc * max(1, len(bodies)))()
+    for i, b in enumerate(bodies):
+        arr[i].type = KINDS[b["kind"]] if isinstance(b["kind"], str) else int(b["kind"])
+        arr[i].shape = (C.c_float * 4)(*b["shape"])
+        arr[i].rgb = (C.c_float * 3)(*b["rgb"])
+        arr[i].n_lon = int(b["n_lon"])
+        arr[i].n_lat = int(b.get("n_lat", 0))
+    d = SceneDesc()
+    d.width, d.height = int(desc["width"]), int(desc["height"])
+    d.n_bodies, d.root_body = len(bodies), int(desc["root_body"])
+    d.bodies = C.cast(arr, C.POINTER(BodyDesc))
+    d.fov_y_deg = desc["fov_y_deg"]
+    d.cam_offset = (C.c_float * 3)(*desc["cam_offset"])
+    d.cam_up = (C.c_float * 3)(*desc["cam_up"])
+    d.z_near, d.z_far = desc["z_near"], desc["z_far"]
+    d.light_dir = (C.c_float * 3)(*desc["light_dir"])
+    d.ambient, d.diffuse = desc["ambient"], desc["diffuse"]
+    d.ground_enabled = 1 if desc["ground_enabled"] else 0
+    d.ground_cell = desc["ground_cell"]
+    d.ground_grey = (C.c_float * 2)(*desc["ground_grey"])
+    d.background_rgb = (C.c_float * 3)(*desc["background_rgb"])
+    return d, [arr]
+
+
+def host_tables(desc):
+    """pxr_host_tables: the scene builder's tables as numpy arrays (no device needed)."""
+    d, keep = make_scene_desc(desc)
+    nv, nt = C.c_uint32(), C.c_uint32()
+    _check(lib().pxr_host_tables(C.byref(d), C.byref(nv), C.byref(nt), None, None, None, None, None))
+    V, T = nv.value, nt.value
+    vt = np.empty((V, 4), np.float32)
+    ti = np.empty((T, 2), np.uint32)
+    ts = np.empty((T, 4), np.float32)
+    cxcy = np.empty(d.width + d.height, np.float32)
+    consts = np.empty(16, np.float32)
+    _check(lib().pxr_host_tables(C.byref(d), None, None, vt.ctypes.data, ti.ctypes.data, ts.ctypes.data,
+                                 cxcy.ctypes.data, consts.ctypes.data))
+    del keep
+    code = vt[:, 3].copy().view(np.uint32)
+    return dict(V=V, T=T, uverts=np.concatenate([vt[:, :3], ((code & 3).astype(np.float32) - 1.0)[:, None]], axis=1),
+                vert_body=code >> 2,
+                tris=np.stack([ti[:, 0] & 0xFFFF, ti[:, 0] >> 16, ti[:, 1] & 0xFFFF], axis=1).astype(np.uint32),
+                tri_body=ti[:, 1] >> 16, normals=ts[:, :3].copy(), mul=ts[:, 3].copy(),
+                cx=cxcy[:d.width].copy(), cy=cxcy[d.width:].copy(),
+                Rv=consts[:9].reshape(3, 3).copy(), f=float(consts[9]), gs=consts[10:12].copy(), l=consts[12:15].copy(),
+                lds_bytes=int(consts[15]))
+
+
+class Scene:
+    """Owns one pxr_scene handle.  Tensors passed to render_batch must live on the scene's GPU."""
+
+    def __init__(self, desc):
+        d, keep = make_scene_desc(desc)
+        h = C.c_void_p()
+        _check(lib().pxr_create_scene(C.byref(d), C.byref(h)))
+        del keep
+        self._h = h
+        self.W, self.H, self.K = d.width, d.height, d.n_bodies
+        self._bound = []  # keeps bound distractor tensors alive
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _check(lib().pxr_destroy_scene(self._h))
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def info(self):
+        v, t, l, b = C.c_uint32(), C.c_uint32(), C.c_uint32(), C.c_uint32()
+        _check(lib().pxr_scene_info(self._h, C.byref(v), C.byref(t), C.byref(l), C.byref(b)))
+        return dict(n_verts=v.value, n_tris=t.value, lds_bytes=l.value, block_threads=b.value)
+
+    def set_block_threads(self, n):
+        _check(lib().pxr_set_block_threads(self._h, int(n)))
+
+    def apply_distractor(self, d=None):
+        """d: None / {"mode": "none"} to unbind, or a dict as produced by the workload generators,
+        with `video` / `env_offset` given as CUDA uint8 / int32 tensors."""
+        self._bound = []
+        if d is None or d.get("mode", "none") == "none":
+            _check(lib().pxr_apply_distractor(self._h, None))
+            return
+        s = DistractorDesc()
+        s.mode = MODES[d["mode"]]
+        s.seed = int(d.get("seed", 0))
+        s.scale_lo, s.scale_hi = d.get("scale", (1.0, 1.0))
+        s.offset_lo, s.offset_hi = d.get("offset", (0.0, 0.0))
+        if d["mode"] == "video":
+            v = d["video"]
+            assert v.is_cuda and v.is_contiguous() and v.dtype.itemsize == 1 and tuple(v.shape[1:]) == (self.H, self.W, 3)
+            s.d_video = v.data_ptr()
+            s.n_frames = v.shape[0]
+            s.alpha = float(d.get("alpha", 0.5))
+            self._bound.append(v)
+            eo = d.get("env_offset")
+            if eo is not None:
+                assert eo.is_cuda and eo.is_contiguous() and eo.dtype.itemsize == 4
+                s.d_env_offset = eo.data_ptr()
+                self._bound.append(eo)
+        _check(lib().pxr_apply_distractor(self._h, C.byref(s)))
+
+    def render_batch(self, poses, shapes=None, step0=0, env0=0, frames=None, ids=None, want_ids=False, stream=None):
+        """poses: CUDA float32 [B,S,K,7]; shapes: CUDA float32 [B,K,4] or None.
+        Returns (frames uint8 [B,S,H,W,3], ids int32-typed uint32 bits [B,S,H,W] or None); enqueue only."""
+        import torch
+        assert poses.is_cuda and poses.dtype == torch.float32 and poses.is_contiguous()
+        B, S = int(poses.shape[0]), int(poses.shape[1])
+        assert tuple(poses.shape) == (B, S, self.K, 7), tuple(poses.shape)
+        if shapes is not None:
+            assert shapes.is_cuda and shapes.dtype == torch.float32 and shapes.is_contiguous()
+            assert tuple(shapes.shape) == (B, self.K, 4)
+        if frames is None:
+            frames = torch.empty((B, S, self.H, self.W, 3), dtype=torch.uint8, device=poses.device)
+        else:
+            assert frames.is_cuda and frames.is_contiguous() and frames.dtype == torch.uint8
+            assert tuple(frames.shape) == (B, S, self.H, self.W, 3)
+        if ids is None and want_ids:
+            ids = torch.empty((B, S, self.H, self.W), dtype=torch.int32, device=poses.device)
+        if ids is not None:
+            assert ids.is_cuda and ids.is_contiguous() and ids.dtype == torch.int32
+            assert tuple(ids.shape) == (B, S, self.H, self.W)
+        if stream is None:
+            stream = torch.cuda.current_stream(poses.device).cuda_stream
+        _check(lib().pxr_render_batch(self._h, poses.data_ptr(), None if shapes is None else shapes.data_ptr(),
+                                      B, S, int(step0), int(env0), frames.data_ptr(),
+                                      None if ids is None else ids.data_ptr(), C.c_void_p(stream)))
+        return frames, ids
+
+
+def ids_to_numpy(ids):
+    """int32 CUDA tensor holding uint32 id bits -> numpy uint32."""
+    return ids.cpu().numpy().view(np.uint32)

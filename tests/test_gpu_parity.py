@@ -1,0 +1,301 @@
+"""GPU parity: libpxr (HIP, through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Bar: winning-id maps bit-exact; RGB within 1/255 per channel after uint8 rounding (the same fp32
+operation order is used on both sides, so the expected difference is 0 and is asserted where noted).
+"""
+import numpy as np
+import pytest
+
+from paper_2502_00021_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+BG = 0xFFFFFFFF
+GROUND = 0xFFFFFFFE
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as _torch
+    assert _torch.cuda.is_available(), "these tests need the MI355X"
+    return _torch
+
+
+@pytest.fixture(scope="module")
+def pxr():
+    from paper_2502_00021_amd import pxr as _pxr
+    _pxr.lib()
+    return _pxr
+
+
+def _bind(torch, scene, dis):
+    if dis is None:
+        scene.apply_distractor(None)
+        return
+    d = dict(dis)
+    if d["mode"] == "video":
+        d["video"] = torch.from_numpy(np.ascontiguousarray(d["video"])).cuda()
+        if d.get("env_offset") is not None:
+            d["env_offset"] = torch.from_numpy(np.asarray(d["env_offset"]).astype(np.int32)).cuda()
+    scene.apply_distractor(d)
+
+
+def gpu_render(torch, pxr, w, step0=0, env0=0, threads=None, scene=None):
+    own = scene is None
+    if own:
+        scene = pxr.Scene(w["desc"])
+    if threads:
+        scene.set_block_threads(threads)
+    _bind(torch, scene, w["distractor"])
+    poses = torch.from_numpy(w["poses"]).cuda()
+    shapes = None if w["shapes"] is None else torch.from_numpy(w["shapes"]).cuda()
+    frames, ids = scene.render_batch(poses, shapes, step0=step0, env0=env0, want_ids=True)
+    torch.cuda.synchronize()
+    out = dict(frames=frames.cpu().numpy(), ids=pxr.ids_to_numpy(ids))
+    if own:
+        scene.close()
+    return out
+
+
+def assert_parity(got, ref, exact_rgb=True):
+    assert got["ids"].shape == ref["ids"].shape and got["frames"].shape == ref["frames"].shape
+    bad = np.argwhere(got["ids"] != ref["ids"])
+    assert len(bad) == 0, f"{len(bad)} id mismatches, first at {bad[0]}: gpu {got['ids'][tuple(bad[0])]:#x} oracle {ref['ids'][tuple(bad[0])]:#x}"
+    diff = np.abs(got["frames"].astype(np.int16) - ref["frames"].astype(np.int16))
+    assert diff.max() <= 1, f"RGB differs by {diff.max()} LSB at {np.argwhere(diff > 1)[0]}"
+    if exact_rgb:
+        assert diff.max() == 0, f"{int((diff > 0).sum())} channels differ by 1 LSB"
+
+
+def oracle_render(orc, w, step0=0, env0=0):
+    s = orc.Scene(w["desc"])
+    return s.render(w["poses"], w["shapes"], step0=step0, env0=env0, distractor=w["distractor"])
+
+
+# ---------------------------------------------------------------- the five configurations
+
+@pytest.mark.parametrize("cfg,B,threads", [(1, 16, 256), (1, 16, 1024), (2, 48, 512), (2, 24, 256), (3, 40, 512),
+                                           (3, 24, 1024), (4, 24, 1024), (4, 16, 512), (5, 20, 512), (5, 12, 256)])
+def test_configs_match_oracle(torch, pxr, orc, cfg, B, threads):
+    w = wl.make(cfg, B=B)
+    got = gpu_render(torch, pxr, w, step0=3, env0=11, threads=threads)
+    ref = oracle_render(orc, w, step0=3, env0=11)
+    assert_parity(got, ref)
+    tri = ref["ids"] < GROUND
+    assert tri.any() and (ref["ids"] == GROUND).any() and (ref["ids"] == BG).any()
+
+
+def test_default_block_threads_and_info(torch, pxr, orc):
+    for cfg in (1, 2, 3, 4, 5):
+        w = wl.make(cfg, B=2)
+        sc = pxr.Scene(w["desc"])
+        info = sc.info()
+        o = orc.Scene(w["desc"])
+        assert (info["n_verts"], info["n_tris"]) == (o.V, o.T)
+        assert info["block_threads"] in (256, 512, 1024) and info["lds_bytes"] <= 160 * 1024
+        got = gpu_render(torch, pxr, w, scene=sc)
+        assert_parity(got, oracle_render(orc, w))
+        sc.close()
+
+
+# ---------------------------------------------------------------- structure of the path
+
+def test_determinism_and_slice_and_step_split(torch, pxr, orc):
+    w = wl.make(5, B=24)
+    a = gpu_render(torch, pxr, w, step0=7, env0=100)
+    b = gpu_render(torch, pxr, w, step0=7, env0=100)
+    assert np.array_equal(a["frames"], b["frames"]) and np.array_equal(a["ids"], b["ids"])
+    # one env alone, with its global index
+    e = 13
+    one = dict(w, poses=w["poses"][e:e + 1], shapes=w["shapes"][e:e + 1])
+    c = gpu_render(torch, pxr, one, step0=7, env0=100 + e)
+    assert np.array_equal(c["frames"][0], a["frames"][e]) and np.array_equal(c["ids"][0], a["ids"][e])
+    # steps 7,8,9 in one call == step 7 then steps 8,9
+    first = dict(w, poses=np.ascontiguousarray(w["poses"][:, :1]))
+    rest = dict(w, poses=np.ascontiguousarray(w["poses"][:, 1:]))
+    f0 = gpu_render(torch, pxr, first, step0=7, env0=100)
+    f1 = gpu_render(torch, pxr, rest, step0=8, env0=100)
+    assert np.array_equal(np.concatenate([f0["frames"], f1["frames"]], axis=1), a["frames"])
+
+
+def test_block_size_does_not_change_output(torch, pxr):
+    w = wl.make(4, B=20)
+    outs = [gpu_render(torch, pxr, w, threads=t) for t in (256, 512, 1024)]
+    for o in outs[1:]:
+        assert np.array_equal(o["frames"], outs[0]["frames"]) and np.array_equal(o["ids"], outs[0]["ids"])
+
+
+def test_batch_sizes_around_the_xcd_remap(torch, pxr, orc):
+    """Frame <-> workgroup renumbering must be a bijection for every grid size modulo 8."""
+    base = wl.make(3, B=41)
+    ref = oracle_render(orc, base)
+    for B in (1, 2, 7, 8, 9, 15, 16, 17, 33, 41):
+        w = dict(base, poses=base["poses"][:B])
+        got = gpu_render(torch, pxr, w)
+        assert_parity(got, dict(frames=ref["frames"][:B], ids=ref["ids"][:B]))
+
+
+# ---------------------------------------------------------------- image shapes
+
+@pytest.mark.parametrize("W,H", [(8, 8), (33, 27), (40, 24), (127, 9), (128, 128), (31, 31), (84, 84), (9, 128)])
+def test_image_shapes_including_unpacked_store_path(torch, pxr, orc, W, H):
+    """W*H not a multiple of 4 takes the byte-store epilogue; 128x128 is the largest frame."""
+    w = wl.make(3, B=6)
+    w["desc"]["width"], w["desc"]["height"] = W, H
+    assert_parity(gpu_render(torch, pxr, w, step0=2), oracle_render(orc, w, step0=2))
+    rng = np.random.default_rng(W * 131 + H)
+    video = rng.integers(0, 256, (7, H, W, 3), dtype=np.uint8)
+    w["distractor"] = dict(mode="video", seed=5, video=video, alpha=0.5, env_offset=None)
+    assert_parity(gpu_render(torch, pxr, w, step0=2), oracle_render(orc, w, step0=2))
+
+
+# ---------------------------------------------------------------- large triangles, clipping, rejects
+
+def _close_up(W=64, H=64, offset=(-0.9, 0.1, 0.35)):
+    bodies = [wl.box(0.3, 0.25, 0.2, (0.8, 0.5, 0.3), 2), wl.capsule(0.15, 0.3, (0.2, 0.7, 0.4), 8, 3),
+              wl.sphere(0.25, (0.5, 0.5, 0.9), 10, 4)]
+    d = wl.default_scene(W, H, bodies)
+    d["cam_offset"] = offset
+    return d
+
+
+def test_large_triangles_take_the_wave_path(torch, pxr, orc):
+    rng = np.random.default_rng(101)
+    B = 24
+    poses = np.zeros((B, 1, 3, 7), np.float32)
+    poses[:, 0, 0, :3] = (0, 0, 1)
+    poses[:, 0, 0, 3:] = wl.random_quats(rng, (B,))
+    for b in (1, 2):
+        poses[:, 0, b, :3] = np.array([0, 0, 1]) + rng.uniform(-0.5, 0.5, (B, 3))
+        poses[:, 0, b, 3:] = wl.random_quats(rng, (B,))
+    for W, H in [(64, 64), (128, 128), (33, 27)]:
+        w = dict(desc=_close_up(W, H), poses=poses, shapes=None, distractor=None)
+        ref = oracle_render(orc, w)
+        assert ((ref["ids"] < GROUND).mean() > 0.3)  # triangles tens of pixels wide
+        assert_parity(gpu_render(torch, pxr, w), ref)
+
+
+def test_huge_offscreen_extents_use_64bit_edges(torch, pxr, orc):
+    """Camera almost touching a big box: snapped coordinates run to millions, products beyond 2^31."""
+    bodies = [wl.sphere(0.05, (0.5, 0.5, 0.5), 8, 4), wl.box(3.0, 3.0, 0.5, (0.7, 0.6, 0.2), 3),
+              wl.capsule(0.4, 2.0, (0.3, 0.6, 0.8), 6, 2)]
+    d = wl.default_scene(64, 64, bodies)
+    d["cam_offset"] = (-0.6, 0.0, 0.25)
+    rng = np.random.default_rng(103)
+    B = 16
+    poses = np.zeros((B, 1, 3, 7), np.float32)
+    poses[:, 0, 0, :3] = (0, 0, 1.2)
+    poses[:, 0, 0, 3] = 1
+    poses[:, 0, 1, :3] = np.array([1.5, 0, 0.6]) + rng.uniform(-1.0, 1.0, (B, 3)) * np.array([1.0, 1.0, 0.3])
+    poses[:, 0, 1, 3:] = wl.random_quats(rng, (B,))
+    poses[:, 0, 2, :3] = np.array([0.5, 0, 1.2]) + rng.uniform(-0.5, 0.5, (B, 3))
+    poses[:, 0, 2, 3:] = wl.random_quats(rng, (B,))
+    w = dict(desc=d, poses=poses, shapes=None, distractor=None)
+    ref = oracle_render(orc, w)
+    s = orc.Scene(d)
+    spans = []
+    for e in range(B):
+        vs = s.vertex_stage(poses[e, 0])
+        ok = vs["rejected"] == 0
+        spans.append(int(np.ptp(vs["X"][ok])) if ok.any() else 0)
+    assert max(spans) > 1 << 17, "scene does not exercise the 64-bit path"
+    assert (ref["ids"] < GROUND).mean() > 0.2
+    assert_parity(gpu_render(torch, pxr, w), ref)
+
+
+def test_rejected_and_degenerate_inputs(torch, pxr, orc):
+    w = wl.make(2, B=8)
+    p = w["poses"].copy()
+    p[0, 0, :, 0] -= 10.0          # whole chain far behind the camera (root too: camera follows it) -> visible
+    p[1, 0, 1:, 0] = -5.0          # links behind the camera: rejected
+    p[2, 0, 3, :3] = np.nan        # non-finite position
+    p[3, 0, 2, 3:] = np.nan        # non-finite quaternion
+    p[4, 0, 0, 2] = -3.0           # root (and the camera) below the ground plane
+    p[5, 0, 4, :3] = p[5, 0, 0, :3] + np.array([-2.45, 0, 1.0], np.float32)  # a link straddling the near plane
+    p[6, 0, :, 3:] = 0.0           # zero quaternions: bodies collapse to their centres
+    p[7, 0, 5, 1] = 1e6            # far off to the side: guard band
+    w["poses"] = p
+    ref = oracle_render(orc, w)
+    got = gpu_render(torch, pxr, w)
+    assert_parity(got, ref)
+    assert not np.any(ref["ids"][4] == GROUND)  # camera below the plane: no ground
+
+
+def test_ground_variants(torch, pxr, orc):
+    w = wl.make(1, B=8)
+    for over in (dict(ground_enabled=False), dict(ground_cell=0.37), dict(z_far=4.0), dict(cam_up=(0.2, 0.1, 1.0)),
+                 dict(cam_offset=(1.5, 2.0, 3.0)), dict(fov_y_deg=25.0), dict(light_dir=(0.5, 0.2, -0.4))):
+        w2 = dict(w, desc=dict(w["desc"], **over))
+        assert_parity(gpu_render(torch, pxr, w2), oracle_render(orc, w2))
+
+
+# ---------------------------------------------------------------- distractors
+
+def test_colour_distractor_per_step_and_identity(torch, pxr, orc):
+    w = wl.make(3, B=12)
+    plain = gpu_render(torch, pxr, dict(w, distractor=None))
+    ident = gpu_render(torch, pxr, dict(w, distractor=dict(mode="color", seed=1, scale=(1.0, 1.0), offset=(0.0, 0.0))))
+    assert np.array_equal(plain["frames"], ident["frames"])
+    a = gpu_render(torch, pxr, w, step0=0)
+    b = gpu_render(torch, pxr, w, step0=1)
+    assert np.array_equal(a["ids"], b["ids"]) and not np.array_equal(a["frames"], b["frames"])
+    for step0, env0 in [(0, 0), (1, 0), (0xFFFFFFFE, 0), (5, 0xFFFFFFF0)]:
+        assert_parity(gpu_render(torch, pxr, w, step0=step0, env0=env0), oracle_render(orc, w, step0=step0, env0=env0))
+    big_seed = dict(w, distractor=dict(w["distractor"], seed=0xFEDCBA9876543210))
+    assert_parity(gpu_render(torch, pxr, big_seed, step0=9), oracle_render(orc, big_seed, step0=9))
+
+
+def test_video_distractor_offsets_alpha_and_wrap(torch, pxr, orc):
+    w = wl.make(4, B=12)
+    video = w["distractor"]["video"]
+    for dis, step0 in [(dict(mode="video", seed=4, video=video, alpha=0.5, env_offset=None), 0),
+                       (dict(mode="video", seed=4, video=video, alpha=0.5, env_offset=None), 63),
+                       (dict(mode="video", seed=9, video=video[:5], alpha=0.25, env_offset=None), 0xFFFFFFF0),
+                       (dict(mode="video", seed=4, video=video, alpha=1.0, env_offset=np.arange(12) * 7 + 60), 3),
+                       (dict(mode="video", seed=4, video=video, alpha=0.0, env_offset=None), 3)]:
+        w2 = dict(w, distractor=dis)
+        ref = oracle_render(orc, w2, step0=step0, env0=5)
+        assert_parity(gpu_render(torch, pxr, w2, step0=step0, env0=5), ref)
+    plain = gpu_render(torch, pxr, dict(w, distractor=None))
+    assert np.array_equal(plain["frames"], gpu_render(torch, pxr, w2, step0=3)["frames"])  # alpha = 0
+
+
+def test_rebinding_and_unbinding(torch, pxr, orc):
+    w = wl.make(3, B=6)
+    sc = pxr.Scene(w["desc"])
+    col = gpu_render(torch, pxr, w, scene=sc)
+    none = gpu_render(torch, pxr, dict(w, distractor=None), scene=sc)
+    col2 = gpu_render(torch, pxr, w, scene=sc)
+    assert np.array_equal(col["frames"], col2["frames"]) and not np.array_equal(col["frames"], none["frames"])
+    assert_parity(none, oracle_render(orc, dict(w, distractor=None)))
+    sc.close()
+
+
+# ---------------------------------------------------------------- argument errors on a live scene
+
+def test_render_argument_errors(torch, pxr):
+    w = wl.make(1, B=4)
+    sc = pxr.Scene(w["desc"])
+    L = pxr.lib()
+    poses = torch.from_numpy(w["poses"]).cuda()
+    frames = torch.empty((4, 1, 32, 32, 3), dtype=torch.uint8, device="cuda")
+    h = sc._h
+    assert L.pxr_render_batch(h, None, None, 4, 1, 0, 0, frames.data_ptr(), None, None) == pxr.ERR_INVALID_ARG
+    assert L.pxr_render_batch(h, poses.data_ptr(), None, 0, 1, 0, 0, frames.data_ptr(), None, None) == pxr.ERR_INVALID_ARG
+    assert L.pxr_render_batch(h, poses.data_ptr(), None, 4, 1, 0xFFFFFFFF, 0, frames.data_ptr(), None, None) == pxr.ERR_INVALID_ARG
+    assert L.pxr_render_batch(h, poses.data_ptr(), None, 4, 1, 0, 0, frames.data_ptr() + 1, None, None) == pxr.ERR_INVALID_ARG
+    assert L.pxr_render_batch(h, poses.data_ptr(), None, 1 << 31, 1, 0, 0, frames.data_ptr(), None, None) == pxr.ERR_INVALID_ARG
+    assert b"pxr_render_batch" in L.pxr_last_error()
+    with pytest.raises(pxr.PxrError):
+        sc.set_block_threads(128)
+    d = pxr.DistractorDesc()
+    d.mode = 2
+    import ctypes as C
+    assert L.pxr_apply_distractor(h, C.byref(d)) == pxr.ERR_INVALID_ARG  # video without a clip
+    d.mode = 9
+    assert L.pxr_apply_distractor(h, C.byref(d)) == pxr.ERR_INVALID_ARG
+    # the scene is still usable after the rejected calls
+    f, _ = sc.render_batch(poses)
+    torch.cuda.synchronize()
+    assert f.shape == (4, 1, 32, 32, 3)
+    sc.close()

@@ -1,0 +1,103 @@
+"""CPU-side checks of libpxr.so: exported symbols, argument validation, and the scene builder's
+tables against the oracle's (two independent tessellators / camera derivations must agree bit for bit)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2502_00021_amd import pxr
+from paper_2502_00021_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "pxr.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(pxr_[a-z_]+)\s*\(", header))
+    assert {"pxr_create_scene", "pxr_destroy_scene", "pxr_apply_distractor", "pxr_render_batch",
+            "pxr_last_error"} <= names
+    L = pxr.lib()
+    for n in sorted(names):
+        assert hasattr(L, n), f"{n} is declared in pxr.h but not exported"
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_scene_tables_equal_the_oracles(orc, cfg):
+    desc = wl.make(cfg, B=1)["desc"]
+    t = pxr.host_tables(desc)
+    s = orc.Scene(desc)
+    m, cam = s.mesh(), s.camera()
+    assert (t["V"], t["T"]) == (s.V, s.T)
+    for k in ("uverts", "tris", "normals", "mul", "vert_body", "tri_body"):
+        assert np.array_equal(t[k], m[k]), k
+    for k in ("Rv", "cx", "cy", "gs", "l"):
+        assert np.array_equal(t[k], cam[k]), k
+    assert t["f"] == cam["f"]
+    assert 0 < t["lds_bytes"] <= 160 * 1024
+
+
+def test_tables_for_odd_tessellations(orc):
+    bodies = [wl.capsule(0.1, 0.2, (0.5, 0.5, 0.5), 3, 1), wl.sphere(0.2, (0.1, 0.2, 0.3), 5, 2),
+              wl.box(0.1, 0.2, 0.3, (0.3, 0.2, 0.1), 3), wl.capsule(0.05, 0.0, (0.5, 0.5, 0.5), 7, 3)]
+    desc = wl.default_scene(40, 24, bodies, root_body=2)
+    desc.update(fov_y_deg=47.0, cam_offset=(1.0, -2.0, 0.5), light_dir=(0.3, 0.3, -0.2), ground_cell=0.5)
+    t = pxr.host_tables(desc)
+    s = orc.Scene(desc)
+    m, cam = s.mesh(), s.camera()
+    for k in ("uverts", "tris", "normals", "mul", "vert_body", "tri_body"):
+        assert np.array_equal(t[k], m[k]), k
+    for k in ("Rv", "cx", "cy", "gs", "l"):
+        assert np.array_equal(t[k], cam[k]), k
+
+
+def _expect(desc, code):
+    with pytest.raises(pxr.PxrError) as ei:
+        pxr.host_tables(desc)
+    assert ei.value.code == code
+    assert len(str(ei.value)) > 20
+
+
+def test_scene_validation_errors():
+    base = wl.make(1, B=1)["desc"]
+    _expect(dict(base, width=4), pxr.ERR_UNSUPPORTED)
+    _expect(dict(base, height=129), pxr.ERR_UNSUPPORTED)
+    _expect(dict(base, bodies=[]), pxr.ERR_UNSUPPORTED)
+    _expect(dict(base, bodies=base["bodies"] * 17), pxr.ERR_UNSUPPORTED)  # 68 bodies
+    _expect(dict(base, root_body=4), pxr.ERR_INVALID_ARG)
+    _expect(dict(base, fov_y_deg=float("nan")), pxr.ERR_INVALID_ARG)
+    _expect(dict(base, z_near=0.0), pxr.ERR_INVALID_ARG)
+    _expect(dict(base, z_far=0.05), pxr.ERR_INVALID_ARG)
+    _expect(dict(base, cam_offset=(0.0, 0.0, 0.0)), pxr.ERR_INVALID_ARG)
+    _expect(dict(base, cam_up=(-2.5, 0.0, 1.0)), pxr.ERR_INVALID_ARG)  # parallel to the view direction
+    _expect(dict(base, light_dir=(0.0, 0.0, 0.0)), pxr.ERR_INVALID_ARG)
+    _expect(dict(base, ground_cell=-1.0), pxr.ERR_INVALID_ARG)
+    bad = dict(base["bodies"][0], kind=7)
+    _expect(dict(base, bodies=[bad]), pxr.ERR_INVALID_ARG)
+    _expect(dict(base, bodies=[dict(base["bodies"][0], n_lon=2)]), pxr.ERR_UNSUPPORTED)
+    _expect(dict(base, bodies=[dict(base["bodies"][0], shape=(float("inf"), 1, 1, 1))]), pxr.ERR_INVALID_ARG)
+    # too much geometry for 65535 vertices / the LDS budget
+    _expect(dict(base, bodies=[wl.sphere(0.1, (0.5, 0.5, 0.5), 64, 32)] * 20), pxr.ERR_UNSUPPORTED)
+    _expect(dict(base, width=128, height=128, bodies=[wl.sphere(0.1, (0.5, 0.5, 0.5), 64, 32)] * 2), pxr.ERR_UNSUPPORTED)
+
+
+def test_null_arguments_are_errors_not_crashes():
+    L = pxr.lib()
+    assert L.pxr_create_scene(None, None) == pxr.ERR_INVALID_ARG
+    assert b"null" in L.pxr_last_error()
+    assert L.pxr_apply_distractor(None, None) == pxr.ERR_INVALID_ARG
+    assert L.pxr_render_batch(None, None, None, 1, 1, 0, 0, None, None, None) == pxr.ERR_INVALID_ARG
+    assert L.pxr_scene_info(None, None, None, None, None) == pxr.ERR_INVALID_ARG
+    assert L.pxr_set_block_threads(None, 256) == pxr.ERR_INVALID_ARG
+    assert L.pxr_host_tables(None, None, None, None, None, None, None, None) == pxr.ERR_INVALID_ARG
+    assert L.pxr_destroy_scene(None) == pxr.OK
+
+
+def test_row_division_constant():
+    """p // W == (p * ceil(2^32 / W)) >> 32 for every pixel index of every supported width."""
+    for W in range(8, 129):
+        magic = ((1 << 32) + W - 1) // W
+        p = np.arange(128 * W, dtype=np.uint64)
+        assert np.array_equal((p * np.uint64(magic)) >> np.uint64(32), p // np.uint64(W))
