@@ -31,23 +31,25 @@ from paper_2502_00021_amd import workloads  # noqa: E402
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 HBM_PEAK_GBS = 8000.0
 
-# Measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE) on the headline workload, scaled by
-# the same counters on a plain copy kernel; see profiles/.  None until measured.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = None
+# HBM bytes per launch of the default workload (cfg5, 65536 envs x 3 steps), measured with two
+# rocprofv3 --pmc passes (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the factors a plain 1 GiB copy
+# gives for the same counters); profiles/render_kernel_cfg5_humanoid_box_64.md.  Other workloads: null.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("cfg5", 65536): 2538.8e6}
 
 
 def algorithmic_ops_per_frame(V, T, npix, mode):
-    """Lane-operations per frame that the method itself prescribes ("Roofline").
+    """Lane-operations per frame that the method itself prescribes.
 
     Counted from the operation list of the specification, not from the kernel's
-    instruction stream: 36 per template vertex, 44 per triangle (gather, cull,
-    pixel-range test), 66 per pixel (ground ray, z-resolve, shade, quantise,
-    pack) plus 9 per pixel for the colour distractor or 9 for the video blend.
-    The data-dependent raster term (a few percent) is left out, which can only
+    instruction stream (an IEEE fp32 division counts as 10, memory and address
+    work as 0): 39 per template vertex, 40 per triangle (gather, box,
+    pixel-range test, area sign), 46 per pixel (ground ray, z-resolve, colour,
+    quantise, pack), plus 9 per pixel with a distractor bound.  The
+    data-dependent raster term (a few percent) is left out, which can only
     understate the achieved figure.
     """
-    per_pixel = 66 + (9 if mode in ("color", "video") else 0)
-    return 36 * V + 44 * T + per_pixel * npix
+    per_pixel = 46 + (9 if mode in ("color", "video") else 0)
+    return 39 * V + 40 * T + per_pixel * npix
 
 
 def algorithmic_bytes_per_frame(K, npix, mode, has_shapes, S):
@@ -102,6 +104,9 @@ def main():
     ap.add_argument("--threads", type=int, default=0, help="threads per frame workgroup (0 = library default)")
     ap.add_argument("--no-distractor", action="store_true")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain 1 GiB device-to-device copy kernel (the known-size reference that "
+                         "scales the FETCH_SIZE / WRITE_SIZE counters of a profiler run)")
     ap.add_argument("--extras", action="store_true", help="also time the other configurations (reported under 'others')")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -113,6 +118,17 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
+
+    if args.calibrate_copy:
+        n = 1 << 30
+        src = torch.full((n,), 7, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "launches": 3}))
+        return
 
     def time_workload(cfg, envs, steps, warmup, distract=True, threads=0):
         w = workloads.make(cfg, B=envs)
@@ -169,7 +185,7 @@ def main():
                    "block_threads": r["info"]["block_threads"], "lds_bytes_per_frame": r["info"]["lds_bytes"],
                    "frames_per_step": n_frames},
         "roofline": {"bound": "alu", "achieved": achieved_tops, "peak": ALU_PEAK_TOPS, "unit": "Tlane-op/s",
-                     "frac": achieved_tops / ALU_PEAK_TOPS, "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH,
+                     "frac": achieved_tops / ALU_PEAK_TOPS, "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((args.workload, r["B"])),
                      "kernel": "render_kernel", "avg_launch_ms": 1e3 * avg_kernel_s,
                      "algorithmic_ops_per_frame": ops // n_frames,
                      "hbm": {"achieved": byts / avg_kernel_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -282,7 +282,10 @@ def test_render_argument_errors(torch, pxr):
     h = sc._h
     assert L.pxr_render_batch(h, None, None, 4, 1, 0, 0, frames.data_ptr(), None, None) == pxr.ERR_INVALID_ARG
     assert L.pxr_render_batch(h, poses.data_ptr(), None, 0, 1, 0, 0, frames.data_ptr(), None, None) == pxr.ERR_INVALID_ARG
-    assert L.pxr_render_batch(h, poses.data_ptr(), None, 4, 1, 0xFFFFFFFF, 0, frames.data_ptr(), None, None) == pxr.ERR_INVALID_ARG
+    poses2 = torch.cat([poses, poses], dim=1).contiguous()
+    frames2 = torch.empty((4, 2, 32, 32, 3), dtype=torch.uint8, device="cuda")
+    assert L.pxr_render_batch(h, poses2.data_ptr(), None, 4, 2, 0xFFFFFFFF, 0, frames2.data_ptr(), None, None) == pxr.ERR_INVALID_ARG
+    assert L.pxr_render_batch(h, poses2.data_ptr(), None, 4, 2, 0, 0xFFFFFFFD, frames2.data_ptr(), None, None) == pxr.ERR_INVALID_ARG
     assert L.pxr_render_batch(h, poses.data_ptr(), None, 4, 1, 0, 0, frames.data_ptr() + 1, None, None) == pxr.ERR_INVALID_ARG
     assert L.pxr_render_batch(h, poses.data_ptr(), None, 1 << 31, 1, 0, 0, frames.data_ptr(), None, None) == pxr.ERR_INVALID_ARG
     assert b"pxr_render_batch" in L.pxr_last_error()
