@@ -136,7 +136,7 @@ int pxr_render_batch(pxr_scene* s, const float* d_poses, const float* d_shapes, 
 int pxr_scene_info(const pxr_scene* s, uint32_t* n_verts, uint32_t* n_tris, uint32_t* lds_bytes,
                    uint32_t* block_threads);
 
-/* Override the threads per frame workgroup (256, 512 or 1024); 0 restores the
+/* Override the threads per frame workgroup (256, 512, 768 or 1024); 0 restores the
  * default.  A tuning knob for benchmarks; output does not depend on it. */
 int pxr_set_block_threads(pxr_scene* s, uint32_t threads);
 
@@ -148,9 +148,11 @@ int pxr_set_block_threads(pxr_scene* s, uint32_t threads);
  *   tri_idx   [T*2] v0 | v1<<16 ,  v2 | body<<16
  *   tri_shade [T*4] unit normal in the body frame, colour multiplier
  *   cxcy      [W+H] ray slopes of the pixel-centre columns, then rows
- *   consts    [16]  right[3], up[3], forward[3], focal, ground shade[2], light[3], LDS bytes */
+ *   consts    [16]  right[3], up[3], forward[3], focal, ground shade[2], light[3], LDS bytes
+ *   pair_tbl  [P*3] binning table: q0 | q1<<16, q2 | q3<<16, triA | triB<<16 (two triangles sharing the
+ *             edge q0-q2; a lone triangle has q3 = q2 and triB = 0xFFFF); P is returned in n_pairs */
 int pxr_host_tables(const pxr_scene_desc* desc, uint32_t* n_verts, uint32_t* n_tris, float* vtmpl, uint32_t* tri_idx,
-                    float* tri_shade, float* cxcy, float* consts);
+                    float* tri_shade, float* cxcy, float* consts, uint32_t* n_pairs, uint32_t* pair_tbl);
 
 /* Reason for the last failure on this thread; valid until the next call on it. */
 const char* pxr_last_error(void);

@@ -28,11 +28,12 @@ int fail(int code, const std::string& msg) {
 }
 
 uint32_t pick_block_threads(const pxr::SceneConsts& sc) {
-    // As many waves per compute unit as the 160 KB of LDS allow: with few
-    // resident workgroups each one has to bring its own latency hiding.
+    // Fill the 32 wave slots of a compute unit: LDS decides how many frame
+    // workgroups are resident, the workgroup size makes up the rest.  (The
+    // 1024-thread variant is compiled for 64 VGPRs so that two of them fit.)
     const uint32_t groups_per_cu = (160u * 1024u) / (sc.lds_total ? sc.lds_total : 1u);
-    if (groups_per_cu >= 4) return 256;
-    if (groups_per_cu >= 2) return 512;
+    if (groups_per_cu >= 8) return 256;
+    if (groups_per_cu >= 3) return 512;
     return 1024;
 }
 
@@ -63,11 +64,12 @@ int pxr_create_scene(const pxr_scene_desc* desc, pxr_scene** out) {
         size_t bytes;
         size_t off;
     };
-    Part parts[5] = {{hs.vtmpl.data(), hs.vtmpl.size() * 4, 0},
+    Part parts[6] = {{hs.vtmpl.data(), hs.vtmpl.size() * 4, 0},
                      {hs.tri_idx.data(), hs.tri_idx.size() * 4, 0},
                      {hs.tri_shade.data(), hs.tri_shade.size() * 4, 0},
                      {hs.body_const.data(), hs.body_const.size() * 4, 0},
-                     {hs.cxcy.data(), hs.cxcy.size() * 4, 0}};
+                     {hs.cxcy.data(), hs.cxcy.size() * 4, 0},
+                     {hs.pair_tbl.data(), hs.pair_tbl.size() * 4, 0}};
     size_t total = 0;
     for (Part& p : parts) {
         p.off = total;
@@ -93,6 +95,7 @@ int pxr_create_scene(const pxr_scene_desc* desc, pxr_scene** out) {
     s->sc.tri_shade = reinterpret_cast<const float*>(base + parts[2].off);
     s->sc.body_const = reinterpret_cast<const float*>(base + parts[3].off);
     s->sc.cxcy = reinterpret_cast<const float*>(base + parts[4].off);
+    s->sc.pair_tbl = reinterpret_cast<const uint32_t*>(base + parts[5].off);
 
     rc = pxr::prepare_kernels(s->sc.lds_total, err);
     if (rc != PXR_OK) {
@@ -178,7 +181,7 @@ int pxr_scene_info(const pxr_scene* s, uint32_t* n_verts, uint32_t* n_tris, uint
 }
 
 int pxr_host_tables(const pxr_scene_desc* desc, uint32_t* n_verts, uint32_t* n_tris, float* vtmpl, uint32_t* tri_idx,
-                    float* tri_shade, float* cxcy, float* consts) {
+                    float* tri_shade, float* cxcy, float* consts, uint32_t* n_pairs, uint32_t* pair_tbl) {
     if (!desc) return fail(PXR_ERR_INVALID_ARG, "pxr_host_tables: null desc");
     pxr::HostScene hs;
     std::string err;
@@ -190,6 +193,8 @@ int pxr_host_tables(const pxr_scene_desc* desc, uint32_t* n_verts, uint32_t* n_t
     if (tri_idx) std::memcpy(tri_idx, hs.tri_idx.data(), hs.tri_idx.size() * 4);
     if (tri_shade) std::memcpy(tri_shade, hs.tri_shade.data(), hs.tri_shade.size() * 4);
     if (cxcy) std::memcpy(cxcy, hs.cxcy.data(), hs.cxcy.size() * 4);
+    if (n_pairs) *n_pairs = hs.c.P;
+    if (pair_tbl) std::memcpy(pair_tbl, hs.pair_tbl.data(), hs.pair_tbl.size() * 4);
     if (consts) {
         for (int i = 0; i < 3; ++i) {
             consts[i] = hs.c.Rt[i];
@@ -208,8 +213,8 @@ int pxr_host_tables(const pxr_scene_desc* desc, uint32_t* n_verts, uint32_t* n_t
 int pxr_set_block_threads(pxr_scene* s, uint32_t threads) {
     if (!s) return fail(PXR_ERR_INVALID_ARG, "pxr_set_block_threads: null scene");
     if (threads == 0) threads = s->default_threads;
-    if (threads != 256 && threads != 512 && threads != 1024)
-        return fail(PXR_ERR_INVALID_ARG, "pxr_set_block_threads: must be 256, 512 or 1024");
+    if (threads != 256 && threads != 512 && threads != 768 && threads != 1024)
+        return fail(PXR_ERR_INVALID_ARG, "pxr_set_block_threads: must be 256, 512, 768 or 1024");
     s->block_threads = threads;
     return PXR_OK;
 }

@@ -15,10 +15,14 @@ namespace pxr {
 // near-plane / guard-band test; any triangle touching it is dropped.
 constexpr int32_t kRejectedX = INT32_MIN;
 
-// A surviving triangle whose clamped pixel range holds at most this many
-// pixel centres (and whose fixed-point extent is below 2^15) is rasterised by
-// one lane; anything bigger is spread over a whole wavefront.
+// Raster bins by the number of pixel centres in a surviving triangle's clamped
+// bounding box (both fixed-point extents must also be below 2^15):
+//   tiny  <= kTinyMaxPixels   one lane, at most two loop trips
+//   small <= kSmallMaxPixels  one lane
+//   large otherwise           a whole wavefront, one pixel per lane
+constexpr uint32_t kTinyMaxPixels = 2;
 constexpr uint32_t kSmallMaxPixels = 16;
+constexpr uint32_t kNoTriangle = 0xFFFFu;
 
 // Per-body record kept in LDS for the duration of one frame (floats).
 //   [0..8]  M  = view rotation * body rotation, row-major
@@ -40,16 +44,19 @@ struct SceneConsts {
     float cell, gs[2], bg[3];
     uint32_t ground_on, cell_is_one;
     // sizes
-    uint32_t W, H, npix, K, root, V, T;
+    uint32_t W, H, npix, K, root, V, T, P;  // P = entries of the pair table
     uint32_t magicW;  // ceil(2^32 / W): p / W == mulhi(p, magicW) for p < 2^14 * 2^7
     // device tables
     const float* vtmpl;       // [V][4]  ux,uy,uz, bits = body<<2 | (s+1)
     const uint32_t* tri_idx;  // [T][2]  v0 | v1<<16 ,  v2 | body<<16
     const float* tri_shade;   // [T][4]  unit normal (body frame), colour multiplier
+    const uint32_t* pair_tbl; // [P][3]  q0 | q1<<16 , q2 | q3<<16 , triA | triB<<16: two triangles sharing the
+                              //         edge q0-q2, or one triangle (q3 = q2, triB = kNoTriangle)
     const float* body_const;  // [K][8]  shape a,b,c,h ; rgb r,g,b,0
     const float* cxcy;        // [W+H]   pixel-centre ray slopes
     // LDS carve-up (byte offsets into the dynamic segment)
-    uint32_t lds_keys, lds_vx, lds_vy, lds_vd, lds_body, lds_list, lds_cxcy, lds_misc, lds_total;
+    // lds_keys doubles as the surviving-pair list (u16[P]) before the raster phase clears it
+    uint32_t lds_keys, lds_vx, lds_vy, lds_vd, lds_body, lds_list, lds_large, lds_cxcy, lds_misc, lds_total;
 };
 
 // Distractor state bound by pxr_apply_distractor.
@@ -69,6 +76,7 @@ struct HostScene {
     std::vector<float> vtmpl;
     std::vector<uint32_t> tri_idx;
     std::vector<float> tri_shade;
+    std::vector<uint32_t> pair_tbl;
     std::vector<float> body_const;
     std::vector<float> cxcy;
 };

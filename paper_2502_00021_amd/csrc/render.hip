@@ -9,10 +9,14 @@
 // seeded counter-based generator.
 //
 // Phases of one workgroup (barriers between them):
-//   0  clear the pixel keys, load per-body transforms          (LDS)
+//   0  per-body transforms, per-frame draws and the three non-triangle colours
 //   1  instancing: template vertex -> view space -> snapped fixed point
-//   2  binning: per triangle cull + pixel-range test; survivors are compacted
-//      wave-wide (ballot + mbcnt) into a "one lane" bin and a "whole wave" bin
+//   2a binning, coarse: one lane per PAIR of edge-sharing triangles, one
+//      bounding-box / pixel-centre test for both; surviving pairs are
+//      compacted wave-wide (ballot + mbcnt) into a list in LDS
+//   2b binning, exact: one lane per triangle of a surviving pair: cull, own
+//      pixel range, then compaction into three bins by candidate-pixel count
+//      (tiny / small: one lane each, large: a whole wave)
 //   3  raster: integer edge functions, top-left rule, float reversed depth,
 //      64-bit LDS atomic max on (depth bits << 32 | ~triangle id)
 //   4  resolve: ground ray, id -> flat Lambert colour, distractor, uint8 pack,
@@ -121,8 +125,33 @@ __device__ __forceinline__ void raster_small(const TriSetup& s, uint32_t tri, ui
 }
 
 // A whole wavefront sweeps a large triangle in 8x8 pixel tiles, one pixel per
-// lane, with 64-bit edge functions (coordinates reach 2^22, products 2^46).
-__device__ __forceinline__ void raster_wave(const TriSetup& s, uint32_t tri, uint32_t W, u64* keys, uint32_t lane) {
+// lane; extents below 2^15 allow exact 24-bit multiplies.
+__device__ __forceinline__ void raster_wave32(const TriSetup& s, uint32_t tri, uint32_t W, u64* keys, uint32_t lane) {
+    const int dx_ab = s.bx - s.ax, dy_ab = s.by - s.ay;
+    const int dx_bc = s.cx - s.bx, dy_bc = s.cy - s.by;
+    const int dx_ca = s.ax - s.cx, dy_ca = s.ay - s.cy;
+    const int A2 = __mul24(dx_ab, s.cy - s.ay) - __mul24(dy_ab, s.cx - s.ax);
+    const float invA = 1.0f / (float)A2;
+    const int b_ab = edge_bias(dx_ab, dy_ab), b_bc = edge_bias(dx_bc, dy_bc), b_ca = edge_bias(dx_ca, dy_ca);
+    const int li = (int)(lane & 7u), lj = (int)(lane >> 3);
+    for (int ty = s.j0 & ~7; ty <= s.j1; ty += 8)
+        for (int tx = s.i0 & ~7; tx <= s.i1; tx += 8) {
+            const int i = tx + li, j = ty + lj;
+            if (i < s.i0 || i > s.i1 || j < s.j0 || j > s.j1) continue;
+            const int px = (i << 8) + 128, py = (j << 8) + 128;
+            const int e_ab = __mul24(dx_ab, py - s.ay) - __mul24(dy_ab, px - s.ax);
+            const int e_bc = __mul24(dx_bc, py - s.by) - __mul24(dy_bc, px - s.bx);
+            const int e_ca = __mul24(dx_ca, py - s.cy) - __mul24(dy_ca, px - s.cx);
+            if (((e_ab + b_ab) | (e_bc + b_bc) | (e_ca + b_ca)) >= 0) {
+                const float beta = (float)e_ca * invA, gamma = (float)e_ab * invA;
+                z_test(keys, (uint32_t)j * W + (uint32_t)i, __builtin_fmaf(beta, s.dDb, __builtin_fmaf(gamma, s.dDc, s.Da)),
+                       tri);
+            }
+        }
+}
+
+// The same sweep with 64-bit edge functions (coordinates reach 2^22, products 2^46).
+__device__ __forceinline__ void raster_wave64(const TriSetup& s, uint32_t tri, uint32_t W, u64* keys, uint32_t lane) {
     typedef long long i64;
     const i64 dx_ab = s.bx - s.ax, dy_ab = s.by - s.ay;
     const i64 dx_bc = s.cx - s.bx, dy_bc = s.cy - s.by;
@@ -151,10 +180,9 @@ __device__ __forceinline__ void raster_wave(const TriSetup& s, uint32_t tri, uin
 // Gather a triangle's snapped vertices and its clamped pixel-centre range.
 // Returns false if a vertex was rejected or no pixel centre is inside the
 // bounding box.  `small_extent` = both fixed-point extents below 2^15.
-__device__ __forceinline__ bool tri_gather(const SceneConsts& sc, const uint32_t* __restrict__ tri_idx, uint32_t t,
-                                           const int* vx, const int* vy, TriSetup& s, uint32_t& v0, uint32_t& v1,
-                                           uint32_t& v2, bool& small_extent) {
-    const uint2 ti = reinterpret_cast<const uint2*>(tri_idx)[t];
+__device__ __forceinline__ bool tri_gather(const SceneConsts& sc, uint32_t t, const int* vx, const int* vy, TriSetup& s,
+                                           uint32_t& v0, uint32_t& v1, uint32_t& v2, bool& small_extent) {
+    const uint2 ti = reinterpret_cast<const uint2*>(sc.tri_idx)[t];
     v0 = ti.x & 0xFFFFu;
     v1 = ti.x >> 16;
     v2 = ti.y & 0xFFFFu;
@@ -182,28 +210,146 @@ __device__ __forceinline__ void tri_depths(TriSetup& s, const float* vd, uint32_
     s.dDc = vd[v1] - s.Da;
 }
 
+// Wave-wide stream compaction: lanes with `pred` append `value` to a u16 list.
+// `dir` = +1 grows the list upwards from `origin`, -1 downwards.  Must be
+// reached by every lane of the wave (it is, the callers' loops have uniform
+// trip counts).  One LDS atomic per wave.
+__device__ __forceinline__ void wave_append(bool pred, uint32_t value, uint32_t* counter, uint16_t* list, int origin, int dir,
+                                            uint32_t lane) {
+    const u64 m = __ballot(pred);
+    if (m) {
+        uint32_t base = 0;
+        if (lane == 0) base = atomicAdd(counter, (uint32_t)__popcll(m));
+        base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
+        if (pred) {
+            const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+            list[origin + dir * (int)(base + rank)] = (uint16_t)value;
+        }
+    }
+}
+
+__device__ __forceinline__ uint32_t quantise(float c) {
+    return (uint32_t)(int)__builtin_floorf(__builtin_fmaf(c, 255.0f, 0.5f)) & 0xFFu;
+}
+
 // ---------------------------------------------------------------- the kernel
 
-struct FrameUniforms {  // written by thread 0 into LDS, read by all after a barrier
-    uint32_t n_small, n_large;
+#ifdef PXR_PHASE_TIMING
+// Profiling build only: lane 0 of every workgroup adds the shader-clock span of each phase.
+__device__ unsigned long long g_phase_cycles[8];
+#define PXR_PHASE_BEGIN() unsigned long long phase_t0 = clock64()
+#define PXR_PHASE_MARK(i)                                         \
+    if (tid == 0) {                                               \
+        const unsigned long long now = clock64();                 \
+        atomicAdd(&g_phase_cycles[i], now - phase_t0);            \
+        phase_t0 = now;                                           \
+    }
+#else
+#define PXR_PHASE_BEGIN()
+#define PXR_PHASE_MARK(i)
+#endif
+
+struct FrameUniforms {  // written in phase 0 (lane 0) or by LDS atomics, read by all after a barrier
+    uint32_t n_pairs, n_tiny, n_small, n_large;
     float scale[3], offs[3];
     uint32_t video_frame;
+    float base_col[3][3];     // background, ground grey 0, ground grey 1 after the colour distractor
+    uint32_t base_packed[3];  // the same three, quantised: R | G<<8 | B<<16
 };
 
+// Everything phase 4 needs that is uniform over the frame, in registers.
+struct ResolveCtx {
+    float eye_x, eye_y, eye_z, inv_ez;
+    bool ground_ok;
+    uint32_t mode;
+    float scale[3], offs[3];
+    const float* base_col;        // LDS: [3][3] background, ground grey 0, ground grey 1 (after the colour distractor)
+    const uint32_t* base_packed;  // LDS: [3] the same, quantised
+    const uint8_t* vframe;
+    float alpha;
+};
+
+// Ground plane z = 0 along the pixel's ray: returns its z-test key (0 = miss)
+// and the ray parameter (= view depth) of the hit.
+__device__ __forceinline__ u64 ground_key(const SceneConsts& sc, const ResolveCtx& rc, float ndz, float& tg) {
+    tg = 0.0f;
+    if (rc.ground_ok && ndz > 0.0f) {
+        tg = rc.eye_z / ndz;
+        if (tg >= sc.z_near && tg <= sc.z_far) {
+            const float dg = (sc.z_near * ndz) * rc.inv_ez;
+            return ((u64)__float_as_uint(dg) << 32) | 1ull;
+        }
+    }
+    return 0ull;
+}
+
+// One pixel: winner of (triangles, ground, background) -> colour -> distractor
+// -> 24-bit RGB.  `low` returns ~id.  `vbytes` = the pixel's three video bytes
+// (R | G<<8 | B<<16), only read in video mode.
+__device__ __forceinline__ uint32_t resolve_pixel(const SceneConsts& sc, const ResolveCtx& rc, const float* body, u64 key,
+                                                  u64 gkey, float tg, float dwx, float dwy, uint32_t vbytes, uint32_t& low) {
+    key = key > gkey ? key : gkey;
+    low = (uint32_t)key;
+    if (low > 1u) {
+        // a triangle: flat Lambert + ambient in the body frame
+        const uint32_t g = 0xFFFFFFFFu - low;
+        const float4 ns = reinterpret_cast<const float4*>(sc.tri_shade)[g];
+        const float* o = body + (sc.tri_idx[g * 2 + 1] >> 16) * kBodyStride;
+        float I = __builtin_fmaf(ns.x, o[12], __builtin_fmaf(ns.y, o[13], ns.z * o[14]));
+        I = I > 0.0f ? I : 0.0f;
+        const float sh = __builtin_fmaf(sc.diffuse, I, sc.ambient);
+        uint32_t rgb = 0;
+#pragma unroll
+        for (int ch = 0; ch < 3; ++ch) {
+            float v = (o[20 + ch] * ns.w) * sh;
+            v = v < 1.0f ? v : 1.0f;
+            if (rc.mode == PXR_DISTRACT_COLOR) {
+                v = __builtin_fmaf(v, rc.scale[ch], rc.offs[ch]);
+                v = v > 0.0f ? v : 0.0f;
+                v = v < 1.0f ? v : 1.0f;
+            }
+            rgb |= quantise(v) << (8 * ch);
+        }
+        return rgb;
+    }
+    // background or ground: one of three colours per frame
+    int cls = 0;
+    if (low == 1u) {
+        const float wx = __builtin_fmaf(tg, dwx, rc.eye_x);
+        const float wy = __builtin_fmaf(tg, dwy, rc.eye_y);
+        const float ux = sc.cell_is_one ? wx : wx / sc.cell;
+        const float uy = sc.cell_is_one ? wy : wy / sc.cell;
+        cls = 1 + (((int)__builtin_floorf(ux) + (int)__builtin_floorf(uy)) & 1);
+    }
+    if (rc.mode != PXR_DISTRACT_VIDEO) return rc.base_packed[cls];
+    uint32_t rgb = 0;
+#pragma unroll
+    for (int ch = 0; ch < 3; ++ch) {
+        const float c = rc.base_col[cls * 3 + ch];
+        const float vf = (float)((vbytes >> (8 * ch)) & 0xFFu) * (1.0f / 255.0f);
+        rgb |= quantise(__builtin_fmaf(rc.alpha, vf - c, c)) << (8 * ch);
+    }
+    return rgb;
+}
+
+// Register budget: two 80 KB workgroups share a compute unit, so 1024-thread groups need all
+// 8 wave slots per SIMD (<= 64 VGPRs); the smaller groups may use more registers.
 template <int NT, int PX>
-__global__ __launch_bounds__(NT) void render_kernel(const SceneConsts sc, const DistractConsts dc,
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ? 8 : (NT >= 768 ? 6 : 4)))) void render_kernel(const SceneConsts sc, const DistractConsts dc,
                                                     const float* __restrict__ poses, const float* __restrict__ shapes,
                                                     uint32_t S, uint32_t step0, uint32_t env0,
                                                     uint8_t* __restrict__ frames, uint32_t* __restrict__ ids) {
     extern __shared__ __align__(16) unsigned char lds[];
     u64* keys = reinterpret_cast<u64*>(lds + sc.lds_keys);
+    uint16_t* pair_list = reinterpret_cast<uint16_t*>(lds + sc.lds_keys);  // dead before the keys are cleared
     int* vx = reinterpret_cast<int*>(lds + sc.lds_vx);
     int* vy = reinterpret_cast<int*>(lds + sc.lds_vy);
     float* vd = reinterpret_cast<float*>(lds + sc.lds_vd);
     float* body = reinterpret_cast<float*>(lds + sc.lds_body);
     float* cxcy = reinterpret_cast<float*>(lds + sc.lds_cxcy);
     FrameUniforms* fu = reinterpret_cast<FrameUniforms*>(lds + sc.lds_misc);
-    uint16_t* list = reinterpret_cast<uint16_t*>(lds + sc.lds_list);
+    uint16_t* list = reinterpret_cast<uint16_t*>(lds + sc.lds_list);    // tiny bin grows up, small bin grows down
+    uint16_t* large = reinterpret_cast<uint16_t*>(lds + sc.lds_large);  // large bin
 
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & 63u;
@@ -218,8 +364,8 @@ __global__ __launch_bounds__(NT) void render_kernel(const SceneConsts sc, const 
     const float eye_y = pose[sc.root * 7 + 1] + sc.off[1];
     const float eye_z = pose[sc.root * 7 + 2] + sc.off[2];
 
-    // ---- phase 0: clear keys (0 = background at depth 0), per-body transforms, per-frame draws
-    for (uint32_t p = tid; p < sc.npix; p += NT) keys[p] = 0ull;
+    PXR_PHASE_BEGIN();
+    // ---- phase 0: per-body transforms, per-frame draws, the three non-triangle colours
     for (uint32_t i = tid; i < sc.W + sc.H; i += NT) cxcy[i] = sc.cxcy[i];
     if (tid < sc.K) {
         const float* p = pose + tid * 7;
@@ -253,17 +399,20 @@ __global__ __launch_bounds__(NT) void render_kernel(const SceneConsts sc, const 
 #pragma unroll
         for (int c = 0; c < 3; ++c) o[20 + c] = sc.body_const[tid * 8 + 4 + c];
     }
-    if (tid == 0) {
+    if (tid == NT - 1) {  // a lane of the last wave: the first wave is busy with the bodies
+        fu->n_pairs = 0;
+        fu->n_tiny = 0;
         fu->n_small = 0;
         fu->n_large = 0;
+        float scale[3] = {1.0f, 1.0f, 1.0f}, offs[3] = {0.0f, 0.0f, 0.0f};
         if (dc.mode == PXR_DISTRACT_COLOR) {
             uint32_t r[4];
             counter_rng(dc.seed_lo, dc.seed_hi, env, step, 0u, 0u, r);
 #pragma unroll
-            for (int c = 0; c < 3; ++c) fu->scale[c] = __builtin_fmaf(unit_float(r[c]), dc.scale_span, dc.scale_lo);
+            for (int c = 0; c < 3; ++c) scale[c] = __builtin_fmaf(unit_float(r[c]), dc.scale_span, dc.scale_lo);
             counter_rng(dc.seed_lo, dc.seed_hi, env, step, 1u, 0u, r);
 #pragma unroll
-            for (int c = 0; c < 3; ++c) fu->offs[c] = __builtin_fmaf(unit_float(r[c]), dc.offset_span, dc.offset_lo);
+            for (int c = 0; c < 3; ++c) offs[c] = __builtin_fmaf(unit_float(r[c]), dc.offset_span, dc.offset_lo);
         } else if (dc.mode == PXR_DISTRACT_VIDEO) {
             uint32_t first;
             if (dc.env_offset) {
@@ -275,8 +424,32 @@ __global__ __launch_bounds__(NT) void render_kernel(const SceneConsts sc, const 
             }
             fu->video_frame = (uint32_t)(((u64)first + (u64)step) % dc.n_frames);
         }
+        // Background and the two ground greys are the same for every pixel that shows them:
+        // run them through the colour distractor and the quantiser once per frame.
+#pragma unroll
+        for (int k = 0; k < 3; ++k) {
+            uint32_t packed = 0;
+#pragma unroll
+            for (int c = 0; c < 3; ++c) {
+                float v = k == 0 ? sc.bg[c] : sc.gs[k - 1];
+                if (dc.mode == PXR_DISTRACT_COLOR) {
+                    v = __builtin_fmaf(v, scale[c], offs[c]);
+                    v = v > 0.0f ? v : 0.0f;
+                    v = v < 1.0f ? v : 1.0f;
+                }
+                fu->base_col[k][c] = v;
+                packed |= quantise(v) << (8 * c);
+            }
+            fu->base_packed[k] = packed;
+        }
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            fu->scale[c] = scale[c];
+            fu->offs[c] = offs[c];
+        }
     }
     __syncthreads();
+    PXR_PHASE_MARK(0);
 
     // ---- phase 1: instancing + projection + snap (one lane per template vertex)
     for (uint32_t v = tid; v < sc.V; v += NT) {
@@ -304,194 +477,204 @@ __global__ __launch_bounds__(NT) void render_kernel(const SceneConsts sc, const 
         vd[v] = sc.z_near * inv;
     }
     __syncthreads();
+    PXR_PHASE_MARK(1);
 
-    // ---- phase 2: binning.  Uniform trip count so that ballots see whole waves.
-    for (uint32_t t0 = 0; t0 < sc.T; t0 += NT) {
-        const uint32_t t = t0 + tid;
-        bool keep = false, small = false;
-        if (t < sc.T) {
-            TriSetup s;
-            uint32_t v0, v1, v2;
-            bool small_extent;
-            if (tri_gather(sc, sc.tri_idx, t, vx, vy, s, v0, v1, v2, small_extent)) {
-                bool front;
-                if (small_extent)
-                    front = __mul24(s.bx - s.ax, s.cy - s.ay) > __mul24(s.by - s.ay, s.cx - s.ax);
-                else
-                    front = (long long)(s.bx - s.ax) * (long long)(s.cy - s.ay) >
-                            (long long)(s.by - s.ay) * (long long)(s.cx - s.ax);
-                keep = front;
-                small = small_extent && (uint32_t)((s.i1 - s.i0 + 1) * (s.j1 - s.j0 + 1)) <= kSmallMaxPixels;
+    // ---- phase 2a: coarse binning, one lane per pair of edge-sharing triangles.
+    // A pair survives if its four vertices' box holds a pixel centre (or if a
+    // vertex was rejected: then the exact per-triangle test decides).
+    for (uint32_t p0 = 0; p0 < sc.P; p0 += NT) {
+        const uint32_t p = p0 + tid;
+        bool keep = false;
+        if (p < sc.P) {
+            const uint32_t w0 = sc.pair_tbl[p * 3 + 0], w1 = sc.pair_tbl[p * 3 + 1];
+            const uint32_t q0 = w0 & 0xFFFFu, q1 = w0 >> 16, q2 = w1 & 0xFFFFu, q3 = w1 >> 16;
+            const int x0 = vx[q0], x1 = vx[q1], x2 = vx[q2], x3 = vx[q3];
+            if (x0 == kRejectedX || x1 == kRejectedX || x2 == kRejectedX || x3 == kRejectedX) {
+                keep = true;
+            } else {
+                const int y0 = vy[q0], y1 = vy[q1], y2 = vy[q2], y3 = vy[q3];
+                const int minx = min(imin3(x0, x1, x2), x3), maxx = max(imax3(x0, x1, x2), x3);
+                const int miny = min(imin3(y0, y1, y2), y3), maxy = max(imax3(y0, y1, y2), y3);
+                const int i0 = max(0, (minx + 127) >> 8), i1 = min((int)sc.W - 1, (maxx - 128) >> 8);
+                const int j0 = max(0, (miny + 127) >> 8), j1 = min((int)sc.H - 1, (maxy - 128) >> 8);
+                keep = i0 <= i1 && j0 <= j1;
             }
         }
-        const u64 m_small = __ballot(keep && small);
-        const u64 m_large = __ballot(keep && !small);
-        if (m_small) {
-            uint32_t base = 0;
-            if (lane == 0) base = atomicAdd(&fu->n_small, (uint32_t)__popcll(m_small));
-            base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
-            if (keep && small)
-                list[base + __builtin_amdgcn_mbcnt_hi((uint32_t)(m_small >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m_small, 0u))] =
-                    (uint16_t)t;
-        }
-        if (m_large) {
-            uint32_t base = 0;
-            if (lane == 0) base = atomicAdd(&fu->n_large, (uint32_t)__popcll(m_large));
-            base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
-            if (keep && !small)
-                list[sc.T - 1 - (base + __builtin_amdgcn_mbcnt_hi((uint32_t)(m_large >> 32),
-                                                                  __builtin_amdgcn_mbcnt_lo((uint32_t)m_large, 0u)))] =
-                    (uint16_t)t;
-        }
+        wave_append(keep, p, &fu->n_pairs, pair_list, 0, +1, lane);
     }
     __syncthreads();
+    PXR_PHASE_MARK(2);
 
-    // ---- phase 3: raster + z-test into the LDS key buffer
-    const uint32_t n_small = fu->n_small, n_large = fu->n_large;
-    for (uint32_t k = tid; k < n_small; k += NT) {
+    // ---- phase 2b: exact binning, one lane per triangle of a surviving pair
+    const uint32_t n_items = 2u * fu->n_pairs;
+    for (uint32_t k0 = 0; k0 < n_items; k0 += NT) {
+        const uint32_t k = k0 + tid;
+        int cls = 0;  // 0 none, 1 tiny, 2 small, 3 large
+        uint32_t t = 0;
+        if (k < n_items) {
+            const uint32_t w2 = sc.pair_tbl[(uint32_t)pair_list[k >> 1] * 3 + 2];
+            t = (k & 1u) ? (w2 >> 16) : (w2 & 0xFFFFu);
+            if (t != kNoTriangle) {
+                TriSetup s;
+                uint32_t v0, v1, v2;
+                bool small_extent;
+                if (tri_gather(sc, t, vx, vy, s, v0, v1, v2, small_extent)) {
+                    bool front;
+                    if (small_extent)
+                        front = __mul24(s.bx - s.ax, s.cy - s.ay) > __mul24(s.by - s.ay, s.cx - s.ax);
+                    else
+                        front = (long long)(s.bx - s.ax) * (long long)(s.cy - s.ay) >
+                                (long long)(s.by - s.ay) * (long long)(s.cx - s.ax);
+                    if (front) {
+                        const uint32_t npx = (uint32_t)((s.i1 - s.i0 + 1) * (s.j1 - s.j0 + 1));
+                        cls = !small_extent || npx > kSmallMaxPixels ? 3 : (npx > kTinyMaxPixels ? 2 : 1);
+                    }
+                }
+            }
+        }
+        wave_append(cls == 1, t, &fu->n_tiny, list, 0, +1, lane);
+        wave_append(cls == 2, t, &fu->n_small, list, (int)sc.T - 1, -1, lane);
+        wave_append(cls == 3, t, &fu->n_large, large, 0, +1, lane);
+    }
+    __syncthreads();
+    PXR_PHASE_MARK(3);
+
+    // the pair list is dead: clear the pixel keys it shared LDS with (0 = background at depth 0)
+    for (uint32_t p = tid; p < sc.npix; p += NT) keys[p] = 0ull;
+    __syncthreads();
+    PXR_PHASE_MARK(4);
+
+    // ---- phase 3: raster + z-test into the LDS key buffer.  Tiny triangles are dealt to lanes
+    // from the front, small ones from the back, so that waves stay homogeneous and busy.
+    const uint32_t n_tiny = fu->n_tiny, n_small = fu->n_small, n_large = fu->n_large;
+    for (uint32_t k = tid; k < n_tiny; k += NT) {
         const uint32_t t = list[k];
         TriSetup s;
         uint32_t v0, v1, v2;
         bool small_extent;
-        tri_gather(sc, sc.tri_idx, t, vx, vy, s, v0, v1, v2, small_extent);
+        tri_gather(sc, t, vx, vy, s, v0, v1, v2, small_extent);
         tri_depths(s, vd, v0, v1, v2);
         raster_small(s, t, sc.W, keys);
     }
-    for (uint32_t k = tid >> 6; k < n_large; k += NT / 64) {
+    for (uint32_t k = NT - 1 - tid; k < n_small; k += NT) {
         const uint32_t t = list[sc.T - 1 - k];
         TriSetup s;
         uint32_t v0, v1, v2;
         bool small_extent;
-        tri_gather(sc, sc.tri_idx, t, vx, vy, s, v0, v1, v2, small_extent);
+        tri_gather(sc, t, vx, vy, s, v0, v1, v2, small_extent);
         tri_depths(s, vd, v0, v1, v2);
-        raster_wave(s, t, sc.W, keys, lane);
+        raster_small(s, t, sc.W, keys);
+    }
+    {
+        const uint32_t n_waves = NT / 64, wave = (tid >> 6);
+        // start in the middle waves: the first ones hold the tiny bin, the last ones the small bin
+        for (uint32_t k = (wave + n_waves / 2) % n_waves; k < n_large; k += n_waves) {
+            const uint32_t t = large[k];
+            TriSetup s;
+            uint32_t v0, v1, v2;
+            bool small_extent;
+            tri_gather(sc, t, vx, vy, s, v0, v1, v2, small_extent);
+            tri_depths(s, vd, v0, v1, v2);
+            if (small_extent)
+                raster_wave32(s, t, sc.W, keys, lane);
+            else
+                raster_wave64(s, t, sc.W, keys, lane);
+        }
     }
     __syncthreads();
+    PXR_PHASE_MARK(5);
 
     // ---- phase 4: resolve + shade + distractor + pack + store
-    const bool ground_ok = sc.ground_on && eye_z > 0.0f;
-    const float inv_ez = 1.0f / eye_z;
-    const uint32_t mode = dc.mode;
-    float scale[3] = {1.0f, 1.0f, 1.0f}, offs[3] = {0.0f, 0.0f, 0.0f};
-    const uint8_t* vframe = nullptr;
-    if (mode == PXR_DISTRACT_COLOR) {
+    ResolveCtx rc;
+    rc.eye_x = eye_x;
+    rc.eye_y = eye_y;
+    rc.eye_z = eye_z;
+    rc.inv_ez = 1.0f / eye_z;
+    rc.ground_ok = sc.ground_on && eye_z > 0.0f;
+    rc.mode = dc.mode;
+    rc.vframe = nullptr;
+    rc.alpha = dc.alpha;
 #pragma unroll
-        for (int c = 0; c < 3; ++c) {
-            scale[c] = fu->scale[c];
-            offs[c] = fu->offs[c];
-        }
-    } else if (mode == PXR_DISTRACT_VIDEO) {
-        vframe = dc.video + (size_t)fu->video_frame * sc.npix * 3;
+    for (int c = 0; c < 3; ++c) {
+        rc.scale[c] = fu->scale[c];
+        rc.offs[c] = fu->offs[c];
     }
+    rc.base_col = &fu->base_col[0][0];
+    rc.base_packed = fu->base_packed;
+    if (rc.mode == PXR_DISTRACT_VIDEO) rc.vframe = dc.video + (size_t)fu->video_frame * sc.npix * 3;
     uint8_t* out = frames + (size_t)frame * sc.npix * 3;
     uint32_t* out_ids = ids ? ids + (size_t)frame * sc.npix : nullptr;
 
-    for (uint32_t q = tid; q * PX < sc.npix; q += NT) {
-        const uint32_t p0 = q * PX;
-        uint32_t j = __umulhi(p0, sc.magicW);
-        uint32_t i = p0 - j * sc.W;
-        uint32_t vid[3] = {0u, 0u, 0u};
-        if (PX == 4 && mode == PXR_DISTRACT_VIDEO) {
-            const uint32_t* vsrc = reinterpret_cast<const uint32_t*>(vframe) + q * 3;
-            vid[0] = vsrc[0];
-            vid[1] = vsrc[1];
-            vid[2] = vsrc[2];
-        }
-        uint32_t packed[3] = {0u, 0u, 0u};
-        uint32_t idv[PX];
+    if (PX == 4) {
+        // Four consecutive pixels of one row per lane (W is a multiple of 4): the row part of
+        // the ray is shared, and without camera roll so is the whole ground test.
+        const bool no_roll = sc.Rt[2] == 0.0f;
+        for (uint32_t q = tid; q * 4 < sc.npix; q += NT) {
+            const uint32_t p0 = q * 4;
+            const uint32_t j = __umulhi(p0, sc.magicW);
+            const uint32_t i0 = p0 - j * sc.W;
+            const float cyj = cxcy[sc.W + j];
+            const float rx = __builtin_fmaf(sc.Up[0], cyj, sc.Fw[0]);
+            const float ry = __builtin_fmaf(sc.Up[1], cyj, sc.Fw[1]);
+            const float rz = __builtin_fmaf(sc.Up[2], cyj, sc.Fw[2]);
+            const float4 cx4 = *reinterpret_cast<const float4*>(cxcy + i0);
+            const float cxs[4] = {cx4.x, cx4.y, cx4.z, cx4.w};
+            uint32_t vid[3] = {0u, 0u, 0u};
+            if (rc.mode == PXR_DISTRACT_VIDEO) {
+                const uint32_t* vsrc = reinterpret_cast<const uint32_t*>(rc.vframe) + q * 3;
+                vid[0] = vsrc[0];
+                vid[1] = vsrc[1];
+                vid[2] = vsrc[2];
+            }
+            const uint32_t vb[4] = {vid[0] & 0xFFFFFFu, (vid[0] >> 24) | ((vid[1] & 0xFFFFu) << 8),
+                                    (vid[1] >> 16) | ((vid[2] & 0xFFu) << 16), vid[2] >> 8};
+            float tg_row = 0.0f;
+            u64 gkey_row = 0ull;
+            if (no_roll) gkey_row = ground_key(sc, rc, -rz, tg_row);  // fma(+-0, cx, rz) == rz
+            uint32_t rgb[4], low[4];
 #pragma unroll
-        for (int k = 0; k < PX; ++k) {
-            const uint32_t p = p0 + k;
-            u64 key = keys[p];
-            // ground: ray through the pixel centre against z = 0
+            for (int k = 0; k < 4; ++k) {
+                float tg = tg_row;
+                u64 gkey = gkey_row;
+                if (!no_roll) gkey = ground_key(sc, rc, -__builtin_fmaf(sc.Rt[2], cxs[k], rz), tg);
+                const float dwx = __builtin_fmaf(sc.Rt[0], cxs[k], rx);
+                const float dwy = __builtin_fmaf(sc.Rt[1], cxs[k], ry);
+                rgb[k] = resolve_pixel(sc, rc, body, keys[p0 + k], gkey, tg, dwx, dwy, vb[k], low[k]);
+            }
+            struct alignas(4) U3 {
+                uint32_t a, b, c;
+            };
+            *reinterpret_cast<U3*>(reinterpret_cast<uint32_t*>(out) + q * 3) =
+                U3{rgb[0] | (rgb[1] << 24), (rgb[1] >> 8) | (rgb[2] << 16), (rgb[2] >> 16) | (rgb[3] << 8)};
+            if (out_ids)
+                reinterpret_cast<uint4*>(out_ids)[q] =
+                    make_uint4(0xFFFFFFFFu - low[0], 0xFFFFFFFFu - low[1], 0xFFFFFFFFu - low[2], 0xFFFFFFFFu - low[3]);
+        }
+    } else {
+        // any image shape: one pixel per lane, byte stores
+        for (uint32_t p = tid; p < sc.npix; p += NT) {
+            const uint32_t j = __umulhi(p, sc.magicW);
+            const uint32_t i = p - j * sc.W;
             const float cxi = cxcy[i], cyj = cxcy[sc.W + j];
             const float dwx = __builtin_fmaf(sc.Rt[0], cxi, __builtin_fmaf(sc.Up[0], cyj, sc.Fw[0]));
             const float dwy = __builtin_fmaf(sc.Rt[1], cxi, __builtin_fmaf(sc.Up[1], cyj, sc.Fw[1]));
             const float dwz = __builtin_fmaf(sc.Rt[2], cxi, __builtin_fmaf(sc.Up[2], cyj, sc.Fw[2]));
-            const float ndz = -dwz;
-            float tg = 0.0f;
-            if (ground_ok && ndz > 0.0f) {
-                tg = eye_z / ndz;
-                if (tg >= sc.z_near && tg <= sc.z_far) {
-                    const float dg = (sc.z_near * ndz) * inv_ez;
-                    const u64 gkey = ((u64)__float_as_uint(dg) << 32) | 1ull;
-                    key = key > gkey ? key : gkey;
-                }
+            float tg;
+            const u64 gkey = ground_key(sc, rc, -dwz, tg);
+            uint32_t vbytes = 0;
+            if (rc.mode == PXR_DISTRACT_VIDEO) {
+                const uint8_t* v = rc.vframe + (size_t)p * 3;
+                vbytes = (uint32_t)v[0] | ((uint32_t)v[1] << 8) | ((uint32_t)v[2] << 16);
             }
-            const uint32_t low = (uint32_t)key;
-            float c[3];
-            if (low == 0u) {
-                c[0] = sc.bg[0];
-                c[1] = sc.bg[1];
-                c[2] = sc.bg[2];
-            } else if (low == 1u) {
-                const float wx = __builtin_fmaf(tg, dwx, eye_x);
-                const float wy = __builtin_fmaf(tg, dwy, eye_y);
-                const float ux = sc.cell_is_one ? wx : wx / sc.cell;
-                const float uy = sc.cell_is_one ? wy : wy / sc.cell;
-                const int par = ((int)__builtin_floorf(ux) + (int)__builtin_floorf(uy)) & 1;
-                c[0] = c[1] = c[2] = par ? sc.gs[1] : sc.gs[0];
-            } else {
-                const uint32_t g = 0xFFFFFFFFu - low;
-                const float4 ns = reinterpret_cast<const float4*>(sc.tri_shade)[g];
-                const float* o = body + (sc.tri_idx[g * 2 + 1] >> 16) * kBodyStride;
-                float I = __builtin_fmaf(ns.x, o[12], __builtin_fmaf(ns.y, o[13], ns.z * o[14]));
-                I = I > 0.0f ? I : 0.0f;
-                const float sh = __builtin_fmaf(sc.diffuse, I, sc.ambient);
-#pragma unroll
-                for (int ch = 0; ch < 3; ++ch) {
-                    const float v = (o[20 + ch] * ns.w) * sh;
-                    c[ch] = v < 1.0f ? v : 1.0f;
-                }
-            }
-            if (mode == PXR_DISTRACT_COLOR) {
-#pragma unroll
-                for (int ch = 0; ch < 3; ++ch) {
-                    float v = __builtin_fmaf(c[ch], scale[ch], offs[ch]);
-                    v = v > 0.0f ? v : 0.0f;
-                    c[ch] = v < 1.0f ? v : 1.0f;
-                }
-            } else if (mode == PXR_DISTRACT_VIDEO && low <= 1u) {
-#pragma unroll
-                for (int ch = 0; ch < 3; ++ch) {
-                    uint32_t byte;
-                    if (PX == 4) {
-                        const int bi = k * 3 + ch;
-                        byte = (vid[bi >> 2] >> ((bi & 3) * 8)) & 0xFFu;
-                    } else {
-                        byte = vframe[(size_t)p * 3 + ch];
-                    }
-                    const float vf = (float)byte * (1.0f / 255.0f);
-                    c[ch] = __builtin_fmaf(dc.alpha, vf - c[ch], c[ch]);
-                }
-            }
-#pragma unroll
-            for (int ch = 0; ch < 3; ++ch) {
-                const uint32_t u8 = (uint32_t)(int)__builtin_floorf(__builtin_fmaf(c[ch], 255.0f, 0.5f)) & 0xFFu;
-                if (PX == 4) {
-                    const int bi = k * 3 + ch;
-                    packed[bi >> 2] |= u8 << ((bi & 3) * 8);
-                } else {
-                    out[(size_t)p * 3 + ch] = (uint8_t)u8;
-                }
-            }
-            idv[k] = 0xFFFFFFFFu - low;
-            if (++i == sc.W) {
-                i = 0;
-                ++j;
-            }
-        }
-        if (PX == 4) {
-            uint32_t* dst = reinterpret_cast<uint32_t*>(out) + q * 3;
-            struct alignas(4) U3 {
-                uint32_t a, b, c;
-            };
-            *reinterpret_cast<U3*>(dst) = U3{packed[0], packed[1], packed[2]};
-            if (out_ids) reinterpret_cast<uint4*>(out_ids)[q] = make_uint4(idv[0], idv[1], idv[2], idv[3]);
-        } else {
-            if (out_ids) out_ids[p0] = idv[0];
+            uint32_t low;
+            const uint32_t rgb = resolve_pixel(sc, rc, body, keys[p], gkey, tg, dwx, dwy, vbytes, low);
+            out[(size_t)p * 3 + 0] = (uint8_t)(rgb & 0xFFu);
+            out[(size_t)p * 3 + 1] = (uint8_t)((rgb >> 8) & 0xFFu);
+            out[(size_t)p * 3 + 2] = (uint8_t)(rgb >> 16);
+            if (out_ids) out_ids[p] = 0xFFFFFFFFu - low;
         }
     }
+    PXR_PHASE_MARK(6);
 }
 
 template <int NT, int PX>
@@ -521,6 +704,17 @@ int prepare_one(uint32_t lds_bytes, std::string& err) {
 
 }  // namespace
 
+#ifdef PXR_PHASE_TIMING
+extern "C" int pxr_debug_phase_cycles(unsigned long long* out, int reset) {
+    if (out && hipMemcpyFromSymbol(out, HIP_SYMBOL(g_phase_cycles), sizeof(g_phase_cycles)) != hipSuccess) return 1;
+    if (reset) {
+        unsigned long long zero[8] = {0};
+        if (hipMemcpyToSymbol(HIP_SYMBOL(g_phase_cycles), zero, sizeof(zero)) != hipSuccess) return 1;
+    }
+    return 0;
+}
+#endif
+
 int prepare_kernels(uint32_t lds_bytes, std::string& err) {
     // The attribute is a per-kernel cap, not a per-launch size: always raise it
     // to the whole 160 KB so that scenes of different sizes can coexist.
@@ -529,9 +723,11 @@ int prepare_kernels(uint32_t lds_bytes, std::string& err) {
     int rc;
     if ((rc = prepare_one<256, 4>(cap, err))) return rc;
     if ((rc = prepare_one<512, 4>(cap, err))) return rc;
+    if ((rc = prepare_one<768, 4>(cap, err))) return rc;
     if ((rc = prepare_one<1024, 4>(cap, err))) return rc;
     if ((rc = prepare_one<256, 1>(cap, err))) return rc;
     if ((rc = prepare_one<512, 1>(cap, err))) return rc;
+    if ((rc = prepare_one<768, 1>(cap, err))) return rc;
     if ((rc = prepare_one<1024, 1>(cap, err))) return rc;
     return PXR_OK;
 }
@@ -540,17 +736,18 @@ int launch_render(const SceneConsts& sc, const DistractConsts& dc, const float* 
                   uint32_t n_frames, uint32_t S, uint32_t step0, uint32_t env0, uint8_t* d_frames, uint32_t* d_ids,
                   uint32_t block_threads, void* stream, std::string& err) {
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    // four pixels per lane need whole 12-byte groups and dword-aligned frames
-    const bool quad = (sc.npix % 4u) == 0u;
+    // four pixels per lane: they must share a row and frames must stay dword-aligned
+    const bool quad = (sc.W % 4u) == 0u;
 #define PXR_LAUNCH(NT)                                                                                                   \
     return quad ? launch_one<NT, 4>(sc, dc, d_poses, d_shapes, n_frames, S, step0, env0, d_frames, d_ids, st, err)       \
                 : launch_one<NT, 1>(sc, dc, d_poses, d_shapes, n_frames, S, step0, env0, d_frames, d_ids, st, err)
     switch (block_threads) {
         case 256: PXR_LAUNCH(256);
         case 512: PXR_LAUNCH(512);
+        case 768: PXR_LAUNCH(768);
         case 1024: PXR_LAUNCH(1024);
         default:
-            err = "block_threads must be 256, 512 or 1024";
+            err = "block_threads must be 256, 512, 768 or 1024";
             return PXR_ERR_INVALID_ARG;
     }
 #undef PXR_LAUNCH

@@ -7,6 +7,7 @@
 // Numerical contract: every table is evaluated in double from the float
 // inputs with libm, each entry rounded to fp32 exactly once.
 
+#include <algorithm>
 #include <cmath>
 #include <cstring>
 
@@ -149,6 +150,45 @@ void tessellate_box(BodyMesh& m, uint32_t n) {
     }
 }
 
+// Binning works on pairs of triangles that share an edge (a quad of a band, a
+// box cell, two neighbouring fan triangles): one box test over four vertices
+// settles both.  Consecutive triangles t, t+1 of a body are paired when t+1
+// runs along one of t's edges in the opposite direction; the entry is
+// (q0,q1,q2,q3) with t = {q0,q1,q2}, t+1 = {q0,q2,q3} as vertex sets.  A
+// triangle without such a neighbour stands alone (q3 = q2).
+void pair_triangles(const BodyMesh& m, uint32_t vbase, uint32_t tbase, std::vector<uint32_t>& tbl) {
+    const uint32_t nt = (uint32_t)m.mul.size();
+    uint32_t t = 0;
+    while (t < nt) {
+        const uint32_t* A = &m.idx[3 * t];
+        bool paired = false;
+        if (t + 1 < nt) {
+            const uint32_t* B = &m.idx[3 * (t + 1)];
+            for (int eb = 0; eb < 3 && !paired; ++eb) {
+                const uint32_t x = B[eb], y = B[(eb + 1) % 3], b3 = B[(eb + 2) % 3];
+                for (int ea = 0; ea < 3; ++ea) {
+                    if (A[ea] == y && A[(ea + 1) % 3] == x) {
+                        const uint32_t a3 = A[(ea + 2) % 3];
+                        tbl.push_back((vbase + x) | ((vbase + a3) << 16));
+                        tbl.push_back((vbase + y) | ((vbase + b3) << 16));
+                        tbl.push_back((tbase + t) | ((tbase + t + 1) << 16));
+                        paired = true;
+                        break;
+                    }
+                }
+            }
+        }
+        if (paired) {
+            t += 2;
+        } else {
+            tbl.push_back((vbase + A[0]) | ((vbase + A[1]) << 16));
+            tbl.push_back((vbase + A[2]) | ((vbase + A[2]) << 16));
+            tbl.push_back((tbase + t) | (kNoTriangle << 16));
+            t += 1;
+        }
+    }
+}
+
 bool finite_all(const float* p, int n) {
     for (int i = 0; i < n; ++i)
         if (!std::isfinite(p[i])) return false;
@@ -226,7 +266,7 @@ int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
             return PXR_ERR_INVALID_ARG;
         }
         const uint32_t nv = (uint32_t)m.pos.size(), nt = (uint32_t)m.mul.size();
-        if (vbase + nv > 65535u || tbase + nt > 65535u) {
+        if (vbase + nv > 65535u || tbase + nt >= kNoTriangle) {
             err = "scene exceeds 65535 vertices or triangles";
             return PXR_ERR_UNSUPPORTED;
         }
@@ -245,6 +285,7 @@ int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
             hs.tri_shade.push_back((float)m.nrm[t].z);
             hs.tri_shade.push_back(m.mul[t]);
         }
+        pair_triangles(m, vbase, tbase, hs.pair_tbl);
         for (int i = 0; i < 4; ++i) hs.body_const[(size_t)b * 8 + i] = bd.shape[i];
         for (int i = 0; i < 3; ++i) hs.body_const[(size_t)b * 8 + 4 + i] = bd.rgb[i];
         vbase += nv;
@@ -252,6 +293,7 @@ int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
     }
     c.V = vbase;
     c.T = tbase;
+    c.P = (uint32_t)(hs.pair_tbl.size() / 3);
 
     // ---- camera: forward looks from the eye to the root, right = forward x up
     const Vec3d off{d.cam_offset[0], d.cam_offset[1], d.cam_offset[2]};
@@ -312,22 +354,24 @@ int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
     // ---- LDS carve-up of one frame workgroup
     auto align = [](uint32_t x, uint32_t a) { return (x + a - 1) / a * a; };
     uint32_t o = 0;
-    c.lds_keys = o;
-    o += c.npix * 8;
+    c.lds_keys = o;  // 16-byte aligned regions first
+    o += align(std::max(c.npix * 8, c.P * 2), 16);
+    c.lds_cxcy = o;
+    o += align((c.W + c.H) * 4, 16);
+    c.lds_misc = o;
+    o += 64 * 4;
+    c.lds_body = o;
+    o += c.K * kBodyStride * 4;
     c.lds_vx = o;
     o += c.V * 4;
     c.lds_vy = o;
     o += c.V * 4;
     c.lds_vd = o;
     o += c.V * 4;
-    c.lds_body = o;
-    o += c.K * kBodyStride * 4;
-    c.lds_cxcy = o;
-    o += (c.W + c.H) * 4;
-    c.lds_misc = o;
-    o += 32 * 4;
     c.lds_list = o;
-    o += align(c.T * 2, 8);
+    o += align(c.T * 2, 4);
+    c.lds_large = o;
+    o += align(c.T * 2, 4);
     c.lds_total = align(o, 16);
     if (c.lds_total > 160u * 1024u) {
         err = "scene needs " + std::to_string(c.lds_total) + " bytes of LDS per frame; the limit is 163840";

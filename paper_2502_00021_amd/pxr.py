@@ -65,7 +65,7 @@ def lib():
         L.pxr_render_batch.argtypes = [vp, vp, vp, u32, u32, u32, u32, vp, vp, vp]
         L.pxr_scene_info.argtypes = [vp, vp, vp, vp, vp]
         L.pxr_set_block_threads.argtypes = [vp, u32]
-        L.pxr_host_tables.argtypes = [C.POINTER(SceneDesc), vp, vp, vp, vp, vp, vp, vp]
+        L.pxr_host_tables.argtypes = [C.POINTER(SceneDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.pxr_last_error.restype = C.c_char_p
         for name in ("pxr_create_scene", "pxr_destroy_scene", "pxr_apply_distractor", "pxr_render_batch",
                      "pxr_scene_info", "pxr_set_block_threads", "pxr_host_tables"):
@@ -109,16 +109,18 @@ def make_scene_desc(desc):
 def host_tables(desc):
     """pxr_host_tables: the scene builder's tables as numpy arrays (no device needed)."""
     d, keep = make_scene_desc(desc)
-    nv, nt = C.c_uint32(), C.c_uint32()
-    _check(lib().pxr_host_tables(C.byref(d), C.byref(nv), C.byref(nt), None, None, None, None, None))
-    V, T = nv.value, nt.value
+    nv, nt, npair = C.c_uint32(), C.c_uint32(), C.c_uint32()
+    _check(lib().pxr_host_tables(C.byref(d), C.byref(nv), C.byref(nt), None, None, None, None, None,
+                                 C.byref(npair), None))
+    V, T, P = nv.value, nt.value, npair.value
+    pt = np.empty((P, 3), np.uint32)
     vt = np.empty((V, 4), np.float32)
     ti = np.empty((T, 2), np.uint32)
     ts = np.empty((T, 4), np.float32)
     cxcy = np.empty(d.width + d.height, np.float32)
     consts = np.empty(16, np.float32)
     _check(lib().pxr_host_tables(C.byref(d), None, None, vt.ctypes.data, ti.ctypes.data, ts.ctypes.data,
-                                 cxcy.ctypes.data, consts.ctypes.data))
+                                 cxcy.ctypes.data, consts.ctypes.data, None, pt.ctypes.data))
     del keep
     code = vt[:, 3].copy().view(np.uint32)
     return dict(V=V, T=T, uverts=np.concatenate([vt[:, :3], ((code & 3).astype(np.float32) - 1.0)[:, None]], axis=1),
@@ -127,7 +129,9 @@ def host_tables(desc):
                 tri_body=ti[:, 1] >> 16, normals=ts[:, :3].copy(), mul=ts[:, 3].copy(),
                 cx=cxcy[:d.width].copy(), cy=cxcy[d.width:].copy(),
                 Rv=consts[:9].reshape(3, 3).copy(), f=float(consts[9]), gs=consts[10:12].copy(), l=consts[12:15].copy(),
-                lds_bytes=int(consts[15]))
+                lds_bytes=int(consts[15]),
+                pair_quads=np.stack([pt[:, 0] & 0xFFFF, pt[:, 0] >> 16, pt[:, 1] & 0xFFFF, pt[:, 1] >> 16], axis=1),
+                pair_tris=np.stack([pt[:, 2] & 0xFFFF, pt[:, 2] >> 16], axis=1))
 
 
 class Scene:

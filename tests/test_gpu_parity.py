@@ -75,7 +75,7 @@ def oracle_render(orc, w, step0=0, env0=0):
 # ---------------------------------------------------------------- the five configurations
 
 @pytest.mark.parametrize("cfg,B,threads", [(1, 16, 256), (1, 16, 1024), (2, 48, 512), (2, 24, 256), (3, 40, 512),
-                                           (3, 24, 1024), (4, 24, 1024), (4, 16, 512), (5, 20, 512), (5, 12, 256)])
+                                           (3, 24, 1024), (3, 17, 768), (4, 24, 1024), (4, 16, 512), (5, 20, 512), (5, 12, 256)])
 def test_configs_match_oracle(torch, pxr, orc, cfg, B, threads):
     w = wl.make(cfg, B=B)
     got = gpu_render(torch, pxr, w, step0=3, env0=11, threads=threads)
@@ -92,7 +92,7 @@ def test_default_block_threads_and_info(torch, pxr, orc):
         info = sc.info()
         o = orc.Scene(w["desc"])
         assert (info["n_verts"], info["n_tris"]) == (o.V, o.T)
-        assert info["block_threads"] in (256, 512, 1024) and info["lds_bytes"] <= 160 * 1024
+        assert info["block_threads"] in (256, 512, 768, 1024) and info["lds_bytes"] <= 160 * 1024
         got = gpu_render(torch, pxr, w, scene=sc)
         assert_parity(got, oracle_render(orc, w))
         sc.close()
@@ -120,7 +120,7 @@ def test_determinism_and_slice_and_step_split(torch, pxr, orc):
 
 def test_block_size_does_not_change_output(torch, pxr):
     w = wl.make(4, B=20)
-    outs = [gpu_render(torch, pxr, w, threads=t) for t in (256, 512, 1024)]
+    outs = [gpu_render(torch, pxr, w, threads=t) for t in (256, 512, 768, 1024)]
     for o in outs[1:]:
         assert np.array_equal(o["frames"], outs[0]["frames"]) and np.array_equal(o["ids"], outs[0]["ids"])
 
@@ -302,3 +302,33 @@ def test_render_argument_errors(torch, pxr):
     torch.cuda.synchronize()
     assert f.shape == (4, 1, 32, 32, 3)
     sc.close()
+
+
+# ---------------------------------------------------------------- full benchmark sizes, sampled
+
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_full_size_batches_sampled_against_oracle(torch, pxr, orc, cfg):
+    """The configurations at their full batch size, in the launch configuration bench.py times
+    (library-default workgroup size, ids off for the timed buffer), checked on sampled environments
+    the oracle renders one by one, plus run-to-run determinism of the whole output."""
+    w = wl.make(cfg)
+    B, S = w["poses"].shape[:2]
+    scene = pxr.Scene(w["desc"])
+    _bind(torch, scene, w["distractor"])
+    poses = torch.from_numpy(w["poses"]).cuda()
+    shapes = None if w["shapes"] is None else torch.from_numpy(w["shapes"]).cuda()
+    frames, _ = scene.render_batch(poses, shapes, step0=5, env0=0)
+    again, ids = scene.render_batch(poses, shapes, step0=5, env0=0, want_ids=True)
+    torch.cuda.synchronize()
+    assert torch.equal(frames, again)
+    rng = np.random.default_rng(cfg)
+    chunk = (B * S + 7) // 8 // S  # environments per XCD run of the workgroup renumbering
+    picks = sorted(set([0, 1, B - 1, B - 2, B // 2] + [min(B - 1, k * chunk + d) for k in range(1, 8) for d in (-1, 0)]
+                       + [int(e) for e in rng.integers(0, B, 24)]))
+    o = orc.Scene(w["desc"])
+    for e in picks:
+        sh = None if w["shapes"] is None else w["shapes"][e:e + 1]
+        ref = o.render(w["poses"][e:e + 1], sh, step0=5, env0=e, distractor=w["distractor"])
+        got = dict(frames=frames[e:e + 1].cpu().numpy(), ids=pxr.ids_to_numpy(ids[e:e + 1]))
+        assert_parity(got, ref)
+    scene.close()

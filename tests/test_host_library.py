@@ -53,6 +53,26 @@ def test_tables_for_odd_tessellations(orc):
         assert np.array_equal(t[k], cam[k]), k
 
 
+@pytest.mark.parametrize("cfg", [1, 3, 5])
+def test_pair_table_covers_every_triangle_once(cfg):
+    """Binning table: each triangle appears in exactly one entry, and an entry's quad holds its triangles' vertices."""
+    desc = wl.make(cfg, B=1)["desc"]
+    if cfg == 1:  # odd longitude counts leave unpaired fan triangles
+        desc["bodies"] = [dict(b, n_lon=7, n_lat=3) for b in desc["bodies"]] + [wl.box(0.1, 0.1, 0.1, (0.5, 0.5, 0.5), 3)]
+    t = pxr.host_tables(desc)
+    tris, quads, pt = t["tris"], t["pair_quads"], t["pair_tris"]
+    seen = np.concatenate([pt[:, 0], pt[pt[:, 1] != 0xFFFF, 1]])
+    assert np.array_equal(np.sort(seen), np.arange(t["T"]))
+    for (q0, q1, q2, q3), (ta, tb) in zip(quads, pt):
+        assert set(tris[ta]) == {q0, q1, q2}
+        if tb != 0xFFFF:
+            assert tb == ta + 1 and set(tris[tb]) == {q0, q2, q3} and len({q0, q1, q2, q3}) == 4
+        else:
+            assert q3 == q2
+    paired = (pt[:, 1] != 0xFFFF).sum()
+    assert paired >= 0.45 * t["T"] if cfg != 1 else paired > 0
+
+
 def _expect(desc, code):
     with pytest.raises(pxr.PxrError) as ei:
         pxr.host_tables(desc)
@@ -91,7 +111,7 @@ def test_null_arguments_are_errors_not_crashes():
     assert L.pxr_render_batch(None, None, None, 1, 1, 0, 0, None, None, None) == pxr.ERR_INVALID_ARG
     assert L.pxr_scene_info(None, None, None, None, None) == pxr.ERR_INVALID_ARG
     assert L.pxr_set_block_threads(None, 256) == pxr.ERR_INVALID_ARG
-    assert L.pxr_host_tables(None, None, None, None, None, None, None, None) == pxr.ERR_INVALID_ARG
+    assert L.pxr_host_tables(None, None, None, None, None, None, None, None, None, None) == pxr.ERR_INVALID_ARG
     assert L.pxr_destroy_scene(None) == pxr.OK
 
 
