@@ -19,9 +19,11 @@ constexpr int32_t kRejectedX = INT32_MIN;
 // bounding box (both fixed-point extents must also be below 2^15):
 //   tiny  <= kTinyMaxPixels   one lane, at most two loop trips
 //   small <= kSmallMaxPixels  one lane
-//   large otherwise           a whole wavefront, one pixel per lane
+//   mid   <= kMidMaxPixels    eight lanes, rows dealt round-robin
+//   large otherwise           a whole wavefront, one row per lane
 constexpr uint32_t kTinyMaxPixels = 2;
-constexpr uint32_t kSmallMaxPixels = 16;
+constexpr uint32_t kSmallMaxPixels = 12;
+constexpr uint32_t kMidMaxPixels = 96;
 constexpr uint32_t kNoTriangle = 0xFFFFu;
 
 // Per-body record kept in LDS for the duration of one frame (floats).
@@ -55,7 +57,7 @@ struct SceneConsts {
     const float* body_const;  // [K][8]  shape a,b,c,h ; rgb r,g,b,0
     const float* cxcy;        // [W+H]   pixel-centre ray slopes
     // LDS carve-up (byte offsets into the dynamic segment)
-    // lds_keys doubles as the surviving-pair list (u16[P]) before the raster phase clears it
+    // the lds_keys region first holds the per-vertex cell codes (u32[V]) and the candidate list (u16[T])
     uint32_t lds_keys, lds_vx, lds_vy, lds_vd, lds_body, lds_list, lds_large, lds_cxcy, lds_misc, lds_total;
 };
 

@@ -10,15 +10,18 @@
 //
 // Phases of one workgroup (barriers between them):
 //   0  per-body transforms, per-frame draws and the three non-triangle colours
-//   1  instancing: template vertex -> view space -> snapped fixed point
-//   2a binning, coarse: one lane per PAIR of edge-sharing triangles, one
-//      bounding-box / pixel-centre test for both; surviving pairs are
-//      compacted wave-wide (ballot + mbcnt) into a list in LDS
-//   2b binning, exact: one lane per triangle of a surviving pair: cull, own
-//      pixel range, then compaction into three bins by candidate-pixel count
-//      (tiny / small: one lane each, large: a whole wave)
-//   3  raster: integer edge functions, top-left rule, float reversed depth,
-//      64-bit LDS atomic max on (depth bits << 32 | ~triangle id)
+//   1  instancing: template vertex -> view space -> snapped fixed point, plus
+//      a per-vertex "cell code" saying between which pixel centres it lies
+//   2a binning, coarse: one lane per PAIR of edge-sharing triangles; from the
+//      cell codes alone (xor / or, no coordinates) decide per triangle whether
+//      its bounding box can hold a pixel centre; candidates are compacted
+//      wave-wide (ballot + mbcnt) into a list in LDS
+//   2b binning, exact: one lane per candidate: exact area sign, pixel range,
+//      then compaction into four bins by candidate-pixel count
+//   3  raster: bins are walked by 1, 1, 8 or 64 lanes per triangle (rows are
+//      dealt round-robin to a triangle's lanes); integer edge functions,
+//      top-left rule, float reversed depth, 64-bit LDS atomic max on
+//      (depth bits << 32 | ~triangle id)
 //   4  resolve: ground ray, id -> flat Lambert colour, distractor, uint8 pack,
 //      coalesced 12-byte stores
 //
@@ -93,88 +96,57 @@ __device__ __forceinline__ void z_test(u64* keys, uint32_t pix, float depth, uin
     atomicMax(&keys[pix], key);
 }
 
-// One lane walks the (at most kSmallMaxPixels) pixel centres of a small
-// triangle.  All differences fit in 16 bits, so 24-bit multiplies are exact.
-__device__ __forceinline__ void raster_small(const TriSetup& s, uint32_t tri, uint32_t W, u64* keys) {
+// Exact products of coordinate differences: 24-bit multiplies when both
+// fixed-point extents of the triangle are below 2^15 (every product < 2^30),
+// 64-bit otherwise (coordinates reach 2^22, products 2^46).
+template <typename I>
+__device__ __forceinline__ I emul(int a, int b);
+template <>
+__device__ __forceinline__ int emul<int>(int a, int b) {
+    return __mul24(a, b);
+}
+template <>
+__device__ __forceinline__ long long emul<long long>(int a, int b) {
+    return (long long)a * (long long)b;
+}
+
+// Walk rows j0 + r, j0 + r + 2^shift, ... of a triangle's candidate pixel range.
+// Edge functions carry their fill-rule bias and are stepped incrementally; a
+// pixel centre is covered when all three are >= 0.
+template <typename I>
+__device__ __forceinline__ void raster_rows(const TriSetup& s, uint32_t tri, uint32_t W, u64* keys, int r, int shift) {
+    int j = s.j0 + r;
+    if (j > s.j1) return;
     const int dx_ab = s.bx - s.ax, dy_ab = s.by - s.ay;
     const int dx_bc = s.cx - s.bx, dy_bc = s.cy - s.by;
     const int dx_ca = s.ax - s.cx, dy_ca = s.ay - s.cy;
-    const int A2 = __mul24(dx_ab, s.cy - s.ay) - __mul24(dy_ab, s.cx - s.ax);
+    const I A2 = emul<I>(dx_ab, s.cy - s.ay) - emul<I>(dy_ab, s.cx - s.ax);
     const float invA = 1.0f / (float)A2;
-    const int b_ab = edge_bias(dx_ab, dy_ab), b_bc = edge_bias(dx_bc, dy_bc), b_ca = edge_bias(dx_ca, dy_ca);
-    const int px0 = (s.i0 << 8) + 128, py0 = (s.j0 << 8) + 128;
-    int r_ab = __mul24(dx_ab, py0 - s.ay) - __mul24(dy_ab, px0 - s.ax);
-    int r_bc = __mul24(dx_bc, py0 - s.by) - __mul24(dy_bc, px0 - s.bx);
-    int r_ca = __mul24(dx_ca, py0 - s.cy) - __mul24(dy_ca, px0 - s.cx);
-    for (int j = s.j0; j <= s.j1; ++j) {
-        int e_ab = r_ab, e_bc = r_bc, e_ca = r_ca;
+    const I b_ab = edge_bias(dx_ab, dy_ab), b_bc = edge_bias(dx_bc, dy_bc), b_ca = edge_bias(dx_ca, dy_ca);
+    const int px0 = (s.i0 << 8) + 128, py = (j << 8) + 128;
+    I f_ab = emul<I>(dx_ab, py - s.ay) - emul<I>(dy_ab, px0 - s.ax) + b_ab;
+    I f_bc = emul<I>(dx_bc, py - s.by) - emul<I>(dy_bc, px0 - s.bx) + b_bc;
+    I f_ca = emul<I>(dx_ca, py - s.cy) - emul<I>(dy_ca, px0 - s.cx) + b_ca;
+    const I sx_ab = (I)dy_ab << 8, sx_bc = (I)dy_bc << 8, sx_ca = (I)dy_ca << 8;
+    const I sy_ab = (I)dx_ab << (8 + shift), sy_bc = (I)dx_bc << (8 + shift), sy_ca = (I)dx_ca << (8 + shift);
+    for (;;) {
+        I e_ab = f_ab, e_bc = f_bc, e_ca = f_ca;
         uint32_t pix = (uint32_t)j * W + (uint32_t)s.i0;
         for (int i = s.i0; i <= s.i1; ++i, ++pix) {
-            if (((e_ab + b_ab) | (e_bc + b_bc) | (e_ca + b_ca)) >= 0) {
-                const float beta = (float)e_ca * invA, gamma = (float)e_ab * invA;
+            if ((e_ab | e_bc | e_ca) >= 0) {
+                const float beta = (float)(e_ca - b_ca) * invA, gamma = (float)(e_ab - b_ab) * invA;
                 z_test(keys, pix, __builtin_fmaf(beta, s.dDb, __builtin_fmaf(gamma, s.dDc, s.Da)), tri);
             }
-            e_ab -= dy_ab << 8;
-            e_bc -= dy_bc << 8;
-            e_ca -= dy_ca << 8;
+            e_ab -= sx_ab;
+            e_bc -= sx_bc;
+            e_ca -= sx_ca;
         }
-        r_ab += dx_ab << 8;
-        r_bc += dx_bc << 8;
-        r_ca += dx_ca << 8;
+        j += 1 << shift;
+        if (j > s.j1) break;  // (stepping past the last row could leave the exactly representable range)
+        f_ab += sy_ab;
+        f_bc += sy_bc;
+        f_ca += sy_ca;
     }
-}
-
-// A whole wavefront sweeps a large triangle in 8x8 pixel tiles, one pixel per
-// lane; extents below 2^15 allow exact 24-bit multiplies.
-__device__ __forceinline__ void raster_wave32(const TriSetup& s, uint32_t tri, uint32_t W, u64* keys, uint32_t lane) {
-    const int dx_ab = s.bx - s.ax, dy_ab = s.by - s.ay;
-    const int dx_bc = s.cx - s.bx, dy_bc = s.cy - s.by;
-    const int dx_ca = s.ax - s.cx, dy_ca = s.ay - s.cy;
-    const int A2 = __mul24(dx_ab, s.cy - s.ay) - __mul24(dy_ab, s.cx - s.ax);
-    const float invA = 1.0f / (float)A2;
-    const int b_ab = edge_bias(dx_ab, dy_ab), b_bc = edge_bias(dx_bc, dy_bc), b_ca = edge_bias(dx_ca, dy_ca);
-    const int li = (int)(lane & 7u), lj = (int)(lane >> 3);
-    for (int ty = s.j0 & ~7; ty <= s.j1; ty += 8)
-        for (int tx = s.i0 & ~7; tx <= s.i1; tx += 8) {
-            const int i = tx + li, j = ty + lj;
-            if (i < s.i0 || i > s.i1 || j < s.j0 || j > s.j1) continue;
-            const int px = (i << 8) + 128, py = (j << 8) + 128;
-            const int e_ab = __mul24(dx_ab, py - s.ay) - __mul24(dy_ab, px - s.ax);
-            const int e_bc = __mul24(dx_bc, py - s.by) - __mul24(dy_bc, px - s.bx);
-            const int e_ca = __mul24(dx_ca, py - s.cy) - __mul24(dy_ca, px - s.cx);
-            if (((e_ab + b_ab) | (e_bc + b_bc) | (e_ca + b_ca)) >= 0) {
-                const float beta = (float)e_ca * invA, gamma = (float)e_ab * invA;
-                z_test(keys, (uint32_t)j * W + (uint32_t)i, __builtin_fmaf(beta, s.dDb, __builtin_fmaf(gamma, s.dDc, s.Da)),
-                       tri);
-            }
-        }
-}
-
-// The same sweep with 64-bit edge functions (coordinates reach 2^22, products 2^46).
-__device__ __forceinline__ void raster_wave64(const TriSetup& s, uint32_t tri, uint32_t W, u64* keys, uint32_t lane) {
-    typedef long long i64;
-    const i64 dx_ab = s.bx - s.ax, dy_ab = s.by - s.ay;
-    const i64 dx_bc = s.cx - s.bx, dy_bc = s.cy - s.by;
-    const i64 dx_ca = s.ax - s.cx, dy_ca = s.ay - s.cy;
-    const i64 A2 = dx_ab * (i64)(s.cy - s.ay) - dy_ab * (i64)(s.cx - s.ax);
-    const float invA = 1.0f / (float)A2;
-    const i64 b_ab = edge_bias((int)dx_ab, (int)dy_ab), b_bc = edge_bias((int)dx_bc, (int)dy_bc),
-              b_ca = edge_bias((int)dx_ca, (int)dy_ca);
-    const int li = (int)(lane & 7u), lj = (int)(lane >> 3);
-    for (int ty = s.j0 & ~7; ty <= s.j1; ty += 8)
-        for (int tx = s.i0 & ~7; tx <= s.i1; tx += 8) {
-            const int i = tx + li, j = ty + lj;
-            if (i < s.i0 || i > s.i1 || j < s.j0 || j > s.j1) continue;
-            const i64 px = (i << 8) + 128, py = (j << 8) + 128;
-            const i64 e_ab = dx_ab * (py - s.ay) - dy_ab * (px - s.ax);
-            const i64 e_bc = dx_bc * (py - s.by) - dy_bc * (px - s.bx);
-            const i64 e_ca = dx_ca * (py - s.cy) - dy_ca * (px - s.cx);
-            if (((e_ab + b_ab) | (e_bc + b_bc) | (e_ca + b_ca)) >= 0) {
-                const float beta = (float)e_ca * invA, gamma = (float)e_ab * invA;
-                z_test(keys, (uint32_t)j * W + (uint32_t)i, __builtin_fmaf(beta, s.dDb, __builtin_fmaf(gamma, s.dDc, s.Da)),
-                       tri);
-            }
-        }
 }
 
 // Gather a triangle's snapped vertices and its clamped pixel-centre range.
@@ -204,28 +176,34 @@ __device__ __forceinline__ bool tri_gather(const SceneConsts& sc, uint32_t t, co
     return s.i0 <= s.i1 && s.j0 <= s.j1;
 }
 
-__device__ __forceinline__ void tri_depths(TriSetup& s, const float* vd, uint32_t v0, uint32_t v1, uint32_t v2) {
+// Raster one binned triangle with lane `r` of the 2^shift lanes that share it.
+__device__ __forceinline__ void raster_binned(const SceneConsts& sc, uint32_t t, const int* vx, const int* vy,
+                                              const float* vd, u64* keys, int r, int shift) {
+    TriSetup s;
+    uint32_t v0, v1, v2;
+    bool small_extent;
+    tri_gather(sc, t, vx, vy, s, v0, v1, v2, small_extent);
     s.Da = vd[v0];
     s.dDb = vd[v2] - s.Da;
     s.dDc = vd[v1] - s.Da;
+    if (small_extent)
+        raster_rows<int>(s, t, sc.W, keys, r, shift);
+    else
+        raster_rows<long long>(s, t, sc.W, keys, r, shift);
 }
 
-// Wave-wide stream compaction: lanes with `pred` append `value` to a u16 list.
-// `dir` = +1 grows the list upwards from `origin`, -1 downwards.  Must be
-// reached by every lane of the wave (it is, the callers' loops have uniform
-// trip counts).  One LDS atomic per wave.
-__device__ __forceinline__ void wave_append(bool pred, uint32_t value, uint32_t* counter, uint16_t* list, int origin, int dir,
-                                            uint32_t lane) {
-    const u64 m = __ballot(pred);
-    if (m) {
-        uint32_t base = 0;
-        if (lane == 0) base = atomicAdd(counter, (uint32_t)__popcll(m));
-        base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
-        if (pred) {
-            const uint32_t rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-            list[origin + dir * (int)(base + rank)] = (uint16_t)value;
-        }
-    }
+// Per-axis cell code of a snapped coordinate for an image of n pixels:
+// 2g = strictly between pixel centres g-1 and g, 2c+1 = exactly on centre c,
+// clamped to [0, 2n] (0 = left of centre 0, 2n = right of centre n-1).  A set
+// of points has no pixel centre within its extent along this axis iff all
+// codes are equal and even.
+__device__ __forceinline__ uint32_t cell_code(int x, int n) {
+    const int f = ((x - 128) >> 8) + ((x + 127) >> 8) + 1;
+    return (uint32_t)min(max(f, 0), 2 * n);
+}
+
+__device__ __forceinline__ uint32_t lanes_below(u64 m) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
 }
 
 __device__ __forceinline__ uint32_t quantise(float c) {
@@ -249,24 +227,25 @@ __device__ unsigned long long g_phase_cycles[8];
 #define PXR_PHASE_MARK(i)
 #endif
 
-struct FrameUniforms {  // written in phase 0 (lane 0) or by LDS atomics, read by all after a barrier
-    uint32_t n_pairs, n_tiny, n_small, n_large;
-    float scale[3], offs[3];
+struct FrameUniforms {  // written in phase 0 (one lane) or by LDS atomics, read by all after a barrier
+    u64 bins;           // four 16-bit counters: tiny | small << 16 | mid << 32 | large << 48
+    uint32_t n_cand;
     uint32_t video_frame;
+    float scale[3], offs[3];
     float base_col[3][3];     // background, ground grey 0, ground grey 1 after the colour distractor
     uint32_t base_packed[3];  // the same three, quantised: R | G<<8 | B<<16
 };
 
-// Everything phase 4 needs that is uniform over the frame, in registers.
+// Everything phase 4 needs that is uniform over the frame.
 struct ResolveCtx {
     float eye_x, eye_y, eye_z, inv_ez;
     bool ground_ok;
     uint32_t mode;
-    float scale[3], offs[3];
-    const float* base_col;        // LDS: [3][3] background, ground grey 0, ground grey 1 (after the colour distractor)
-    const uint32_t* base_packed;  // LDS: [3] the same, quantised
-    const uint8_t* vframe;
     float alpha;
+    float scale[3], offs[3];
+    const float* base_col;        // LDS [3][3]
+    const uint32_t* base_packed;  // LDS [3]
+    const uint8_t* vframe;
 };
 
 // Ground plane z = 0 along the pixel's ray: returns its z-test key (0 = miss)
@@ -335,13 +314,14 @@ __device__ __forceinline__ uint32_t resolve_pixel(const SceneConsts& sc, const R
 // Register budget: two 80 KB workgroups share a compute unit, so 1024-thread groups need all
 // 8 wave slots per SIMD (<= 64 VGPRs); the smaller groups may use more registers.
 template <int NT, int PX>
-__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ? 8 : (NT >= 768 ? 6 : 4)))) void render_kernel(const SceneConsts sc, const DistractConsts dc,
-                                                    const float* __restrict__ poses, const float* __restrict__ shapes,
-                                                    uint32_t S, uint32_t step0, uint32_t env0,
-                                                    uint8_t* __restrict__ frames, uint32_t* __restrict__ ids) {
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ? 8 : (NT >= 768 ? 6 : 4)))) void render_kernel(
+    const SceneConsts sc, const DistractConsts dc, const float* __restrict__ poses, const float* __restrict__ shapes,
+    uint32_t S, uint32_t step0, uint32_t env0, uint8_t* __restrict__ frames, uint32_t* __restrict__ ids) {
     extern __shared__ __align__(16) unsigned char lds[];
     u64* keys = reinterpret_cast<u64*>(lds + sc.lds_keys);
-    uint16_t* pair_list = reinterpret_cast<uint16_t*>(lds + sc.lds_keys);  // dead before the keys are cleared
+    // the key buffer's LDS holds the cell codes and the candidate list until the keys are cleared
+    uint32_t* vm = reinterpret_cast<uint32_t*>(lds + sc.lds_keys);
+    uint16_t* cand = reinterpret_cast<uint16_t*>(lds + sc.lds_keys + sc.V * 4);
     int* vx = reinterpret_cast<int*>(lds + sc.lds_vx);
     int* vy = reinterpret_cast<int*>(lds + sc.lds_vy);
     float* vd = reinterpret_cast<float*>(lds + sc.lds_vd);
@@ -349,7 +329,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     float* cxcy = reinterpret_cast<float*>(lds + sc.lds_cxcy);
     FrameUniforms* fu = reinterpret_cast<FrameUniforms*>(lds + sc.lds_misc);
     uint16_t* list = reinterpret_cast<uint16_t*>(lds + sc.lds_list);    // tiny bin grows up, small bin grows down
-    uint16_t* large = reinterpret_cast<uint16_t*>(lds + sc.lds_large);  // large bin
+    uint16_t* list2 = reinterpret_cast<uint16_t*>(lds + sc.lds_large);  // mid bin grows up, large bin grows down
 
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & 63u;
@@ -400,10 +380,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         for (int c = 0; c < 3; ++c) o[20 + c] = sc.body_const[tid * 8 + 4 + c];
     }
     if (tid == NT - 1) {  // a lane of the last wave: the first wave is busy with the bodies
-        fu->n_pairs = 0;
-        fu->n_tiny = 0;
-        fu->n_small = 0;
-        fu->n_large = 0;
+        fu->bins = 0ull;
+        fu->n_cand = 0;
         float scale[3] = {1.0f, 1.0f, 1.0f}, offs[3] = {0.0f, 0.0f, 0.0f};
         if (dc.mode == PXR_DISTRACT_COLOR) {
             uint32_t r[4];
@@ -451,7 +429,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     __syncthreads();
     PXR_PHASE_MARK(0);
 
-    // ---- phase 1: instancing + projection + snap (one lane per template vertex)
+    // ---- phase 1: instancing + projection + snap + cell code (one lane per template vertex)
     for (uint32_t v = tid; v < sc.V; v += NT) {
         const float4 tv = reinterpret_cast<const float4*>(sc.vtmpl)[v];
         const uint32_t code = __float_as_uint(tv.w);
@@ -468,118 +446,111 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         const float sy = __builtin_fmaf(-sc.f, pvy * inv, sc.halfH);
         const bool ok = (pvz >= sc.z_near) && (__builtin_fabsf(sx) <= 16384.0f) && (__builtin_fabsf(sy) <= 16384.0f);
         int X = kRejectedX, Y = 0;
+        uint32_t m = 0xFFFFFFFFu;  // a rejected vertex never lets a triangle be discarded early
         if (ok) {
             X = (int)__builtin_floorf(__builtin_fmaf(sx, 256.0f, 0.5f));
             Y = (int)__builtin_floorf(__builtin_fmaf(sy, 256.0f, 0.5f));
+            m = cell_code(X, (int)sc.W) | (cell_code(Y, (int)sc.H) << 16);
         }
         vx[v] = X;
         vy[v] = Y;
         vd[v] = sc.z_near * inv;
+        vm[v] = m;
     }
     __syncthreads();
     PXR_PHASE_MARK(1);
 
-    // ---- phase 2a: coarse binning, one lane per pair of edge-sharing triangles.
-    // A pair survives if its four vertices' box holds a pixel centre (or if a
-    // vertex was rejected: then the exact per-triangle test decides).
+    // ---- phase 2a: coarse binning, one lane per pair of edge-sharing triangles (q0,q1,q2), (q0,q2,q3).
+    // A triangle can hold a pixel centre only if, on both axes, its vertices' cell codes are not all
+    // equal-and-even; the xor of the codes tells (low half = x, high half = y).
     for (uint32_t p0 = 0; p0 < sc.P; p0 += NT) {
         const uint32_t p = p0 + tid;
-        bool keep = false;
+        bool keep_a = false, keep_b = false;
+        uint32_t ta = 0, tb = 0;
         if (p < sc.P) {
-            const uint32_t w0 = sc.pair_tbl[p * 3 + 0], w1 = sc.pair_tbl[p * 3 + 1];
-            const uint32_t q0 = w0 & 0xFFFFu, q1 = w0 >> 16, q2 = w1 & 0xFFFFu, q3 = w1 >> 16;
-            const int x0 = vx[q0], x1 = vx[q1], x2 = vx[q2], x3 = vx[q3];
-            if (x0 == kRejectedX || x1 == kRejectedX || x2 == kRejectedX || x3 == kRejectedX) {
-                keep = true;
-            } else {
-                const int y0 = vy[q0], y1 = vy[q1], y2 = vy[q2], y3 = vy[q3];
-                const int minx = min(imin3(x0, x1, x2), x3), maxx = max(imax3(x0, x1, x2), x3);
-                const int miny = min(imin3(y0, y1, y2), y3), maxy = max(imax3(y0, y1, y2), y3);
-                const int i0 = max(0, (minx + 127) >> 8), i1 = min((int)sc.W - 1, (maxx - 128) >> 8);
-                const int j0 = max(0, (miny + 127) >> 8), j1 = min((int)sc.H - 1, (maxy - 128) >> 8);
-                keep = i0 <= i1 && j0 <= j1;
-            }
+            const uint32_t w0 = sc.pair_tbl[p * 3 + 0], w1 = sc.pair_tbl[p * 3 + 1], w2 = sc.pair_tbl[p * 3 + 2];
+            const uint32_t m0 = vm[w0 & 0xFFFFu], m1 = vm[w0 >> 16], m2 = vm[w1 & 0xFFFFu], m3 = vm[w1 >> 16];
+            const uint32_t odd = m0 & 0x00010001u, x02 = m0 ^ m2;
+            const uint32_t da = (m0 ^ m1) | x02 | odd, db = x02 | (m0 ^ m3) | odd;
+            ta = w2 & 0xFFFFu;
+            tb = w2 >> 16;
+            keep_a = (da & 0xFFFFu) != 0u && da > 0xFFFFu;
+            keep_b = (db & 0xFFFFu) != 0u && db > 0xFFFFu && tb != kNoTriangle;
         }
-        wave_append(keep, p, &fu->n_pairs, pair_list, 0, +1, lane);
+        const u64 ma = __ballot(keep_a), mb = __ballot(keep_b);
+        if (ma | mb) {
+            uint32_t base = 0;
+            if (lane == 0) base = atomicAdd(&fu->n_cand, (uint32_t)(__popcll(ma) + __popcll(mb)));
+            base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
+            const uint32_t slot = base + lanes_below(ma) + lanes_below(mb);
+            if (keep_a) cand[slot] = (uint16_t)ta;
+            if (keep_b) cand[slot + (keep_a ? 1u : 0u)] = (uint16_t)tb;
+        }
     }
     __syncthreads();
     PXR_PHASE_MARK(2);
 
-    // ---- phase 2b: exact binning, one lane per triangle of a surviving pair
-    const uint32_t n_items = 2u * fu->n_pairs;
-    for (uint32_t k0 = 0; k0 < n_items; k0 += NT) {
+    // ---- phase 2b: exact binning, one lane per candidate triangle: reject, area sign, pixel range,
+    // then one of four bins by the number of candidate pixel centres (one packed LDS atomic per wave).
+    const uint32_t n_cand = fu->n_cand;
+    for (uint32_t k0 = 0; k0 < n_cand; k0 += NT) {
         const uint32_t k = k0 + tid;
-        int cls = 0;  // 0 none, 1 tiny, 2 small, 3 large
+        int cls = 0;  // 0 none, 1 tiny, 2 small, 3 mid, 4 large
         uint32_t t = 0;
-        if (k < n_items) {
-            const uint32_t w2 = sc.pair_tbl[(uint32_t)pair_list[k >> 1] * 3 + 2];
-            t = (k & 1u) ? (w2 >> 16) : (w2 & 0xFFFFu);
-            if (t != kNoTriangle) {
-                TriSetup s;
-                uint32_t v0, v1, v2;
-                bool small_extent;
-                if (tri_gather(sc, t, vx, vy, s, v0, v1, v2, small_extent)) {
-                    bool front;
-                    if (small_extent)
-                        front = __mul24(s.bx - s.ax, s.cy - s.ay) > __mul24(s.by - s.ay, s.cx - s.ax);
-                    else
-                        front = (long long)(s.bx - s.ax) * (long long)(s.cy - s.ay) >
-                                (long long)(s.by - s.ay) * (long long)(s.cx - s.ax);
-                    if (front) {
-                        const uint32_t npx = (uint32_t)((s.i1 - s.i0 + 1) * (s.j1 - s.j0 + 1));
-                        cls = !small_extent || npx > kSmallMaxPixels ? 3 : (npx > kTinyMaxPixels ? 2 : 1);
-                    }
+        if (k < n_cand) {
+            t = cand[k];
+            TriSetup s;
+            uint32_t v0, v1, v2;
+            bool small_extent;
+            if (tri_gather(sc, t, vx, vy, s, v0, v1, v2, small_extent)) {
+                bool front;
+                if (small_extent)
+                    front = __mul24(s.bx - s.ax, s.cy - s.ay) > __mul24(s.by - s.ay, s.cx - s.ax);
+                else
+                    front = (long long)(s.bx - s.ax) * (long long)(s.cy - s.ay) >
+                            (long long)(s.by - s.ay) * (long long)(s.cx - s.ax);
+                if (front) {
+                    const uint32_t npx = (uint32_t)((s.i1 - s.i0 + 1) * (s.j1 - s.j0 + 1));
+                    cls = npx <= kTinyMaxPixels ? 1 : (npx <= kSmallMaxPixels ? 2 : (npx <= kMidMaxPixels ? 3 : 4));
                 }
             }
         }
-        wave_append(cls == 1, t, &fu->n_tiny, list, 0, +1, lane);
-        wave_append(cls == 2, t, &fu->n_small, list, (int)sc.T - 1, -1, lane);
-        wave_append(cls == 3, t, &fu->n_large, large, 0, +1, lane);
+        const u64 m1 = __ballot(cls == 1), m2 = __ballot(cls == 2), m3 = __ballot(cls == 3), m4 = __ballot(cls == 4);
+        if (m1 | m2 | m3 | m4) {
+            u64 old = 0;
+            if (lane == 0)
+                old = atomicAdd(&fu->bins, (u64)__popcll(m1) | ((u64)__popcll(m2) << 16) | ((u64)__popcll(m3) << 32) |
+                                               ((u64)__popcll(m4) << 48));
+            const uint32_t old_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)old);
+            const uint32_t old_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(old >> 32));
+            if (cls == 1) list[(old_lo & 0xFFFFu) + lanes_below(m1)] = (uint16_t)t;
+            if (cls == 2) list[sc.T - 1 - ((old_lo >> 16) + lanes_below(m2))] = (uint16_t)t;
+            if (cls == 3) list2[(old_hi & 0xFFFFu) + lanes_below(m3)] = (uint16_t)t;
+            if (cls == 4) list2[sc.T - 1 - ((old_hi >> 16) + lanes_below(m4))] = (uint16_t)t;
+        }
     }
     __syncthreads();
     PXR_PHASE_MARK(3);
 
-    // the pair list is dead: clear the pixel keys it shared LDS with (0 = background at depth 0)
+    // codes and candidates are dead: clear the pixel keys they shared LDS with (0 = background at depth 0)
     for (uint32_t p = tid; p < sc.npix; p += NT) keys[p] = 0ull;
     __syncthreads();
     PXR_PHASE_MARK(4);
 
-    // ---- phase 3: raster + z-test into the LDS key buffer.  Tiny triangles are dealt to lanes
-    // from the front, small ones from the back, so that waves stay homogeneous and busy.
-    const uint32_t n_tiny = fu->n_tiny, n_small = fu->n_small, n_large = fu->n_large;
-    for (uint32_t k = tid; k < n_tiny; k += NT) {
-        const uint32_t t = list[k];
-        TriSetup s;
-        uint32_t v0, v1, v2;
-        bool small_extent;
-        tri_gather(sc, t, vx, vy, s, v0, v1, v2, small_extent);
-        tri_depths(s, vd, v0, v1, v2);
-        raster_small(s, t, sc.W, keys);
-    }
-    for (uint32_t k = NT - 1 - tid; k < n_small; k += NT) {
-        const uint32_t t = list[sc.T - 1 - k];
-        TriSetup s;
-        uint32_t v0, v1, v2;
-        bool small_extent;
-        tri_gather(sc, t, vx, vy, s, v0, v1, v2, small_extent);
-        tri_depths(s, vd, v0, v1, v2);
-        raster_small(s, t, sc.W, keys);
-    }
+    // ---- phase 3: raster + z-test into the LDS key buffer.  The bins start at different
+    // lanes of the workgroup so that all waves get a share.
     {
-        const uint32_t n_waves = NT / 64, wave = (tid >> 6);
-        // start in the middle waves: the first ones hold the tiny bin, the last ones the small bin
-        for (uint32_t k = (wave + n_waves / 2) % n_waves; k < n_large; k += n_waves) {
-            const uint32_t t = large[k];
-            TriSetup s;
-            uint32_t v0, v1, v2;
-            bool small_extent;
-            tri_gather(sc, t, vx, vy, s, v0, v1, v2, small_extent);
-            tri_depths(s, vd, v0, v1, v2);
-            if (small_extent)
-                raster_wave32(s, t, sc.W, keys, lane);
-            else
-                raster_wave64(s, t, sc.W, keys, lane);
-        }
+        const u64 bins = fu->bins;
+        const uint32_t n_tiny = (uint32_t)bins & 0xFFFFu, n_small = ((uint32_t)bins >> 16);
+        const uint32_t n_mid = (uint32_t)(bins >> 32) & 0xFFFFu, n_large = (uint32_t)(bins >> 48);
+        for (uint32_t k = tid; k < n_tiny; k += NT) raster_binned(sc, list[k], vx, vy, vd, keys, 0, 0);
+        for (uint32_t k = NT - 1 - tid; k < n_small; k += NT) raster_binned(sc, list[sc.T - 1 - k], vx, vy, vd, keys, 0, 0);
+        // mid: 8 lanes per triangle, starting in the middle waves
+        for (uint32_t k = ((tid >> 3) + NT / 16) % (NT / 8); k < n_mid; k += NT / 8)
+            raster_binned(sc, list2[k], vx, vy, vd, keys, (int)(tid & 7u), 3);
+        // large: a whole wave per triangle
+        for (uint32_t k = ((tid >> 6) + NT / 128) % (NT / 64); k < n_large; k += NT / 64)
+            raster_binned(sc, list2[sc.T - 1 - k], vx, vy, vd, keys, (int)lane, 6);
     }
     __syncthreads();
     PXR_PHASE_MARK(5);
@@ -592,8 +563,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     rc.inv_ez = 1.0f / eye_z;
     rc.ground_ok = sc.ground_on && eye_z > 0.0f;
     rc.mode = dc.mode;
-    rc.vframe = nullptr;
     rc.alpha = dc.alpha;
+    rc.vframe = nullptr;
 #pragma unroll
     for (int c = 0; c < 3; ++c) {
         rc.scale[c] = fu->scale[c];

@@ -355,7 +355,7 @@ int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
     auto align = [](uint32_t x, uint32_t a) { return (x + a - 1) / a * a; };
     uint32_t o = 0;
     c.lds_keys = o;  // 16-byte aligned regions first
-    o += align(std::max(c.npix * 8, c.P * 2), 16);
+    o += align(std::max(c.npix * 8, c.V * 4 + c.T * 2), 16);
     c.lds_cxcy = o;
     o += align((c.W + c.H) * 4, 16);
     c.lds_misc = o;
