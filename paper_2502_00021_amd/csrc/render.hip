@@ -222,6 +222,11 @@ __device__ unsigned long long g_phase_cycles[8];
         atomicAdd(&g_phase_cycles[i], now - phase_t0);            \
         phase_t0 = now;                                           \
     }
+#elif defined(PXR_STOP_AFTER)
+// Profiling build only: the kernel ends after phase PXR_STOP_AFTER (counter deltas give per-phase cost).
+#define PXR_PHASE_BEGIN()
+#define PXR_PHASE_MARK(i) \
+    if ((i) == PXR_STOP_AFTER) return
 #else
 #define PXR_PHASE_BEGIN()
 #define PXR_PHASE_MARK(i)
@@ -265,6 +270,8 @@ __device__ __forceinline__ u64 ground_key(const SceneConsts& sc, const ResolveCt
 // One pixel: winner of (triangles, ground, background) -> colour -> distractor
 // -> 24-bit RGB.  `low` returns ~id.  `vbytes` = the pixel's three video bytes
 // (R | G<<8 | B<<16), only read in video mode.
+// UNIT_CELL: the checkerboard cell is 1 m, so the division by the cell size is the identity.
+template <bool UNIT_CELL>
 __device__ __forceinline__ uint32_t resolve_pixel(const SceneConsts& sc, const ResolveCtx& rc, const float* body, u64 key,
                                                   u64 gkey, float tg, float dwx, float dwy, uint32_t vbytes, uint32_t& low) {
     key = key > gkey ? key : gkey;
@@ -296,8 +303,8 @@ __device__ __forceinline__ uint32_t resolve_pixel(const SceneConsts& sc, const R
     if (low == 1u) {
         const float wx = __builtin_fmaf(tg, dwx, rc.eye_x);
         const float wy = __builtin_fmaf(tg, dwy, rc.eye_y);
-        const float ux = sc.cell_is_one ? wx : wx / sc.cell;
-        const float uy = sc.cell_is_one ? wy : wy / sc.cell;
+        const float ux = UNIT_CELL ? wx : wx / sc.cell;
+        const float uy = UNIT_CELL ? wy : wy / sc.cell;
         cls = 1 + (((int)__builtin_floorf(ux) + (int)__builtin_floorf(uy)) & 1);
     }
     if (rc.mode != PXR_DISTRACT_VIDEO) return rc.base_packed[cls];
@@ -309,6 +316,56 @@ __device__ __forceinline__ uint32_t resolve_pixel(const SceneConsts& sc, const R
         rgb |= quantise(__builtin_fmaf(rc.alpha, vf - c, c)) << (8 * ch);
     }
     return rgb;
+}
+
+// Phase 4 for images whose width is a multiple of 4: four consecutive pixels of one row per
+// lane.  The row part of the ray is shared, and without camera roll (NO_ROLL: the right vector is
+// horizontal) so is the whole ground test, which then costs one division per lane, not four.
+template <int NT, bool UNIT_CELL, bool NO_ROLL>
+__device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const ResolveCtx& rc, const float* body,
+                                              const float* cxcy, const u64* keys, uint8_t* out, uint32_t* out_ids,
+                                              uint32_t tid) {
+    for (uint32_t q = tid; q * 4 < sc.npix; q += NT) {
+        const uint32_t p0 = q * 4;
+        const uint32_t j = __umulhi(p0, sc.magicW);
+        const uint32_t i0 = p0 - j * sc.W;
+        const float cyj = cxcy[sc.W + j];
+        const float rx = __builtin_fmaf(sc.Up[0], cyj, sc.Fw[0]);
+        const float ry = __builtin_fmaf(sc.Up[1], cyj, sc.Fw[1]);
+        const float rz = __builtin_fmaf(sc.Up[2], cyj, sc.Fw[2]);
+        const float4 cx4 = *reinterpret_cast<const float4*>(cxcy + i0);
+        const float cxs[4] = {cx4.x, cx4.y, cx4.z, cx4.w};
+        uint32_t vid[3] = {0u, 0u, 0u};
+        if (rc.mode == PXR_DISTRACT_VIDEO) {
+            const uint32_t* vsrc = reinterpret_cast<const uint32_t*>(rc.vframe) + q * 3;
+            vid[0] = vsrc[0];
+            vid[1] = vsrc[1];
+            vid[2] = vsrc[2];
+        }
+        const uint32_t vb[4] = {vid[0] & 0xFFFFFFu, (vid[0] >> 24) | ((vid[1] & 0xFFFFu) << 8),
+                                (vid[1] >> 16) | ((vid[2] & 0xFFu) << 16), vid[2] >> 8};
+        float tg_row = 0.0f;
+        u64 gkey_row = 0ull;
+        if (NO_ROLL) gkey_row = ground_key(sc, rc, -rz, tg_row);  // fma(+-0, cx, rz) == rz
+        uint32_t rgb[4], low[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            float tg = tg_row;
+            u64 gkey = gkey_row;
+            if (!NO_ROLL) gkey = ground_key(sc, rc, -__builtin_fmaf(sc.Rt[2], cxs[k], rz), tg);
+            const float dwx = __builtin_fmaf(sc.Rt[0], cxs[k], rx);
+            const float dwy = __builtin_fmaf(sc.Rt[1], cxs[k], ry);
+            rgb[k] = resolve_pixel<UNIT_CELL>(sc, rc, body, keys[p0 + k], gkey, tg, dwx, dwy, vb[k], low[k]);
+        }
+        struct alignas(4) U3 {
+            uint32_t a, b, c;
+        };
+        *reinterpret_cast<U3*>(reinterpret_cast<uint32_t*>(out) + q * 3) =
+            U3{rgb[0] | (rgb[1] << 24), (rgb[1] >> 8) | (rgb[2] << 16), (rgb[2] >> 16) | (rgb[3] << 8)};
+        if (out_ids)
+            reinterpret_cast<uint4*>(out_ids)[q] =
+                make_uint4(0xFFFFFFFFu - low[0], 0xFFFFFFFFu - low[1], 0xFFFFFFFFu - low[2], 0xFFFFFFFFu - low[3]);
+    }
 }
 
 // Register budget: two 80 KB workgroups share a compute unit, so 1024-thread groups need all
@@ -577,49 +634,18 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     uint32_t* out_ids = ids ? ids + (size_t)frame * sc.npix : nullptr;
 
     if (PX == 4) {
-        // Four consecutive pixels of one row per lane (W is a multiple of 4): the row part of
-        // the ray is shared, and without camera roll so is the whole ground test.
+        // uniform scene properties select a specialised loop (kept out of the per-pixel code)
         const bool no_roll = sc.Rt[2] == 0.0f;
-        for (uint32_t q = tid; q * 4 < sc.npix; q += NT) {
-            const uint32_t p0 = q * 4;
-            const uint32_t j = __umulhi(p0, sc.magicW);
-            const uint32_t i0 = p0 - j * sc.W;
-            const float cyj = cxcy[sc.W + j];
-            const float rx = __builtin_fmaf(sc.Up[0], cyj, sc.Fw[0]);
-            const float ry = __builtin_fmaf(sc.Up[1], cyj, sc.Fw[1]);
-            const float rz = __builtin_fmaf(sc.Up[2], cyj, sc.Fw[2]);
-            const float4 cx4 = *reinterpret_cast<const float4*>(cxcy + i0);
-            const float cxs[4] = {cx4.x, cx4.y, cx4.z, cx4.w};
-            uint32_t vid[3] = {0u, 0u, 0u};
-            if (rc.mode == PXR_DISTRACT_VIDEO) {
-                const uint32_t* vsrc = reinterpret_cast<const uint32_t*>(rc.vframe) + q * 3;
-                vid[0] = vsrc[0];
-                vid[1] = vsrc[1];
-                vid[2] = vsrc[2];
-            }
-            const uint32_t vb[4] = {vid[0] & 0xFFFFFFu, (vid[0] >> 24) | ((vid[1] & 0xFFFFu) << 8),
-                                    (vid[1] >> 16) | ((vid[2] & 0xFFu) << 16), vid[2] >> 8};
-            float tg_row = 0.0f;
-            u64 gkey_row = 0ull;
-            if (no_roll) gkey_row = ground_key(sc, rc, -rz, tg_row);  // fma(+-0, cx, rz) == rz
-            uint32_t rgb[4], low[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                float tg = tg_row;
-                u64 gkey = gkey_row;
-                if (!no_roll) gkey = ground_key(sc, rc, -__builtin_fmaf(sc.Rt[2], cxs[k], rz), tg);
-                const float dwx = __builtin_fmaf(sc.Rt[0], cxs[k], rx);
-                const float dwy = __builtin_fmaf(sc.Rt[1], cxs[k], ry);
-                rgb[k] = resolve_pixel(sc, rc, body, keys[p0 + k], gkey, tg, dwx, dwy, vb[k], low[k]);
-            }
-            struct alignas(4) U3 {
-                uint32_t a, b, c;
-            };
-            *reinterpret_cast<U3*>(reinterpret_cast<uint32_t*>(out) + q * 3) =
-                U3{rgb[0] | (rgb[1] << 24), (rgb[1] >> 8) | (rgb[2] << 16), (rgb[2] >> 16) | (rgb[3] << 8)};
-            if (out_ids)
-                reinterpret_cast<uint4*>(out_ids)[q] =
-                    make_uint4(0xFFFFFFFFu - low[0], 0xFFFFFFFFu - low[1], 0xFFFFFFFFu - low[2], 0xFFFFFFFFu - low[3]);
+        if (sc.cell_is_one) {
+            if (no_roll)
+                resolve_rows4<NT, true, true>(sc, rc, body, cxcy, keys, out, out_ids, tid);
+            else
+                resolve_rows4<NT, true, false>(sc, rc, body, cxcy, keys, out, out_ids, tid);
+        } else {
+            if (no_roll)
+                resolve_rows4<NT, false, true>(sc, rc, body, cxcy, keys, out, out_ids, tid);
+            else
+                resolve_rows4<NT, false, false>(sc, rc, body, cxcy, keys, out, out_ids, tid);
         }
     } else {
         // any image shape: one pixel per lane, byte stores
@@ -638,7 +664,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
                 vbytes = (uint32_t)v[0] | ((uint32_t)v[1] << 8) | ((uint32_t)v[2] << 16);
             }
             uint32_t low;
-            const uint32_t rgb = resolve_pixel(sc, rc, body, keys[p], gkey, tg, dwx, dwy, vbytes, low);
+            const uint32_t rgb = resolve_pixel<false>(sc, rc, body, keys[p], gkey, tg, dwx, dwy, vbytes, low);
             out[(size_t)p * 3 + 0] = (uint8_t)(rgb & 0xFFu);
             out[(size_t)p * 3 + 1] = (uint8_t)((rgb >> 8) & 0xFFu);
             out[(size_t)p * 3 + 2] = (uint8_t)(rgb >> 16);
