@@ -31,10 +31,9 @@ from paper_2502_00021_amd import workloads  # noqa: E402
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch of the default workload (cfg5, 65536 envs x 3 steps), measured with two
-# rocprofv3 --pmc passes (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the factors a plain 1 GiB copy
-# gives for the same counters); profiles/render_kernel_cfg5_humanoid_box_64.md.  Other workloads: null.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("cfg5", 65536): 2538.8e6}
+# HBM bytes per launch, measured with two rocprofv3 --pmc passes (FETCH_SIZE x 2.000 + WRITE_SIZE x
+# 1.000, the factors a plain 1 GiB copy gives for the same counters); see profiles/.  Others: null.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("cfg5", 65536): 2541.6e6, ("cfg4", 16384): 404.4e6}
 
 
 def algorithmic_ops_per_frame(V, T, npix, mode):
