@@ -1,0 +1,24 @@
+"""The oracle under AddressSanitizer + UndefinedBehaviorSanitizer (host code only): a native driver
+renders scenes with every primitive, degenerate poses and both distractors; any report fails the test."""
+import os
+import subprocess
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_oracle_is_clean_under_asan_and_ubsan(tmp_path):
+    exe = str(tmp_path / "orc_sanitize")
+    subprocess.check_call(["g++", "-std=c++17", "-O1", "-g", "-ffp-contract=off", "-fsanitize=address,undefined",
+                           "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer",
+                           os.path.join(ROOT, "oracle", "orc.cpp"), os.path.join(ROOT, "tests", "orc_sanitize_main.cpp"),
+                           "-o", exe])
+    env = dict(os.environ, ASAN_OPTIONS="verify_asan_link_order=0:detect_leaks=1:abort_on_error=0",
+               UBSAN_OPTIONS="print_stacktrace=1:halt_on_error=1")
+    env.pop("LD_PRELOAD", None)
+    r = subprocess.run([exe], env=env, capture_output=True, text=True, timeout=120)
+    sys.stdout.write(r.stdout)
+    sys.stderr.write(r.stderr[-4000:])
+    assert r.returncode == 0, r.stderr[-2000:]
+    assert r.stdout.startswith("ok ")
+    assert "runtime error" not in r.stderr and "AddressSanitizer" not in r.stderr
