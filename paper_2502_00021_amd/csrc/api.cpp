@@ -194,7 +194,9 @@ int pxr_host_tables(const pxr_scene_desc* desc, uint32_t* n_verts, uint32_t* n_t
     if (tri_shade) std::memcpy(tri_shade, hs.tri_shade.data(), hs.tri_shade.size() * 4);
     if (cxcy) std::memcpy(cxcy, hs.cxcy.data(), hs.cxcy.size() * 4);
     if (n_pairs) *n_pairs = hs.c.P;
-    if (pair_tbl) std::memcpy(pair_tbl, hs.pair_tbl.data(), hs.pair_tbl.size() * 4);
+    if (pair_tbl)
+        for (uint32_t p = 0; p < hs.c.P; ++p)
+            for (int w = 0; w < 3; ++w) pair_tbl[p * 3 + w] = hs.pair_tbl[p * 4 + w];
     if (consts) {
         for (int i = 0; i < 3; ++i) {
             consts[i] = hs.c.Rt[i];

@@ -21,9 +21,18 @@ constexpr int32_t kRejectedX = INT32_MIN;
 //   small <= kSmallMaxPixels  one lane
 //   mid   <= kMidMaxPixels    eight lanes, rows dealt round-robin
 //   large otherwise           a whole wavefront, one row per lane
-constexpr uint32_t kTinyMaxPixels = 2;
-constexpr uint32_t kSmallMaxPixels = 12;
-constexpr uint32_t kMidMaxPixels = 96;
+#ifndef PXR_TINY_MAX
+#define PXR_TINY_MAX 2
+#endif
+#ifndef PXR_SMALL_MAX
+#define PXR_SMALL_MAX 12
+#endif
+#ifndef PXR_MID_MAX
+#define PXR_MID_MAX 96
+#endif
+constexpr uint32_t kTinyMaxPixels = PXR_TINY_MAX;
+constexpr uint32_t kSmallMaxPixels = PXR_SMALL_MAX;
+constexpr uint32_t kMidMaxPixels = PXR_MID_MAX;
 constexpr uint32_t kNoTriangle = 0xFFFFu;
 
 // Per-body record kept in LDS for the duration of one frame (floats).
@@ -52,7 +61,7 @@ struct SceneConsts {
     const float* vtmpl;       // [V][4]  ux,uy,uz, bits = body<<2 | (s+1)
     const uint32_t* tri_idx;  // [T][2]  v0 | v1<<16 ,  v2 | body<<16
     const float* tri_shade;   // [T][4]  unit normal (body frame), colour multiplier
-    const uint32_t* pair_tbl; // [P][3]  q0 | q1<<16 , q2 | q3<<16 , triA | triB<<16: two triangles sharing the
+    const uint32_t* pair_tbl; // [P][4]  q0 | q1<<16 , q2 | q3<<16 , triA | triB<<16 , 0: two triangles sharing the
                               //         edge q0-q2, or one triangle (q3 = q2, triB = kNoTriangle)
     const float* body_const;  // [K][8]  shape a,b,c,h ; rgb r,g,b,0
     const float* cxcy;        // [W+H]   pixel-centre ray slopes

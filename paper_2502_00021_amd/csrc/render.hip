@@ -490,7 +490,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     for (uint32_t v = tid; v < sc.V; v += NT) {
         const float4 tv = reinterpret_cast<const float4*>(sc.vtmpl)[v];
         const uint32_t code = __float_as_uint(tv.w);
-        const float* o = body + (code >> 2) * kBodyStride;
+        const float* o = body + __umul24(code >> 2, kBodyStride);
         const float sel = (float)((int)(code & 3u) - 1);
         const float lx = o[16] * tv.x;
         const float ly = o[17] * tv.y;
@@ -525,7 +525,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         bool keep_a = false, keep_b = false;
         uint32_t ta = 0, tb = 0;
         if (p < sc.P) {
-            const uint32_t w0 = sc.pair_tbl[p * 3 + 0], w1 = sc.pair_tbl[p * 3 + 1], w2 = sc.pair_tbl[p * 3 + 2];
+            const uint4 rec = reinterpret_cast<const uint4*>(sc.pair_tbl)[p];
+            const uint32_t w0 = rec.x, w1 = rec.y, w2 = rec.z;
             const uint32_t m0 = vm[w0 & 0xFFFFu], m1 = vm[w0 >> 16], m2 = vm[w1 & 0xFFFFu], m3 = vm[w1 >> 16];
             const uint32_t odd = m0 & 0x00010001u, x02 = m0 ^ m2;
             const uint32_t da = (m0 ^ m1) | x02 | odd, db = x02 | (m0 ^ m3) | odd;

@@ -172,6 +172,7 @@ void pair_triangles(const BodyMesh& m, uint32_t vbase, uint32_t tbase, std::vect
                         tbl.push_back((vbase + x) | ((vbase + a3) << 16));
                         tbl.push_back((vbase + y) | ((vbase + b3) << 16));
                         tbl.push_back((tbase + t) | ((tbase + t + 1) << 16));
+                        tbl.push_back(0u);  // pad to one 16-byte load
                         paired = true;
                         break;
                     }
@@ -184,6 +185,7 @@ void pair_triangles(const BodyMesh& m, uint32_t vbase, uint32_t tbase, std::vect
             tbl.push_back((vbase + A[0]) | ((vbase + A[1]) << 16));
             tbl.push_back((vbase + A[2]) | ((vbase + A[2]) << 16));
             tbl.push_back((tbase + t) | (kNoTriangle << 16));
+            tbl.push_back(0u);
             t += 1;
         }
     }
@@ -293,7 +295,7 @@ int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
     }
     c.V = vbase;
     c.T = tbase;
-    c.P = (uint32_t)(hs.pair_tbl.size() / 3);
+    c.P = (uint32_t)(hs.pair_tbl.size() / 4);
 
     // ---- camera: forward looks from the eye to the root, right = forward x up
     const Vec3d off{d.cam_offset[0], d.cam_offset[1], d.cam_offset[2]};
