@@ -34,6 +34,8 @@ uint32_t pick_block_threads(const pxr::SceneConsts& sc) {
     const uint32_t groups_per_cu = (160u * 1024u) / (sc.lds_total ? sc.lds_total : 1u);
     if (groups_per_cu >= 8) return 256;
     if (groups_per_cu >= 3) return 512;
+    // the banded kernel variants need more than 64 registers: two groups of 768 threads then
+    if (groups_per_cu == 2 && sc.band_rows < sc.H) return 768;
     return 1024;
 }
 

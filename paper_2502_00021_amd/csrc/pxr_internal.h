@@ -56,6 +56,7 @@ struct SceneConsts {
     uint32_t ground_on, cell_is_one;
     // sizes
     uint32_t W, H, npix, K, root, V, T, P;  // P = entries of the pair table
+    uint32_t band_rows;                     // rows of the frame held by the LDS key buffer at a time
     uint32_t magicW;  // ceil(2^32 / W): p / W == mulhi(p, magicW) for p < 2^14 * 2^7
     // device tables
     const float* vtmpl;       // [V][4]  ux,uy,uz, bits = body<<2 | (s+1)

@@ -114,7 +114,8 @@ __device__ __forceinline__ long long emul<long long>(int a, int b) {
 // Edge functions carry their fill-rule bias and are stepped incrementally; a
 // pixel centre is covered when all three are >= 0.
 template <typename I>
-__device__ __forceinline__ void raster_rows(const TriSetup& s, uint32_t tri, uint32_t W, u64* keys, int r, int shift) {
+__device__ __forceinline__ void raster_rows(const TriSetup& s, uint32_t tri, uint32_t W, u64* keys, int r, int shift,
+                                            int row_lo) {
     int j = s.j0 + r;
     if (j > s.j1) return;
     const int dx_ab = s.bx - s.ax, dy_ab = s.by - s.ay;
@@ -131,7 +132,7 @@ __device__ __forceinline__ void raster_rows(const TriSetup& s, uint32_t tri, uin
     const I sy_ab = (I)dx_ab << (8 + shift), sy_bc = (I)dx_bc << (8 + shift), sy_ca = (I)dx_ca << (8 + shift);
     for (;;) {
         I e_ab = f_ab, e_bc = f_bc, e_ca = f_ca;
-        uint32_t pix = (uint32_t)j * W + (uint32_t)s.i0;
+        uint32_t pix = (uint32_t)(j - row_lo) * W + (uint32_t)s.i0;  // the key buffer holds rows from row_lo on
         for (int i = s.i0; i <= s.i1; ++i, ++pix) {
             if ((e_ab | e_bc | e_ca) >= 0) {
                 const float beta = (float)(e_ca - b_ca) * invA, gamma = (float)(e_ab - b_ab) * invA;
@@ -176,20 +177,24 @@ __device__ __forceinline__ bool tri_gather(const SceneConsts& sc, uint32_t t, co
     return s.i0 <= s.i1 && s.j0 <= s.j1;
 }
 
-// Raster one binned triangle with lane `r` of the 2^shift lanes that share it.
+// Raster one binned triangle with lane `r` of the 2^shift lanes that share it, restricted to
+// the rows [row_lo, row_hi) that the key buffer currently holds.
 __device__ __forceinline__ void raster_binned(const SceneConsts& sc, uint32_t t, const int* vx, const int* vy,
-                                              const float* vd, u64* keys, int r, int shift) {
+                                              const float* vd, u64* keys, int r, int shift, int row_lo, int row_hi) {
     TriSetup s;
     uint32_t v0, v1, v2;
     bool small_extent;
     tri_gather(sc, t, vx, vy, s, v0, v1, v2, small_extent);
+    s.j0 = max(s.j0, row_lo);
+    s.j1 = min(s.j1, row_hi - 1);
+    if (s.j0 > s.j1) return;
     s.Da = vd[v0];
     s.dDb = vd[v2] - s.Da;
     s.dDc = vd[v1] - s.Da;
     if (small_extent)
-        raster_rows<int>(s, t, sc.W, keys, r, shift);
+        raster_rows<int>(s, t, sc.W, keys, r, shift, row_lo);
     else
-        raster_rows<long long>(s, t, sc.W, keys, r, shift);
+        raster_rows<long long>(s, t, sc.W, keys, r, shift, row_lo);
 }
 
 // Per-axis cell code of a snapped coordinate for an image of n pixels:
@@ -324,8 +329,9 @@ __device__ __forceinline__ uint32_t resolve_pixel(const SceneConsts& sc, const R
 template <int NT, bool UNIT_CELL, bool NO_ROLL>
 __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const ResolveCtx& rc, const float* body,
                                               const float* cxcy, const u64* keys, uint8_t* out, uint32_t* out_ids,
-                                              uint32_t tid) {
-    for (uint32_t q = tid; q * 4 < sc.npix; q += NT) {
+                                              uint32_t tid, uint32_t p_begin, uint32_t p_end) {
+    // pixels [p_begin, p_end) of the frame; keys[0] belongs to pixel p_begin
+    for (uint32_t q = (p_begin >> 2) + tid; q * 4 < p_end; q += NT) {
         const uint32_t p0 = q * 4;
         const uint32_t j = __umulhi(p0, sc.magicW);
         const uint32_t i0 = p0 - j * sc.W;
@@ -355,7 +361,7 @@ __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const Resol
             if (!NO_ROLL) gkey = ground_key(sc, rc, -__builtin_fmaf(sc.Rt[2], cxs[k], rz), tg);
             const float dwx = __builtin_fmaf(sc.Rt[0], cxs[k], rx);
             const float dwy = __builtin_fmaf(sc.Rt[1], cxs[k], ry);
-            rgb[k] = resolve_pixel<UNIT_CELL>(sc, rc, body, keys[p0 + k], gkey, tg, dwx, dwy, vb[k], low[k]);
+            rgb[k] = resolve_pixel<UNIT_CELL>(sc, rc, body, keys[p0 - p_begin + k], gkey, tg, dwx, dwy, vb[k], low[k]);
         }
         struct alignas(4) U3 {
             uint32_t a, b, c;
@@ -370,7 +376,8 @@ __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const Resol
 
 // Register budget: two 80 KB workgroups share a compute unit, so 1024-thread groups need all
 // 8 wave slots per SIMD (<= 64 VGPRs); the smaller groups may use more registers.
-template <int NT, int PX>
+// BANDED: the key buffer holds only `band_rows` rows at a time and phases 3-4 loop over bands.
+template <int NT, int PX, bool BANDED>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ? 8 : (NT >= 768 ? 6 : 4)))) void render_kernel(
     const SceneConsts sc, const DistractConsts dc, const float* __restrict__ poses, const float* __restrict__ shapes,
     uint32_t S, uint32_t step0, uint32_t env0, uint8_t* __restrict__ frames, uint32_t* __restrict__ ids) {
@@ -590,97 +597,106 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     __syncthreads();
     PXR_PHASE_MARK(3);
 
-    // codes and candidates are dead: clear the pixel keys they shared LDS with (0 = background at depth 0)
-    for (uint32_t p = tid; p < sc.npix; p += NT) keys[p] = 0ull;
-    __syncthreads();
-    PXR_PHASE_MARK(4);
+    // Tall frames are rendered in horizontal bands so that the key buffer stays small enough for two
+    // workgroups per compute unit; geometry work (phases 0-2) is done once, raster and resolve per band.
+    uint32_t row_lo = 0;
+    do {
+        const uint32_t row_hi = BANDED ? min(sc.H, row_lo + sc.band_rows) : sc.H;
+        const uint32_t p_begin = row_lo * sc.W, p_end = row_hi * sc.W;
+        if (row_lo) __syncthreads();  // the previous band's keys have been resolved
 
-    // ---- phase 3: raster + z-test into the LDS key buffer.  The bins start at different
-    // lanes of the workgroup so that all waves get a share.
-    {
+        // codes and candidates are dead: clear the pixel keys they shared LDS with (0 = background at depth 0)
+        for (uint32_t p = tid; p < p_end - p_begin; p += NT) keys[p] = 0ull;
+        __syncthreads();
+        PXR_PHASE_MARK(4);
+
+        // ---- phase 3: raster + z-test into the LDS key buffer.  The bins start at different
+        // lanes of the workgroup so that all waves get a share.
         const u64 bins = fu->bins;
         const uint32_t n_tiny = (uint32_t)bins & 0xFFFFu, n_small = ((uint32_t)bins >> 16);
         const uint32_t n_mid = (uint32_t)(bins >> 32) & 0xFFFFu, n_large = (uint32_t)(bins >> 48);
-        for (uint32_t k = tid; k < n_tiny; k += NT) raster_binned(sc, list[k], vx, vy, vd, keys, 0, 0);
-        for (uint32_t k = NT - 1 - tid; k < n_small; k += NT) raster_binned(sc, list[sc.T - 1 - k], vx, vy, vd, keys, 0, 0);
+
+        for (uint32_t k = tid; k < n_tiny; k += NT) raster_binned(sc, list[k], vx, vy, vd, keys, 0, 0, (int)row_lo, (int)row_hi);
+        for (uint32_t k = NT - 1 - tid; k < n_small; k += NT)
+            raster_binned(sc, list[sc.T - 1 - k], vx, vy, vd, keys, 0, 0, (int)row_lo, (int)row_hi);
         // mid: 8 lanes per triangle, starting in the middle waves
         for (uint32_t k = ((tid >> 3) + NT / 16) % (NT / 8); k < n_mid; k += NT / 8)
-            raster_binned(sc, list2[k], vx, vy, vd, keys, (int)(tid & 7u), 3);
+            raster_binned(sc, list2[k], vx, vy, vd, keys, (int)(tid & 7u), 3, (int)row_lo, (int)row_hi);
         // large: a whole wave per triangle
         for (uint32_t k = ((tid >> 6) + NT / 128) % (NT / 64); k < n_large; k += NT / 64)
-            raster_binned(sc, list2[sc.T - 1 - k], vx, vy, vd, keys, (int)lane, 6);
-    }
-    __syncthreads();
-    PXR_PHASE_MARK(5);
+            raster_binned(sc, list2[sc.T - 1 - k], vx, vy, vd, keys, (int)lane, 6, (int)row_lo, (int)row_hi);
+        __syncthreads();
+        PXR_PHASE_MARK(5);
 
-    // ---- phase 4: resolve + shade + distractor + pack + store
-    ResolveCtx rc;
-    rc.eye_x = eye_x;
-    rc.eye_y = eye_y;
-    rc.eye_z = eye_z;
-    rc.inv_ez = 1.0f / eye_z;
-    rc.ground_ok = sc.ground_on && eye_z > 0.0f;
-    rc.mode = dc.mode;
-    rc.alpha = dc.alpha;
-    rc.vframe = nullptr;
+        // ---- phase 4: resolve + shade + distractor + pack + store
+        ResolveCtx rc;
+        rc.eye_x = eye_x;
+        rc.eye_y = eye_y;
+        rc.eye_z = eye_z;
+        rc.inv_ez = 1.0f / eye_z;
+        rc.ground_ok = sc.ground_on && eye_z > 0.0f;
+        rc.mode = dc.mode;
+        rc.alpha = dc.alpha;
+        rc.vframe = nullptr;
 #pragma unroll
-    for (int c = 0; c < 3; ++c) {
-        rc.scale[c] = fu->scale[c];
-        rc.offs[c] = fu->offs[c];
-    }
-    rc.base_col = &fu->base_col[0][0];
-    rc.base_packed = fu->base_packed;
-    if (rc.mode == PXR_DISTRACT_VIDEO) rc.vframe = dc.video + (size_t)fu->video_frame * sc.npix * 3;
-    uint8_t* out = frames + (size_t)frame * sc.npix * 3;
-    uint32_t* out_ids = ids ? ids + (size_t)frame * sc.npix : nullptr;
-
-    if (PX == 4) {
-        // uniform scene properties select a specialised loop (kept out of the per-pixel code)
-        const bool no_roll = sc.Rt[2] == 0.0f;
-        if (sc.cell_is_one) {
-            if (no_roll)
-                resolve_rows4<NT, true, true>(sc, rc, body, cxcy, keys, out, out_ids, tid);
-            else
-                resolve_rows4<NT, true, false>(sc, rc, body, cxcy, keys, out, out_ids, tid);
-        } else {
-            if (no_roll)
-                resolve_rows4<NT, false, true>(sc, rc, body, cxcy, keys, out, out_ids, tid);
-            else
-                resolve_rows4<NT, false, false>(sc, rc, body, cxcy, keys, out, out_ids, tid);
+        for (int c = 0; c < 3; ++c) {
+            rc.scale[c] = fu->scale[c];
+            rc.offs[c] = fu->offs[c];
         }
-    } else {
-        // any image shape: one pixel per lane, byte stores
-        for (uint32_t p = tid; p < sc.npix; p += NT) {
-            const uint32_t j = __umulhi(p, sc.magicW);
-            const uint32_t i = p - j * sc.W;
-            const float cxi = cxcy[i], cyj = cxcy[sc.W + j];
-            const float dwx = __builtin_fmaf(sc.Rt[0], cxi, __builtin_fmaf(sc.Up[0], cyj, sc.Fw[0]));
-            const float dwy = __builtin_fmaf(sc.Rt[1], cxi, __builtin_fmaf(sc.Up[1], cyj, sc.Fw[1]));
-            const float dwz = __builtin_fmaf(sc.Rt[2], cxi, __builtin_fmaf(sc.Up[2], cyj, sc.Fw[2]));
-            float tg;
-            const u64 gkey = ground_key(sc, rc, -dwz, tg);
-            uint32_t vbytes = 0;
-            if (rc.mode == PXR_DISTRACT_VIDEO) {
-                const uint8_t* v = rc.vframe + (size_t)p * 3;
-                vbytes = (uint32_t)v[0] | ((uint32_t)v[1] << 8) | ((uint32_t)v[2] << 16);
+        rc.base_col = &fu->base_col[0][0];
+        rc.base_packed = fu->base_packed;
+        if (rc.mode == PXR_DISTRACT_VIDEO) rc.vframe = dc.video + (size_t)fu->video_frame * sc.npix * 3;
+        uint8_t* out = frames + (size_t)frame * sc.npix * 3;
+        uint32_t* out_ids = ids ? ids + (size_t)frame * sc.npix : nullptr;
+        if (PX == 4) {
+            // uniform scene properties select a specialised loop (kept out of the per-pixel code)
+            const bool no_roll = sc.Rt[2] == 0.0f;
+            if (sc.cell_is_one) {
+                if (no_roll)
+                    resolve_rows4<NT, true, true>(sc, rc, body, cxcy, keys, out, out_ids, tid, p_begin, p_end);
+                else
+                    resolve_rows4<NT, true, false>(sc, rc, body, cxcy, keys, out, out_ids, tid, p_begin, p_end);
+            } else {
+                if (no_roll)
+                    resolve_rows4<NT, false, true>(sc, rc, body, cxcy, keys, out, out_ids, tid, p_begin, p_end);
+                else
+                    resolve_rows4<NT, false, false>(sc, rc, body, cxcy, keys, out, out_ids, tid, p_begin, p_end);
             }
-            uint32_t low;
-            const uint32_t rgb = resolve_pixel<false>(sc, rc, body, keys[p], gkey, tg, dwx, dwy, vbytes, low);
-            out[(size_t)p * 3 + 0] = (uint8_t)(rgb & 0xFFu);
-            out[(size_t)p * 3 + 1] = (uint8_t)((rgb >> 8) & 0xFFu);
-            out[(size_t)p * 3 + 2] = (uint8_t)(rgb >> 16);
-            if (out_ids) out_ids[p] = 0xFFFFFFFFu - low;
+        } else {
+            // any image shape: one pixel per lane, byte stores
+            for (uint32_t p = p_begin + tid; p < p_end; p += NT) {
+                const uint32_t j = __umulhi(p, sc.magicW);
+                const uint32_t i = p - j * sc.W;
+                const float cxi = cxcy[i], cyj = cxcy[sc.W + j];
+                const float dwx = __builtin_fmaf(sc.Rt[0], cxi, __builtin_fmaf(sc.Up[0], cyj, sc.Fw[0]));
+                const float dwy = __builtin_fmaf(sc.Rt[1], cxi, __builtin_fmaf(sc.Up[1], cyj, sc.Fw[1]));
+                const float dwz = __builtin_fmaf(sc.Rt[2], cxi, __builtin_fmaf(sc.Up[2], cyj, sc.Fw[2]));
+                float tg;
+                const u64 gkey = ground_key(sc, rc, -dwz, tg);
+                uint32_t vbytes = 0;
+                if (rc.mode == PXR_DISTRACT_VIDEO) {
+                    const uint8_t* v = rc.vframe + (size_t)p * 3;
+                    vbytes = (uint32_t)v[0] | ((uint32_t)v[1] << 8) | ((uint32_t)v[2] << 16);
+                }
+                uint32_t low;
+                const uint32_t rgb = resolve_pixel<false>(sc, rc, body, keys[p - p_begin], gkey, tg, dwx, dwy, vbytes, low);
+                out[(size_t)p * 3 + 0] = (uint8_t)(rgb & 0xFFu);
+                out[(size_t)p * 3 + 1] = (uint8_t)((rgb >> 8) & 0xFFu);
+                out[(size_t)p * 3 + 2] = (uint8_t)(rgb >> 16);
+                if (out_ids) out_ids[p] = 0xFFFFFFFFu - low;
+            }
         }
-    }
+        row_lo += sc.band_rows;
+    } while (BANDED && row_lo < sc.H);
     PXR_PHASE_MARK(6);
 }
 
-template <int NT, int PX>
+template <int NT, int PX, bool BANDED>
 int launch_one(const SceneConsts& sc, const DistractConsts& dc, const float* d_poses, const float* d_shapes,
                uint32_t n_frames, uint32_t S, uint32_t step0, uint32_t env0, uint8_t* d_frames, uint32_t* d_ids,
                hipStream_t stream, std::string& err) {
-    hipLaunchKernelGGL((render_kernel<NT, PX>), dim3(n_frames), dim3(NT), sc.lds_total, stream, sc, dc, d_poses, d_shapes, S,
-                       step0, env0, d_frames, d_ids);
+    hipLaunchKernelGGL((render_kernel<NT, PX, BANDED>), dim3(n_frames), dim3(NT), sc.lds_total, stream, sc, dc, d_poses,
+                       d_shapes, S, step0, env0, d_frames, d_ids);
     const hipError_t rc = hipGetLastError();
     if (rc != hipSuccess) {
         err = std::string("kernel launch failed: ") + hipGetErrorString(rc);
@@ -689,9 +705,9 @@ int launch_one(const SceneConsts& sc, const DistractConsts& dc, const float* d_p
     return PXR_OK;
 }
 
-template <int NT, int PX>
+template <int NT, int PX, bool BANDED>
 int prepare_one(uint32_t lds_bytes, std::string& err) {
-    const hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&render_kernel<NT, PX>),
+    const hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&render_kernel<NT, PX, BANDED>),
                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (rc != hipSuccess) {
         err = std::string("hipFuncSetAttribute(MaxDynamicSharedMemorySize) failed: ") + hipGetErrorString(rc);
@@ -700,7 +716,15 @@ int prepare_one(uint32_t lds_bytes, std::string& err) {
     return PXR_OK;
 }
 
-}  // namespace
+template <int NT>
+int prepare_all(uint32_t cap, std::string& err) {
+    int rc;
+    if ((rc = prepare_one<NT, 4, false>(cap, err))) return rc;
+    if ((rc = prepare_one<NT, 4, true>(cap, err))) return rc;
+    if ((rc = prepare_one<NT, 1, false>(cap, err))) return rc;
+    if ((rc = prepare_one<NT, 1, true>(cap, err))) return rc;
+    return PXR_OK;
+}
 
 #ifdef PXR_PHASE_TIMING
 extern "C" int pxr_debug_phase_cycles(unsigned long long* out, int reset) {
@@ -713,20 +737,18 @@ extern "C" int pxr_debug_phase_cycles(unsigned long long* out, int reset) {
 }
 #endif
 
+}  // namespace
+
 int prepare_kernels(uint32_t lds_bytes, std::string& err) {
     // The attribute is a per-kernel cap, not a per-launch size: always raise it
     // to the whole 160 KB so that scenes of different sizes can coexist.
     (void)lds_bytes;
     const uint32_t cap = 160u * 1024u;
     int rc;
-    if ((rc = prepare_one<256, 4>(cap, err))) return rc;
-    if ((rc = prepare_one<512, 4>(cap, err))) return rc;
-    if ((rc = prepare_one<768, 4>(cap, err))) return rc;
-    if ((rc = prepare_one<1024, 4>(cap, err))) return rc;
-    if ((rc = prepare_one<256, 1>(cap, err))) return rc;
-    if ((rc = prepare_one<512, 1>(cap, err))) return rc;
-    if ((rc = prepare_one<768, 1>(cap, err))) return rc;
-    if ((rc = prepare_one<1024, 1>(cap, err))) return rc;
+    if ((rc = prepare_all<256>(cap, err))) return rc;
+    if ((rc = prepare_all<512>(cap, err))) return rc;
+    if ((rc = prepare_all<768>(cap, err))) return rc;
+    if ((rc = prepare_all<1024>(cap, err))) return rc;
     return PXR_OK;
 }
 
@@ -736,9 +758,11 @@ int launch_render(const SceneConsts& sc, const DistractConsts& dc, const float* 
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     // four pixels per lane: they must share a row and frames must stay dword-aligned
     const bool quad = (sc.W % 4u) == 0u;
-#define PXR_LAUNCH(NT)                                                                                                   \
-    return quad ? launch_one<NT, 4>(sc, dc, d_poses, d_shapes, n_frames, S, step0, env0, d_frames, d_ids, st, err)       \
-                : launch_one<NT, 1>(sc, dc, d_poses, d_shapes, n_frames, S, step0, env0, d_frames, d_ids, st, err)
+    const bool banded = sc.band_rows < sc.H;
+#define PXR_ARGS sc, dc, d_poses, d_shapes, n_frames, S, step0, env0, d_frames, d_ids, st, err
+#define PXR_LAUNCH(NT)                                                                        \
+    return quad ? (banded ? launch_one<NT, 4, true>(PXR_ARGS) : launch_one<NT, 4, false>(PXR_ARGS)) \
+                : (banded ? launch_one<NT, 1, true>(PXR_ARGS) : launch_one<NT, 1, false>(PXR_ARGS))
     switch (block_threads) {
         case 256: PXR_LAUNCH(256);
         case 512: PXR_LAUNCH(512);
@@ -749,6 +773,7 @@ int launch_render(const SceneConsts& sc, const DistractConsts& dc, const float* 
             return PXR_ERR_INVALID_ARG;
     }
 #undef PXR_LAUNCH
+#undef PXR_ARGS
 }
 
 }  // namespace pxr

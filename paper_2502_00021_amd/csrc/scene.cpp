@@ -353,32 +353,45 @@ int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
     c.gs[1] = (float)((double)d.ground_grey[1] * lit);
     for (int i = 0; i < 3; ++i) c.bg[i] = d.background_rgb[i];
 
-    // ---- LDS carve-up of one frame workgroup
+    // ---- LDS carve-up of one frame workgroup.  The pixel keys dominate for tall frames; they are
+    // kept for `band_rows` rows at a time.  Prefer the fewest bands that let two workgroups share a
+    // compute unit (80 KB each); failing that, the fewest bands that fit at all.
     auto align = [](uint32_t x, uint32_t a) { return (x + a - 1) / a * a; };
-    uint32_t o = 0;
-    c.lds_keys = o;  // 16-byte aligned regions first
-    o += align(std::max(c.npix * 8, c.V * 4 + c.T * 2), 16);
-    c.lds_cxcy = o;
-    o += align((c.W + c.H) * 4, 16);
-    c.lds_misc = o;
-    o += 64 * 4;
-    c.lds_body = o;
-    o += c.K * kBodyStride * 4;
-    c.lds_vx = o;
-    o += c.V * 4;
-    c.lds_vy = o;
-    o += c.V * 4;
-    c.lds_vd = o;
-    o += c.V * 4;
-    c.lds_list = o;
-    o += align(c.T * 2, 4);
-    c.lds_large = o;
-    o += align(c.T * 2, 4);
-    c.lds_total = align(o, 16);
-    if (c.lds_total > 160u * 1024u) {
-        err = "scene needs " + std::to_string(c.lds_total) + " bytes of LDS per frame; the limit is 163840";
+    auto layout = [&](uint32_t n_bands) {
+        c.band_rows = (c.H + n_bands - 1) / n_bands;
+        uint32_t o = 0;
+        c.lds_keys = o;  // 16-byte aligned regions first
+        o += align(std::max(c.band_rows * c.W * 8, c.V * 4 + c.T * 2), 16);
+        c.lds_cxcy = o;
+        o += align((c.W + c.H) * 4, 16);
+        c.lds_misc = o;
+        o += 64 * 4;
+        c.lds_body = o;
+        o += c.K * kBodyStride * 4;
+        c.lds_vx = o;
+        o += c.V * 4;
+        c.lds_vy = o;
+        o += c.V * 4;
+        c.lds_vd = o;
+        o += c.V * 4;
+        c.lds_list = o;
+        o += align(c.T * 2, 4);
+        c.lds_large = o;
+        o += align(c.T * 2, 4);
+        c.lds_total = align(o, 16);
+        return c.lds_total;
+    };
+    const uint32_t kHalf = 80u * 1024u, kAll = 160u * 1024u, kMaxBands = 8;
+    uint32_t chosen = 0;
+    for (uint32_t nb = 1; nb <= kMaxBands && !chosen; ++nb)
+        if (layout(nb) <= kHalf) chosen = nb;
+    for (uint32_t nb = 1; nb <= kMaxBands && !chosen; ++nb)
+        if (layout(nb) <= kAll) chosen = nb;
+    if (!chosen) {
+        err = "scene needs " + std::to_string(layout(kMaxBands)) + " bytes of LDS per frame; the limit is 163840";
         return PXR_ERR_UNSUPPORTED;
     }
+    layout(chosen);
     return PXR_OK;
 }
 
