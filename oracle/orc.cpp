@@ -14,6 +14,7 @@
 //   G  ground      z=0 plane by per-pixel ray, 1 m checkerboard; background
 //   S  shade       flat Lambert + ambient
 //   X  distractor  colour jitter or video blend, then uint8 quantisation
+//   F  kinematics  (optional producer stage) hinge angles -> body poses
 //
 // Build: g++ -O2 -ffp-contract=off -fno-fast-math.  `float` is IEEE binary32
 // and every fp32 operation is rounded on its own unless written as fmaf().
@@ -631,6 +632,85 @@ int orc_render(const orc_scene* s, const float* poses, const float* shapes, uint
             if (ids) std::memcpy(ids + frame * npix, zb.id.data(), npix * 4);
             if (depth_bits) for (size_t p = 0; p < npix; ++p) depth_bits[frame * npix + p] = fbits(zb.depth[p]);
         }
+    }
+    return 0;
+}
+
+// ---------------------------------------------------------------- F: forward kinematics
+//
+// sin(theta/2), cos(theta/2): h = theta/2; k = nearest integer to h*(2/pi) (ties to even);
+// r = h - k*pi/2 with pi/2 split in two fp32 parts; odd / even Taylor polynomials in r
+// (|r| <= pi/4: truncation error below 2e-9); quadrant from k mod 4.
+void orc_sincos_half(float theta, float* s_out, float* c_out) {
+    const float h = 0.5f * theta;
+    const float kf = std::nearbyint(h * 0.636619772f);
+    float r = std::fmaf(kf, -1.57079625f, h);
+    r = std::fmaf(kf, -7.54978942e-08f, r);
+    const float r2 = r * r;
+    float ps = std::fmaf(r2, 2.75573192e-06f, -1.98412698e-04f);
+    ps = std::fmaf(ps, r2, 8.33333333e-03f);
+    ps = std::fmaf(ps, r2, -1.66666667e-01f);
+    const float sp = std::fmaf(r * r2, ps, r);
+    float pc = std::fmaf(r2, -2.75573192e-07f, 2.48015873e-05f);
+    pc = std::fmaf(pc, r2, -1.38888889e-03f);
+    pc = std::fmaf(pc, r2, 4.16666667e-02f);
+    pc = std::fmaf(pc, r2, -0.5f);
+    const float cp = std::fmaf(pc, r2, 1.0f);
+    const int q = (int)kf & 3;
+    *s_out = q == 0 ? sp : (q == 1 ? cp : (q == 2 ? -sp : -cp));
+    *c_out = q == 0 ? cp : (q == 1 ? -sp : (q == 2 ? -cp : sp));
+}
+
+namespace {
+void quat_matrix(const float* q, float R[3][3]) {  // same formulas as the vertex stage (V)
+    const float w = q[0], x = q[1], y = q[2], z = q[3];
+    R[0][0] = 1.0f - 2.0f * (y * y + z * z);
+    R[0][1] = 2.0f * (x * y - w * z);
+    R[0][2] = 2.0f * (x * z + w * y);
+    R[1][0] = 2.0f * (x * y + w * z);
+    R[1][1] = 1.0f - 2.0f * (x * x + z * z);
+    R[1][2] = 2.0f * (y * z - w * x);
+    R[2][0] = 2.0f * (x * z - w * y);
+    R[2][1] = 2.0f * (y * z + w * x);
+    R[2][2] = 1.0f - 2.0f * (x * x + y * y);
+}
+}  // namespace
+
+int orc_fk(uint32_t n_bodies, const int32_t* parent, const int32_t* slot, const float* anchor, const float* axis,
+           const float* offset, const float* free_poses, const float* angles, float* out) {
+    for (uint32_t k = 0; k < n_bodies; ++k) {
+        float* o = out + (size_t)k * 7;
+        if (parent[k] < 0) {
+            if (slot[k] < 0) return 1;
+            for (int i = 0; i < 7; ++i) o[i] = free_poses[(size_t)slot[k] * 7 + i];
+            continue;
+        }
+        if ((uint32_t)parent[k] >= k) return 1;
+        const float* pp = out + (size_t)parent[k] * 7;
+        const float* pq = pp + 3;
+        const float theta = slot[k] >= 0 ? angles[slot[k]] : 0.0f;
+        float sn, cs;
+        orc_sincos_half(theta, &sn, &cs);
+        const float* u = axis + (size_t)k * 3;
+        const float jw = cs, jx = sn * u[0], jy = sn * u[1], jz = sn * u[2];
+        const float pw = pq[0], px = pq[1], py = pq[2], pz = pq[3];
+        // Hamilton product parent (x) joint
+        float q[4];
+        q[0] = std::fmaf(-pz, jz, std::fmaf(-py, jy, std::fmaf(-px, jx, pw * jw)));
+        q[1] = std::fmaf(py, jz, std::fmaf(-pz, jy, std::fmaf(px, jw, pw * jx)));
+        q[2] = std::fmaf(pz, jx, std::fmaf(-px, jz, std::fmaf(py, jw, pw * jy)));
+        q[3] = std::fmaf(px, jy, std::fmaf(-py, jx, std::fmaf(pz, jw, pw * jz)));
+        float Rp[3][3], Rk[3][3];
+        quat_matrix(pq, Rp);
+        quat_matrix(q, Rk);
+        const float* a = anchor + (size_t)k * 3;
+        const float* c = offset + (size_t)k * 3;
+        for (int r = 0; r < 3; ++r) {
+            const float t1 = dot3(Rp[r], a[0], a[1], a[2]);
+            const float t2 = dot3(Rk[r], c[0], c[1], c[2]);
+            o[r] = (pp[r] + t1) + t2;
+        }
+        for (int i = 0; i < 4; ++i) o[3 + i] = q[i];
     }
     return 0;
 }

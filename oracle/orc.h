@@ -21,7 +21,8 @@
  * pixel counts and watertightness; convex cover count; front set == back set;
  * exact rational point-in-triangle; permutation invariance; analytic and
  * Moller-Trumbore ray casts; horizon row; shade extremes; RNG bijectivity and
- * statistics; distractor identities.
+ * statistics; distractor identities; kinematics against float64 quaternion algebra (an independent
+ * numpy implementation) and libm sin/cos.
  * Parity unpinned: agreement of orc_philox with the published Philox-4x32-10
  * known-answer vectors (none are available offline; the method only needs a
  * reproducible, well-mixed counter-based generator, which the pins do check).
@@ -112,6 +113,18 @@ typedef struct {
 int orc_render(const orc_scene* s, const float* poses, const float* shapes, uint32_t B, uint32_t S,
                uint32_t step0, uint32_t env0, const orc_distractor* dis, const uint32_t* order,
                uint8_t* frames, uint32_t* ids, uint32_t* depth_bits);
+
+/* Forward kinematics for ONE frame (producer stage in front of the renderer: the paper's loop keeps the
+ * simulator state on the device, section 1; here joint angles become body poses without leaving it).
+ * Body k is either free (parent[k] < 0: its pose is free_poses[slot[k]], copied verbatim) or hangs on
+ * body parent[k] < k by a hinge: anchor[k] = hinge position in the parent's frame, axis[k] = unit hinge
+ * axis, offset[k] = body centre relative to the hinge in the body's own frame, angle = angles[slot[k]]
+ * (slot[k] < 0: rigidly attached, angle 0).  All arithmetic fp32 in a fixed order (orc.cpp, section F).
+ * out_poses[K*7] = px,py,pz,qw,qx,qy,qz.  Returns non-zero on a malformed skeleton. */
+int orc_fk(uint32_t n_bodies, const int32_t* parent, const int32_t* slot, const float* anchor, const float* axis,
+           const float* offset, const float* free_poses, const float* angles, float* out_poses);
+/* sin and cos of theta/2 as the kinematics stage computes them (range reduction + polynomials). */
+void orc_sincos_half(float theta, float* s, float* c);
 
 /* Counter-based generator: 10 rounds of the 4x32 multiply/xor network on
  * counter (c0..c3) under the 64-bit key `seed`; out[4]. */

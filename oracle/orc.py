@@ -67,6 +67,10 @@ def lib():
         _lib.orc_philox.restype = None
         _lib.orc_u01.argtypes = [u32]
         _lib.orc_u01.restype = f32
+        _lib.orc_fk.argtypes = [u32] + [vp] * 8
+        _lib.orc_fk.restype = C.c_int
+        _lib.orc_sincos_half.argtypes = [f32, vp, vp]
+        _lib.orc_sincos_half.restype = None
     return _lib
 
 
@@ -217,3 +221,28 @@ def philox(seed, c0, c1, c2, c3):
 
 def u01(x):
     return float(lib().orc_u01(int(x)))
+
+
+def sincos_half(theta):
+    s, c = C.c_float(), C.c_float()
+    lib().orc_sincos_half(float(theta), C.byref(s), C.byref(c))
+    return s.value, c.value
+
+
+def fk(skel, free_poses, angles):
+    """Forward kinematics over a batch: skel = dict(parent, slot, anchor, axis, offset) of length-K arrays,
+    free_poses [..., F, 7], angles [..., J] -> poses [..., K, 7] (fp32)."""
+    parent = np.ascontiguousarray(skel["parent"], dtype=np.int32)
+    slot = np.ascontiguousarray(skel["slot"], dtype=np.int32)
+    anchor, axis, offset = _f32(skel["anchor"]), _f32(skel["axis"]), _f32(skel["offset"])
+    K = parent.shape[0]
+    free_poses, angles = _f32(free_poses), _f32(angles)
+    lead = free_poses.shape[:-2]
+    fp = free_poses.reshape(-1, free_poses.shape[-2], 7)
+    an = angles.reshape(fp.shape[0], -1)
+    out = np.empty((fp.shape[0], K, 7), np.float32)
+    for n in range(fp.shape[0]):
+        rc = lib().orc_fk(K, _p(parent), _p(slot), _p(anchor), _p(axis), _p(offset), _p(fp[n]), _p(an[n]), _p(out[n]))
+        if rc:
+            raise ValueError("orc_fk rejected the skeleton")
+    return out.reshape(*lead, K, 7)

@@ -87,6 +87,19 @@ def _pose(pos, quat):
 EZ = np.array([0.0, 0.0, 1.0])
 
 
+# ------------------------------------------------------------------ skeleton descriptions (inputs of the kinematics stage)
+
+def _skeleton(K):
+    """All bodies free-floating until hinged: parent -1, slot = index into the free poses / the angles."""
+    return dict(parent=np.full(K, -1, np.int32), slot=np.full(K, -1, np.int32), anchor=np.zeros((K, 3), np.float32),
+                axis=np.tile(np.array([1.0, 0.0, 0.0], np.float32), (K, 1)), offset=np.zeros((K, 3), np.float32))
+
+
+def _hinge(skel, k, parent, slot, anchor, axis, offset):
+    skel["parent"][k], skel["slot"][k] = parent, slot
+    skel["anchor"][k], skel["axis"][k], skel["offset"][k] = anchor, axis, offset
+
+
 # ------------------------------------------------------------------ the five configurations
 
 def cfg1(B=16):
@@ -126,8 +139,14 @@ def cfg2(B=256):
         start = centre + h[i] * axis
         pos[:, 0, i] = centre
         quat[:, 0, i] = q
-    return dict(name="cfg2-chain-64", desc=default_scene(64, 64, bodies), poses=_pose(pos, quat),
-                shapes=None, distractor=None, step0=0)
+    poses = _pose(pos, quat)
+    skel = _skeleton(K)
+    skel["slot"][0] = 0  # link 0 is free
+    for i in range(1, K):
+        _hinge(skel, i, parent=i - 1, slot=i - 1, anchor=(0, 0, h[i - 1]), axis=(1, 0, 0), offset=(0, 0, h[i]))
+    fk = dict(skel=skel, free_poses=poses[:, :, :1].copy(), angles=theta[:, None, 1:].astype(np.float32))
+    return dict(name="cfg2-chain-64", desc=default_scene(64, 64, bodies), poses=poses,
+                shapes=None, distractor=None, step0=0, fk=fk)
 
 
 def cfg3(B=4096):
@@ -159,8 +178,16 @@ def cfg3(B=4096):
         pos[:, 0, 2 + 2 * leg] = knee + hl * d2
         quat[:, 0, 2 + 2 * leg] = q2
     dis = dict(mode="color", seed=SEED_BASE + 3, scale=(0.5, 1.5), offset=(-0.2, 0.2))
-    return dict(name="cfg3-quadruped-64", desc=default_scene(64, 64, bodies), poses=_pose(pos, quat),
-                shapes=None, distractor=dis, step0=0)
+    poses = _pose(pos, quat)
+    skel = _skeleton(K)
+    skel["slot"][0] = 0
+    for leg in range(4):
+        _hinge(skel, 1 + 2 * leg, parent=0, slot=2 * leg, anchor=hips[leg], axis=(0, 1, 0), offset=(0, 0, -hl))
+        _hinge(skel, 2 + 2 * leg, parent=1 + 2 * leg, slot=2 * leg + 1, anchor=(0, 0, -hl), axis=(0, 1, 0),
+               offset=(0, 0, -hl))
+    fk = dict(skel=skel, free_poses=poses[:, :, :1].copy(), angles=ang.reshape(B, 1, 8).astype(np.float32))
+    return dict(name="cfg3-quadruped-64", desc=default_scene(64, 64, bodies), poses=poses,
+                shapes=None, distractor=dis, step0=0, fk=fk)
 
 
 def _humanoid_scene(rng):
@@ -201,6 +228,19 @@ def _humanoid_fk(q_root, root, angles, half, axes, anchors):
     return pos, quat
 
 
+def _humanoid_skeleton(K, half, axes, anchors):
+    skel = _skeleton(K)
+    skel["slot"][0] = 0
+    _hinge(skel, 1, parent=0, slot=-1, anchor=(0, 0, 0.38), axis=(1, 0, 0), offset=(0, 0, 0))  # head, rigid
+    for limb in range(4):
+        for k in range(3):
+            idx = 2 + limb * 3 + k
+            _hinge(skel, idx, parent=0 if k == 0 else idx - 1, slot=limb * 3 + k,
+                   anchor=anchors[limb] if k == 0 else (0, 0, -half[limb, k - 1]), axis=axes[limb, k],
+                   offset=(0, 0, -half[limb, k]))
+    return skel
+
+
 def make_video(rng, n_frames, H, W):
     """Synthetic distractor video [n,H,W,3] uint8: dark random-grey background + 6 moving random-colour discs."""
     grey = rng.integers(10, 50, (H, W, 1))
@@ -230,8 +270,11 @@ def cfg4(B=16384):
     root = np.broadcast_to(np.array([0.0, 0.0, 1.25]), (B, 3))
     pos, quat = _humanoid_fk(q_root, root, angles, half, axes, anchors)
     dis = dict(mode="video", seed=SEED_BASE + 4, video=video, alpha=0.5, env_offset=None)
+    poses = _pose(pos[:, None], quat[:, None])
+    fk = dict(skel=_humanoid_skeleton(14, half, axes, anchors), free_poses=poses[:, :, :1].copy(),
+              angles=angles.reshape(B, 1, 12).astype(np.float32))
     return dict(name="cfg4-humanoid-84-video", desc=default_scene(84, 84, bodies),
-                poses=_pose(pos[:, None], quat[:, None]), shapes=None, distractor=dis, step0=0)
+                poses=poses, shapes=None, distractor=dis, step0=0, fk=fk)
 
 
 def cfg5(B=65536, S=3):
@@ -251,9 +294,11 @@ def cfg5(B=65536, S=3):
     angles = rng.uniform(-1.0, 1.0, (B, 4, 3))
     pos = np.zeros((B, S, K, 3))
     quat = np.zeros((B, S, K, 4))
+    all_angles = np.zeros((B, S, 12), np.float32)
     for s in range(S):
         if s > 0:
             angles = angles + rng.normal(0.0, 0.05, (B, 4, 3))
+        all_angles[:, s] = angles.reshape(B, 12)
         p, q = _humanoid_fk(q_root, root, angles, half, axes, anchors)
         pos[:, s, :14] = p
         quat[:, s, :14] = q
@@ -264,8 +309,12 @@ def cfg5(B=65536, S=3):
         shapes[:, k] = np.asarray(bodies[k]["shape"], np.float32)
     shapes[:, 14, :3] = ext.astype(np.float32)
     dis = dict(mode="color", seed=SEED_BASE + 5, scale=(0.5, 1.5), offset=(-0.2, 0.2))
+    poses = _pose(pos, quat)
+    skel = _humanoid_skeleton(K, half, axes, anchors)
+    skel["slot"][14] = 1  # the box is the second free body
+    fk = dict(skel=skel, free_poses=np.ascontiguousarray(poses[:, :, [0, 14]]), angles=all_angles)
     return dict(name="cfg5-humanoid-box-64-stack3", desc=default_scene(64, 64, bodies),
-                poses=_pose(pos, quat), shapes=shapes, distractor=dis, step0=0)
+                poses=poses, shapes=shapes, distractor=dis, step0=0, fk=fk)
 
 
 CONFIGS = {1: cfg1, 2: cfg2, 3: cfg3, 4: cfg4, 5: cfg5}
