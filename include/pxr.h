@@ -130,6 +130,47 @@ int pxr_apply_distractor(pxr_scene* s, const pxr_distractor_desc* d);
 int pxr_render_batch(pxr_scene* s, const float* d_poses, const float* d_shapes, uint32_t B, uint32_t S,
                      uint32_t step0, uint32_t env0, uint8_t* d_frames, uint32_t* d_ids, void* hip_stream);
 
+/* Kinematic tree of the scene's bodies, for callers whose simulator state is joint angles rather than
+ * body poses (the paper's loop keeps that state on the device, section 1; this stage turns it into the
+ * renderer's input there).  All arrays are host memory, copied by pxr_set_skeleton.
+ *   parent[k]  -1: body k is free, its pose is free pose number slot[k] (0 <= slot[k] < n_free), copied
+ *              verbatim; otherwise body k hangs on body parent[k] < k by a hinge
+ *   slot[k]    hinged body: index of its angle (0 <= slot[k] < n_angles), or -1 = rigidly attached (angle 0)
+ *   anchor[k]  hinge position in the parent's frame; axis[k] unit hinge axis (same in both frames);
+ *   offset[k]  body centre relative to the hinge, in the body's own frame   (each [n_bodies*3])
+ * Pose of a hinged body: q = q_parent (x) (cos(a/2), sin(a/2) axis);
+ *   p = (p_parent + R(q_parent) anchor) + R(q) offset,  fp32, R as in the vertex stage, sin/cos of a/2 by a
+ *   two-term pi/2 reduction and degree-9 / degree-10 Taylor polynomials (device-independent). */
+typedef struct {
+    uint32_t n_bodies, n_free, n_angles;
+    const int32_t* parent;
+    const int32_t* slot;
+    const float* anchor;
+    const float* axis;
+    const float* offset;
+} pxr_skeleton_desc;
+
+/* Bind (or with k == NULL remove) the scene's skeleton.  Host only; one small allocation and upload.  The
+ * caller must have synchronised streams still using the previous skeleton.
+ * Errors: INVALID_ARG (null array, n_bodies != the scene's, parent[k] >= k, slot out of range, non-finite
+ * entry); UNSUPPORTED (the 64 frames a wavefront poses at a time do not fit the 160 KB of LDS:
+ * (7*n_bodies + 7*n_free + n_angles) * 260 bytes); OOM; DEVICE. */
+int pxr_set_skeleton(pxr_scene* s, const pxr_skeleton_desc* k);
+
+/* Forward kinematics for N frames: d_free_poses [N,n_free,7] and d_angles [N,n_angles] (may be NULL when
+ * the count is 0) -> d_poses [N,n_bodies,7] (xyz, wxyz), all fp32 device buffers, 4-byte aligned.  One kernel,
+ * one lane per frame; enqueue only.  Errors: INVALID_ARG (no skeleton bound, null or misaligned buffer,
+ * N == 0); DEVICE. */
+int pxr_pose_batch(pxr_scene* s, const float* d_free_poses, const float* d_angles, uint32_t n_frames,
+                   float* d_poses, void* hip_stream);
+
+/* pxr_pose_batch over B*S frames followed by pxr_render_batch on the same stream: joint angles in, frames
+ * out, nothing crossing the host.  d_poses [B,S,n_bodies,7] is caller-provided and receives the poses (a
+ * learner usually wants them as well); the other arguments are those of the two calls. */
+int pxr_render_batch_kinematic(pxr_scene* s, const float* d_free_poses, const float* d_angles, const float* d_shapes,
+                               uint32_t B, uint32_t S, uint32_t step0, uint32_t env0, float* d_poses,
+                               uint8_t* d_frames, uint32_t* d_ids, void* hip_stream);
+
 /* Scene facts for callers and tests: total template vertices and triangles,
  * dynamic LDS bytes per frame workgroup, threads per workgroup.  Any out
  * pointer may be NULL. */

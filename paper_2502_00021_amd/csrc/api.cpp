@@ -13,6 +13,8 @@ struct pxr_scene {
     pxr::SceneConsts sc{};
     pxr::DistractConsts dc{};
     void* d_arena = nullptr;
+    pxr::SkeletonConsts sk{};
+    void* d_skeleton = nullptr;
     int device = 0;
     uint32_t block_threads = 0;
     uint32_t default_threads = 0;
@@ -113,7 +115,11 @@ int pxr_create_scene(const pxr_scene_desc* desc, pxr_scene** out) {
 
 int pxr_destroy_scene(pxr_scene* s) {
     if (!s) return PXR_OK;
-    const hipError_t hrc = hipFree(s->d_arena);
+    hipError_t hrc = hipFree(s->d_arena);
+    if (s->d_skeleton) {
+        const hipError_t hrc2 = hipFree(s->d_skeleton);
+        if (hrc == hipSuccess) hrc = hrc2;
+    }
     delete s;
     if (hrc != hipSuccess) return fail(PXR_ERR_DEVICE, std::string("pxr_destroy_scene: hipFree failed: ") + hipGetErrorString(hrc));
     return PXR_OK;
@@ -171,6 +177,101 @@ int pxr_render_batch(pxr_scene* s, const float* d_poses, const float* d_shapes, 
                                       s->block_threads, hip_stream, err);
     if (rc != PXR_OK) return fail(rc, "pxr_render_batch: " + err);
     return PXR_OK;
+}
+
+int pxr_set_skeleton(pxr_scene* s, const pxr_skeleton_desc* k) {
+    if (!s) return fail(PXR_ERR_INVALID_ARG, "pxr_set_skeleton: null scene");
+    if (!k) {
+        if (s->d_skeleton) (void)hipFree(s->d_skeleton);
+        s->d_skeleton = nullptr;
+        s->sk = pxr::SkeletonConsts{};
+        return PXR_OK;
+    }
+    if (!k->parent || !k->slot || !k->anchor || !k->axis || !k->offset)
+        return fail(PXR_ERR_INVALID_ARG, "pxr_set_skeleton: null array");
+    const uint32_t K = s->sc.K;
+    if (k->n_bodies != K) return fail(PXR_ERR_INVALID_ARG, "pxr_set_skeleton: n_bodies differs from the scene's");
+    for (uint32_t b = 0; b < K; ++b) {
+        const int32_t p = k->parent[b], sl = k->slot[b];
+        if (p < 0) {
+            if (sl < 0 || (uint32_t)sl >= k->n_free)
+                return fail(PXR_ERR_INVALID_ARG, "pxr_set_skeleton: a free body needs a slot in [0, n_free)");
+        } else {
+            if ((uint32_t)p >= b) return fail(PXR_ERR_INVALID_ARG, "pxr_set_skeleton: a parent must precede its child");
+            if (sl < -1 || (sl >= 0 && (uint32_t)sl >= k->n_angles))
+                return fail(PXR_ERR_INVALID_ARG, "pxr_set_skeleton: hinge slot outside [-1, n_angles)");
+        }
+        for (int c = 0; c < 3; ++c)
+            if (!std::isfinite(k->anchor[b * 3 + c]) || !std::isfinite(k->axis[b * 3 + c]) ||
+                !std::isfinite(k->offset[b * 3 + c]))
+                return fail(PXR_ERR_INVALID_ARG, "pxr_set_skeleton: non-finite anchor, axis or offset");
+    }
+    pxr::SkeletonConsts sk{};
+    sk.K = K;
+    sk.J = k->n_angles;
+    sk.F = k->n_free;
+    if ((uint64_t)sk.J + 7ull * sk.F + 7ull * K > 630ull || pxr::fk_lds_bytes(sk) > 160u * 1024u)
+        return fail(PXR_ERR_UNSUPPORTED, "pxr_set_skeleton: 64 frames of this skeleton do not fit 160 KB of LDS");
+    // one allocation: parent[K], slot[K], hinge[K][9]
+    std::vector<uint32_t> staging((size_t)K * 11);
+    for (uint32_t b = 0; b < K; ++b) {
+        staging[b] = (uint32_t)k->parent[b];
+        staging[K + b] = (uint32_t)k->slot[b];
+        float h[9];
+        for (int c = 0; c < 3; ++c) {
+            h[c] = k->anchor[b * 3 + c];
+            h[3 + c] = k->axis[b * 3 + c];
+            h[6 + c] = k->offset[b * 3 + c];
+        }
+        std::memcpy(&staging[2 * (size_t)K + (size_t)b * 9], h, sizeof(h));
+    }
+    std::string err;
+    int rc = pxr::prepare_fk_kernel(err);
+    if (rc != PXR_OK) return fail(rc, "pxr_set_skeleton: " + err);
+    void* d = nullptr;
+    hipError_t hrc = hipMalloc(&d, staging.size() * 4);
+    if (hrc != hipSuccess)
+        return fail(hrc == hipErrorOutOfMemory ? PXR_ERR_OOM : PXR_ERR_DEVICE,
+                    std::string("pxr_set_skeleton: hipMalloc failed: ") + hipGetErrorString(hrc));
+    hrc = hipMemcpy(d, staging.data(), staging.size() * 4, hipMemcpyHostToDevice);
+    if (hrc != hipSuccess) {
+        (void)hipFree(d);
+        return fail(PXR_ERR_DEVICE, std::string("pxr_set_skeleton: upload failed: ") + hipGetErrorString(hrc));
+    }
+    if (s->d_skeleton) (void)hipFree(s->d_skeleton);
+    s->d_skeleton = d;
+    sk.parent = static_cast<const int32_t*>(d);
+    sk.slot = sk.parent + K;
+    sk.hinge = reinterpret_cast<const float*>(sk.slot + K);
+    s->sk = sk;
+    return PXR_OK;
+}
+
+int pxr_pose_batch(pxr_scene* s, const float* d_free_poses, const float* d_angles, uint32_t n_frames, float* d_poses,
+                   void* hip_stream) {
+    if (!s) return fail(PXR_ERR_INVALID_ARG, "pxr_pose_batch: null scene");
+    if (!s->d_skeleton) return fail(PXR_ERR_INVALID_ARG, "pxr_pose_batch: no skeleton bound (pxr_set_skeleton)");
+    if (n_frames == 0 || n_frames > 0x7FFFFFFFu) return fail(PXR_ERR_INVALID_ARG, "pxr_pose_batch: n_frames must lie in [1, 2^31-1]");
+    if (!d_poses || (s->sk.F && !d_free_poses) || (s->sk.J && !d_angles))
+        return fail(PXR_ERR_INVALID_ARG, "pxr_pose_batch: null buffer");
+    if ((reinterpret_cast<uintptr_t>(d_free_poses) & 3u) || (reinterpret_cast<uintptr_t>(d_angles) & 3u) ||
+        (reinterpret_cast<uintptr_t>(d_poses) & 3u))
+        return fail(PXR_ERR_INVALID_ARG, "pxr_pose_batch: buffers must be 4-byte aligned");
+    std::string err;
+    const int rc = pxr::launch_fk(s->sk, d_free_poses, d_angles, n_frames, d_poses, hip_stream, err);
+    if (rc != PXR_OK) return fail(rc, "pxr_pose_batch: " + err);
+    return PXR_OK;
+}
+
+int pxr_render_batch_kinematic(pxr_scene* s, const float* d_free_poses, const float* d_angles, const float* d_shapes,
+                               uint32_t B, uint32_t S, uint32_t step0, uint32_t env0, float* d_poses, uint8_t* d_frames,
+                               uint32_t* d_ids, void* hip_stream) {
+    if (B == 0 || S == 0 || (uint64_t)B * S > 0x7FFFFFFFull)
+        return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch_kinematic: B*S must lie in [1, 2^31-1]");
+    if (!d_frames) return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch_kinematic: null frames");
+    int rc = pxr_pose_batch(s, d_free_poses, d_angles, B * S, d_poses, hip_stream);
+    if (rc != PXR_OK) return rc;
+    return pxr_render_batch(s, d_poses, d_shapes, B, S, step0, env0, d_frames, d_ids, hip_stream);
 }
 
 int pxr_scene_info(const pxr_scene* s, uint32_t* n_verts, uint32_t* n_tris, uint32_t* lds_bytes, uint32_t* block_threads) {

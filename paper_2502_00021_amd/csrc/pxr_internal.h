@@ -82,6 +82,14 @@ struct DistractConsts {
     const uint32_t* env_offset;
 };
 
+// Skeleton bound by pxr_set_skeleton (device tables live in their own allocation).
+struct SkeletonConsts {
+    uint32_t K, J, F;        // bodies, hinge angles per frame, free poses per frame
+    const int32_t* parent;   // [K]  -1 = free body
+    const int32_t* slot;     // [K]  free: index of its pose; hinged: index of its angle, -1 = rigid
+    const float* hinge;      // [K][9]  anchor (parent frame), unit axis, body centre relative to the hinge (body frame)
+};
+
 // Host-side result of tessellation + camera derivation.
 struct HostScene {
     SceneConsts c{};
@@ -97,13 +105,19 @@ struct HostScene {
 // left for the caller).  Returns a PXR_* code and a message on failure.
 int build_host_scene(const pxr_scene_desc& desc, HostScene& hs, std::string& err);
 
-// render.hip: enqueue one batch.  `block_threads` in {256,512,1024}.
+// render.hip: enqueue one batch.  `block_threads` in {256,512,768,1024}.
 int launch_render(const SceneConsts& sc, const DistractConsts& dc, const float* d_poses, const float* d_shapes,
                   uint32_t n_frames, uint32_t S, uint32_t step0, uint32_t env0, uint8_t* d_frames, uint32_t* d_ids,
                   uint32_t block_threads, void* stream, std::string& err);
 
 // render.hip: raise the dynamic-LDS limit of every kernel instantiation once.
 int prepare_kernels(uint32_t lds_bytes, std::string& err);
+
+// kinematics.hip: joint angles -> poses, one lane per frame.
+uint32_t fk_lds_bytes(const SkeletonConsts& sk);
+int prepare_fk_kernel(std::string& err);
+int launch_fk(const SkeletonConsts& sk, const float* d_free_poses, const float* d_angles, uint32_t n_frames,
+              float* d_poses, void* stream, std::string& err);
 
 }  // namespace pxr
 

@@ -1,8 +1,8 @@
 """ctypes binding of libpxr.so — argument marshalling only; every step runs in the HIP library.
 
 Mirrors include/pxr.h one to one: create_scene / destroy_scene /
-apply_distractor / render_batch (+ scene_info, set_block_threads,
-host_tables).  PyTorch is used only to hold device memory and name the stream.
+apply_distractor / render_batch, set_skeleton / pose_batch /
+render_batch_kinematic (+ scene_info, set_block_threads, host_tables).  PyTorch is used only to hold device memory and name the stream.
 There is no fallback: a missing library or a failing call raises.
 """
 import ctypes as C
@@ -48,6 +48,12 @@ class DistractorDesc(C.Structure):
                 ("d_env_offset", C.c_void_p)]
 
 
+class SkeletonDesc(C.Structure):
+    _fields_ = [("n_bodies", C.c_uint32), ("n_free", C.c_uint32), ("n_angles", C.c_uint32),
+                ("parent", C.c_void_p), ("slot", C.c_void_p), ("anchor", C.c_void_p), ("axis", C.c_void_p),
+                ("offset", C.c_void_p)]
+
+
 _lib = None
 
 
@@ -66,9 +72,13 @@ def lib():
         L.pxr_scene_info.argtypes = [vp, vp, vp, vp, vp]
         L.pxr_set_block_threads.argtypes = [vp, u32]
         L.pxr_host_tables.argtypes = [C.POINTER(SceneDesc), vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.pxr_set_skeleton.argtypes = [vp, C.POINTER(SkeletonDesc)]
+        L.pxr_pose_batch.argtypes = [vp, vp, vp, u32, vp, vp]
+        L.pxr_render_batch_kinematic.argtypes = [vp, vp, vp, vp, u32, u32, u32, u32, vp, vp, vp, vp]
         L.pxr_last_error.restype = C.c_char_p
         for name in ("pxr_create_scene", "pxr_destroy_scene", "pxr_apply_distractor", "pxr_render_batch",
-                     "pxr_scene_info", "pxr_set_block_threads", "pxr_host_tables"):
+                     "pxr_scene_info", "pxr_set_block_threads", "pxr_host_tables", "pxr_set_skeleton",
+                     "pxr_pose_batch", "pxr_render_batch_kinematic"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -145,6 +155,7 @@ class Scene:
         self._h = h
         self.W, self.H, self.K = d.width, d.height, d.n_bodies
         self._bound = []  # keeps bound distractor tensors alive
+        self._skel = None  # (n_free, n_angles) of the bound skeleton
 
     def close(self):
         if getattr(self, "_h", None):
@@ -217,6 +228,87 @@ class Scene:
                                       B, S, int(step0), int(env0), frames.data_ptr(),
                                       None if ids is None else ids.data_ptr(), C.c_void_p(stream)))
         return frames, ids
+
+
+    # ---- kinematics stage
+
+    def set_skeleton(self, skel, n_free, n_angles):
+        """skel: dict(parent, slot, anchor, axis, offset) of length-K host arrays (workloads._skeleton), or None."""
+        if skel is None:
+            _check(lib().pxr_set_skeleton(self._h, None))
+            self._skel = None
+            return
+        d, keep = make_skeleton_desc(skel, n_free, n_angles)
+        _check(lib().pxr_set_skeleton(self._h, C.byref(d)))
+        del keep
+        self._skel = (int(n_free), int(n_angles))
+
+    def _fk_args(self, free_poses, angles):
+        import torch
+        if self._skel is None:
+            raise PxrError(ERR_INVALID_ARG, "no skeleton bound (Scene.set_skeleton)")
+        F, J = self._skel
+        lead = tuple(free_poses.shape[:-2]) if F else tuple(angles.shape[:-1])
+        n = int(np.prod(lead))
+        if F:
+            assert free_poses.is_cuda and free_poses.dtype == torch.float32 and free_poses.is_contiguous()
+            assert tuple(free_poses.shape) == lead + (F, 7), tuple(free_poses.shape)
+        if J:
+            assert angles.is_cuda and angles.dtype == torch.float32 and angles.is_contiguous()
+            assert tuple(angles.shape) == lead + (J,), tuple(angles.shape)
+        dev = free_poses.device if F else angles.device
+        return lead, n, dev, (free_poses.data_ptr() if F else None), (angles.data_ptr() if J else None)
+
+    def pose_batch(self, free_poses, angles, poses=None, stream=None):
+        """free_poses: CUDA float32 [..., F, 7]; angles: CUDA float32 [..., J] -> poses [..., K, 7]; enqueue only."""
+        import torch
+        lead, n, dev, pf, pa = self._fk_args(free_poses, angles)
+        if poses is None:
+            poses = torch.empty(lead + (self.K, 7), dtype=torch.float32, device=dev)
+        else:
+            assert poses.is_cuda and poses.is_contiguous() and poses.dtype == torch.float32
+            assert tuple(poses.shape) == lead + (self.K, 7)
+        if stream is None:
+            stream = torch.cuda.current_stream(dev).cuda_stream
+        _check(lib().pxr_pose_batch(self._h, pf, pa, n, poses.data_ptr(), C.c_void_p(stream)))
+        return poses
+
+    def render_batch_kinematic(self, free_poses, angles, shapes=None, step0=0, env0=0, poses=None, frames=None,
+                               want_ids=False, stream=None):
+        """free_poses [B,S,F,7], angles [B,S,J] -> (frames, ids or None, poses [B,S,K,7]); enqueue only."""
+        import torch
+        lead, n, dev, pf, pa = self._fk_args(free_poses, angles)
+        B, S = lead
+        if poses is None:
+            poses = torch.empty((B, S, self.K, 7), dtype=torch.float32, device=dev)
+        if frames is None:
+            frames = torch.empty((B, S, self.H, self.W, 3), dtype=torch.uint8, device=dev)
+        assert poses.is_contiguous() and tuple(poses.shape) == (B, S, self.K, 7) and poses.dtype == torch.float32
+        assert frames.is_contiguous() and tuple(frames.shape) == (B, S, self.H, self.W, 3) and frames.dtype == torch.uint8
+        if shapes is not None:
+            assert shapes.is_cuda and shapes.dtype == torch.float32 and shapes.is_contiguous()
+            assert tuple(shapes.shape) == (B, self.K, 4)
+        ids = torch.empty((B, S, self.H, self.W), dtype=torch.int32, device=dev) if want_ids else None
+        if stream is None:
+            stream = torch.cuda.current_stream(dev).cuda_stream
+        _check(lib().pxr_render_batch_kinematic(self._h, pf, pa, None if shapes is None else shapes.data_ptr(), B, S,
+                                                int(step0), int(env0), poses.data_ptr(), frames.data_ptr(),
+                                                None if ids is None else ids.data_ptr(), C.c_void_p(stream)))
+        return frames, ids, poses
+
+
+def make_skeleton_desc(skel, n_free, n_angles):
+    """dict(parent, slot, anchor, axis, offset) -> (SkeletonDesc, keep-alive list)."""
+    parent = np.ascontiguousarray(skel["parent"], dtype=np.int32)
+    slot = np.ascontiguousarray(skel["slot"], dtype=np.int32)
+    arrs = [np.ascontiguousarray(skel[k], dtype=np.float32).reshape(-1) for k in ("anchor", "axis", "offset")]
+    K = parent.shape[0]
+    assert slot.shape == (K,) and all(a.shape == (K * 3,) for a in arrs)
+    d = SkeletonDesc()
+    d.n_bodies, d.n_free, d.n_angles = K, int(n_free), int(n_angles)
+    d.parent, d.slot = parent.ctypes.data, slot.ctypes.data
+    d.anchor, d.axis, d.offset = (a.ctypes.data for a in arrs)
+    return d, [parent, slot] + arrs
 
 
 def ids_to_numpy(ids):
