@@ -171,6 +171,43 @@ int pxr_render_batch_kinematic(pxr_scene* s, const float* d_free_poses, const fl
                                uint32_t B, uint32_t S, uint32_t step0, uint32_t env0, float* d_poses,
                                uint8_t* d_frames, uint32_t* d_ids, void* hip_stream);
 
+/* ---- frame consumer: the policy's first convolutional layer on the frame stack ----
+ * The paper's throughput loop ends every environment step with a forward pass through one convolutional
+ * layer on the observations (section 2); it gives no hyper-parameters.  Built here: 3x3 kernel, stride 2, no
+ * padding, 32 output channels, the S frames of an environment stacked on the channel axis (channel 3s + c),
+ * inputs scaled by 1/255:
+ *   out[b,oy,ox,o] = act(bias[o] + sum_{ky,kx,s,c} frames[b,s,2oy+ky,2ox+kx,c]/255 * bf16(w[ky,kx,3s+c,o]))
+ * weights rounded to bfloat16 (nearest even) at creation, products and sums in fp32 on the matrix cores,
+ * result = fma(sum, 1/255, bias), optional ReLU, rounded to bfloat16 (nearest even). */
+typedef struct pxr_conv pxr_conv; /* opaque, owned by the library */
+typedef struct {
+    uint32_t in_h, in_w, n_stack;  /* frames [B,n_stack,in_h,in_w,3] uint8 */
+    uint32_t c_out, kernel, stride; /* must be 32, 3, 2 */
+    const float* weights;          /* host [3][3][3*n_stack][32] (height, width, in, out), copied */
+    const float* bias;             /* host [32], copied */
+    uint32_t relu;                 /* 0 = linear output */
+} pxr_conv_desc;
+
+/* Host only.  Errors: INVALID_ARG (null, non-finite weight or bias); UNSUPPORTED (other layer shapes,
+ * n_stack outside [1,4], in_h outside [3,512], in_w outside [4,512] or not a multiple of 4); OOM; DEVICE. */
+int pxr_conv_create(const pxr_conv_desc* desc, pxr_conv** out);
+int pxr_conv_destroy(pxr_conv* c); /* NULL accepted; synchronise streams still using it first */
+
+/* d_frames [B,n_stack,in_h,in_w,3] uint8 (what pxr_render_batch writes for S = n_stack) ->
+ * d_out [B,out_h,out_w,32] bfloat16 bit patterns, out_h = (in_h-3)/2+1, out_w = (in_w-3)/2+1.
+ * Device buffers owned by the caller, d_frames 4-byte and d_out 16-byte aligned.  One kernel, enqueue only.
+ * Errors: INVALID_ARG (null, B == 0 or too large, misaligned); DEVICE. */
+int pxr_conv_forward(pxr_conv* c, const uint8_t* d_frames, uint32_t B, uint16_t* d_out, void* hip_stream);
+
+/* Output size, output rows per work item, LDS bytes per workgroup, persistent workgroups per launch.  Any
+ * pointer may be NULL. */
+int pxr_conv_info(const pxr_conv* c, uint32_t* out_h, uint32_t* out_w, uint32_t* band_rows, uint32_t* lds_bytes,
+                  uint32_t* n_groups);
+
+/* Tuning knob for benchmarks: output rows per work item and workgroups per launch (0 = default).  The
+ * output does not depend on it. */
+int pxr_conv_set_tuning(pxr_conv* c, uint32_t band_rows, uint32_t n_groups);
+
 /* Scene facts for callers and tests: total template vertices and triangles,
  * dynamic LDS bytes per frame workgroup, threads per workgroup.  Any out
  * pointer may be NULL. */

@@ -29,6 +29,12 @@ int fail(int code, const std::string& msg) {
     return code;
 }
 
+}  // namespace
+
+int pxr::set_error(int code, const std::string& msg) { return fail(code, msg); }
+
+namespace {
+
 uint32_t pick_block_threads(const pxr::SceneConsts& sc) {
     // Fill the 32 wave slots of a compute unit: LDS decides how many frame
     // workgroups are resident, the workgroup size makes up the rest.  (The

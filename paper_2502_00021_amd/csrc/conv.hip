@@ -1,0 +1,186 @@
+// Frame consumer of libpxr: the policy's first convolutional layer applied to
+// the rendered frame stack, straight from the uint8 frames (PixelBrax, arXiv
+// 2502.00021, section 2: every environment step of the paper's throughput loop
+// ends in a forward pass through one convolutional layer).  gfx950 only.
+//
+//   out[b,oy,ox,o] = act(bias[o] + sum_{ky,kx,s,c} frames[b,s,2oy+ky,2ox+kx,c]/255 * w[ky,kx,3s+c,o])
+//
+// 3x3 kernel, stride 2, no padding, 32 output channels, bf16 weights, fp32
+// accumulation, bf16 NHWC output.  This IS a dense contraction (per
+// environment a [Ho*Wo x 27S] x [27S x 32] product), so it runs on the matrix
+// cores (v_mfma_f32_32x32x16_bf16), but at ~50 FLOP per byte of HBM traffic it
+// is bound by HBM: the design goal is one read of every frame byte, one full
+// 64-byte-line write of every output pixel, and nothing else.
+//
+// Work item = (environment, band of output rows).  Workgroups are persistent
+// (the 36 registers of weights per lane are loaded once per wave) and walk the
+// items with a grid stride:
+//   load   the band's input rows of all S frames: 12-byte loads (4 RGB pixels),
+//          uint8 -> bf16 (exact), written to LDS as [frame][row][pixel][R,G,B,0]
+//   mma    one wavefront per (output row, 32-pixel tile): for each (frame, ky)
+//          ONE aligned 16-byte LDS read per lane is the B operand
+//          (2 pixels x 4 channels; lanes 0-31 take pixels 2ox, 2ox+1, lanes
+//          32-63 take 2ox+2, 2ox+3; the weights of pixel 2ox+3 and of channel 3
+//          are zero), A = the weights: 3S instructions per tile
+//   store  fma(acc, 1/255, bias), ReLU, bf16 (round to nearest even), staged
+//          through 2 KB of wave-private LDS so that a tile leaves as two
+//          contiguous 1 KB stores
+// Matrix rows are permuted so that each lane ends up with 16 consecutive
+// output channels of its pixel (row 8a + 4g + b holds channel 16g + 4a + b).
+
+#include <hip/hip_runtime.h>
+
+#include "pxr_internal.h"
+
+namespace pxr {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr uint32_t kConvThreads = 256;
+constexpr uint32_t kStageBytes = 2048;  // per wave: 32 pixels x 32 channels x bf16
+
+// float(n) for a byte n has at most 8 significant bits: its upper half IS bfloat16(n).
+__device__ __forceinline__ uint32_t bf16_pair(float lo, float hi) {
+    return (__float_as_uint(lo) >> 16) | (__float_as_uint(hi) & 0xFFFF0000u);
+}
+
+__device__ __forceinline__ uint32_t to_bf16_pair(float lo, float hi) {
+    const __bf16 a = (__bf16)lo, b = (__bf16)hi;  // round to nearest even
+    return (uint32_t)__builtin_bit_cast(unsigned short, a) | ((uint32_t)__builtin_bit_cast(unsigned short, b) << 16);
+}
+
+template <int S>
+__global__ __launch_bounds__(kConvThreads) void conv_kernel(const ConvConsts cc, const uint8_t* __restrict__ frames,
+                                                            uint32_t n_items, uint16_t* __restrict__ out) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t g = lane >> 5, n = lane & 31u;
+    const uint32_t frame_lds = cc.rows_in * cc.W * 8u;  // bytes of one frame's band in LDS
+    unsigned char* stage = lds + S * frame_lds + wave * kStageBytes;
+
+    // per-wave constants: the A operands and this lane's 16 biases
+    bf16x8 aw[3 * S];
+#pragma unroll
+    for (int j = 0; j < 3 * S; ++j) {
+        const uint4 v = reinterpret_cast<const uint4*>(cc.wtab)[j * 64 + lane];
+        aw[j] = __builtin_bit_cast(bf16x8, v);
+    }
+    float bias[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) bias[i] = cc.bias[16 * g + i];
+
+    const uint32_t quads_per_row = cc.W >> 2;
+    for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const uint32_t env = item / cc.bands, band = item - env * cc.bands;
+        const uint32_t oy0 = band * cc.band_rows;
+        const uint32_t rows_out = min(cc.band_rows, cc.Ho - oy0);
+        const uint32_t rows = 2u * rows_out + 1u;  // input rows 2*oy0 .. 2*oy0 + rows - 1 (<= H - 1)
+        const uint32_t n_quads = rows * quads_per_row;
+
+        // ---- load + convert: 4 pixels (12 bytes) per lane and trip
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            const uint32_t* src =
+                reinterpret_cast<const uint32_t*>(frames + (((size_t)env * S + s) * cc.H + 2u * oy0) * cc.W * 3u);
+            unsigned char* dst = lds + s * frame_lds;
+            for (uint32_t q = tid; q < n_quads; q += kConvThreads) {
+                const uint32_t d0 = src[q * 3 + 0], d1 = src[q * 3 + 1], d2 = src[q * 3 + 2];
+                const float r0 = (float)(d0 & 0xFFu), g0 = (float)((d0 >> 8) & 0xFFu), b0 = (float)((d0 >> 16) & 0xFFu);
+                const float r1 = (float)(d0 >> 24), g1 = (float)(d1 & 0xFFu), b1 = (float)((d1 >> 8) & 0xFFu);
+                const float r2 = (float)((d1 >> 16) & 0xFFu), g2 = (float)(d1 >> 24), b2 = (float)(d2 & 0xFFu);
+                const float r3 = (float)((d2 >> 8) & 0xFFu), g3 = (float)((d2 >> 16) & 0xFFu), b3 = (float)(d2 >> 24);
+                uint4* o = reinterpret_cast<uint4*>(dst + (size_t)q * 32u);
+                o[0] = make_uint4(bf16_pair(r0, g0), __float_as_uint(b0) >> 16, bf16_pair(r1, g1), __float_as_uint(b1) >> 16);
+                o[1] = make_uint4(bf16_pair(r2, g2), __float_as_uint(b2) >> 16, bf16_pair(r3, g3), __float_as_uint(b3) >> 16);
+            }
+        }
+        __syncthreads();
+
+        // ---- one wavefront per (output row, 32-pixel tile)
+        const uint32_t n_tasks = rows_out * cc.tiles_x;
+        for (uint32_t task = wave; task < n_tasks; task += kConvThreads / 64) {
+            const uint32_t r_out = task / cc.tiles_x, tx = task - r_out * cc.tiles_x;
+            const uint32_t ox = min(tx * 32u + n, cc.Wo - 1u);  // lanes past the row's end recompute its last pixel
+            const unsigned char* bsrc = lds + ((size_t)(2u * r_out) * cc.W + 2u * ox + 2u * g) * 8u;
+            f32x16 acc = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int s = 0; s < S; ++s)
+#pragma unroll
+                for (int ky = 0; ky < 3; ++ky) {
+                    const uint4 v = *reinterpret_cast<const uint4*>(bsrc + s * frame_lds + (size_t)ky * cc.W * 8u);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aw[s * 3 + ky], __builtin_bit_cast(bf16x8, v), acc, 0, 0, 0);
+                }
+            uint32_t packed[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                float a = __builtin_fmaf(acc[2 * i], 1.0f / 255.0f, bias[2 * i]);
+                float b = __builtin_fmaf(acc[2 * i + 1], 1.0f / 255.0f, bias[2 * i + 1]);
+                if (cc.relu) {
+                    a = a > 0.0f ? a : 0.0f;
+                    b = b > 0.0f ? b : 0.0f;
+                }
+                packed[i] = to_bf16_pair(a, b);
+            }
+            uint4* st = reinterpret_cast<uint4*>(stage + n * 64u + g * 32u);
+            st[0] = make_uint4(packed[0], packed[1], packed[2], packed[3]);
+            st[1] = make_uint4(packed[4], packed[5], packed[6], packed[7]);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const uint32_t n_bytes = min(32u, cc.Wo - tx * 32u) * 64u;
+            unsigned char* dst = reinterpret_cast<unsigned char*>(out) +
+                                 (((size_t)env * cc.Ho + oy0 + r_out) * cc.Wo + tx * 32u) * 64u;
+#pragma unroll
+            for (uint32_t h = 0; h < 2; ++h) {
+                const uint32_t off = h * 1024u + lane * 16u;
+                if (off < n_bytes) *reinterpret_cast<uint4*>(dst + off) = *reinterpret_cast<const uint4*>(stage + off);
+            }
+            __builtin_amdgcn_wave_barrier();  // the next tile's staging writes stay behind these reads
+        }
+        __syncthreads();  // the next item's load overwrites the band
+    }
+}
+
+}  // namespace
+
+uint32_t conv_lds_bytes(const ConvConsts& cc) {
+    return cc.S * cc.rows_in * cc.W * 8u + (kConvThreads / 64u) * kStageBytes;
+}
+
+int prepare_conv_kernels(std::string& err) {
+    const void* fns[4] = {reinterpret_cast<const void*>(&conv_kernel<1>), reinterpret_cast<const void*>(&conv_kernel<2>),
+                          reinterpret_cast<const void*>(&conv_kernel<3>), reinterpret_cast<const void*>(&conv_kernel<4>)};
+    for (const void* f : fns) {
+        const hipError_t rc = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (rc != hipSuccess) {
+            err = std::string("hipFuncSetAttribute(MaxDynamicSharedMemorySize) failed: ") + hipGetErrorString(rc);
+            return PXR_ERR_DEVICE;
+        }
+    }
+    return PXR_OK;
+}
+
+int launch_conv(const ConvConsts& cc, const uint8_t* d_frames, uint32_t B, uint16_t* d_out, uint32_t n_groups, void* stream,
+                std::string& err) {
+    const uint32_t n_items = B * cc.bands;
+    const uint32_t grid = min(n_items, n_groups);
+    const uint32_t ldsb = conv_lds_bytes(cc);
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    switch (cc.S) {
+        case 1: hipLaunchKernelGGL(conv_kernel<1>, dim3(grid), dim3(kConvThreads), ldsb, st, cc, d_frames, n_items, d_out); break;
+        case 2: hipLaunchKernelGGL(conv_kernel<2>, dim3(grid), dim3(kConvThreads), ldsb, st, cc, d_frames, n_items, d_out); break;
+        case 3: hipLaunchKernelGGL(conv_kernel<3>, dim3(grid), dim3(kConvThreads), ldsb, st, cc, d_frames, n_items, d_out); break;
+        case 4: hipLaunchKernelGGL(conv_kernel<4>, dim3(grid), dim3(kConvThreads), ldsb, st, cc, d_frames, n_items, d_out); break;
+        default: err = "frame stack depth must lie in [1,4]"; return PXR_ERR_UNSUPPORTED;
+    }
+    const hipError_t rc = hipGetLastError();
+    if (rc != hipSuccess) {
+        err = std::string("kernel launch failed: ") + hipGetErrorString(rc);
+        return PXR_ERR_DEVICE;
+    }
+    return PXR_OK;
+}
+
+}  // namespace pxr

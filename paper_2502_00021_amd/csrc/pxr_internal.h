@@ -113,6 +113,29 @@ int launch_render(const SceneConsts& sc, const DistractConsts& dc, const float* 
 // render.hip: raise the dynamic-LDS limit of every kernel instantiation once.
 int prepare_kernels(uint32_t lds_bytes, std::string& err);
 
+// Frame consumer (first convolutional layer of the policy), bound by pxr_conv_create.
+// 3x3 kernel, stride 2, 32 output channels; the frame stack is the channel axis.
+struct ConvConsts {
+    uint32_t H, W, S;        // input frames [S,H,W,3] per environment
+    uint32_t Ho, Wo;         // output size
+    uint32_t tiles_x;        // 32-pixel tiles per output row
+    uint32_t band_rows;      // output rows per work item
+    uint32_t bands;          // work items per environment
+    uint32_t rows_in;        // input rows held in LDS per frame = 2 * band_rows + 1
+    uint32_t relu;
+    const uint32_t* wtab;    // [3S][64 lanes][4] the A operands of the matrix instruction, bf16 pairs
+    const float* bias;       // [32]
+};
+
+// api.cpp: record the calling thread's last error and return `code`.
+int set_error(int code, const std::string& msg);
+
+// conv.hip
+uint32_t conv_lds_bytes(const ConvConsts& cc);
+int prepare_conv_kernels(std::string& err);
+int launch_conv(const ConvConsts& cc, const uint8_t* d_frames, uint32_t B, uint16_t* d_out, uint32_t n_groups,
+                void* stream, std::string& err);
+
 // kinematics.hip: joint angles -> poses, one lane per frame.
 uint32_t fk_lds_bytes(const SkeletonConsts& sk);
 int prepare_fk_kernel(std::string& err);

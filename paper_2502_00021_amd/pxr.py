@@ -54,6 +54,12 @@ class SkeletonDesc(C.Structure):
                 ("offset", C.c_void_p)]
 
 
+class ConvDesc(C.Structure):
+    _fields_ = [("in_h", C.c_uint32), ("in_w", C.c_uint32), ("n_stack", C.c_uint32),
+                ("c_out", C.c_uint32), ("kernel", C.c_uint32), ("stride", C.c_uint32),
+                ("weights", C.c_void_p), ("bias", C.c_void_p), ("relu", C.c_uint32)]
+
+
 _lib = None
 
 
@@ -75,6 +81,13 @@ def lib():
         L.pxr_set_skeleton.argtypes = [vp, C.POINTER(SkeletonDesc)]
         L.pxr_pose_batch.argtypes = [vp, vp, vp, u32, vp, vp]
         L.pxr_render_batch_kinematic.argtypes = [vp, vp, vp, vp, u32, u32, u32, u32, vp, vp, vp, vp]
+        L.pxr_conv_create.argtypes = [C.POINTER(ConvDesc), C.POINTER(vp)]
+        L.pxr_conv_destroy.argtypes = [vp]
+        L.pxr_conv_forward.argtypes = [vp, vp, u32, vp, vp]
+        L.pxr_conv_info.argtypes = [vp, vp, vp, vp, vp, vp]
+        L.pxr_conv_set_tuning.argtypes = [vp, u32, u32]
+        for name in ("pxr_conv_create", "pxr_conv_destroy", "pxr_conv_forward", "pxr_conv_info", "pxr_conv_set_tuning"):
+            getattr(L, name).restype = C.c_int
         L.pxr_last_error.restype = C.c_char_p
         for name in ("pxr_create_scene", "pxr_destroy_scene", "pxr_apply_distractor", "pxr_render_batch",
                      "pxr_scene_info", "pxr_set_block_threads", "pxr_host_tables", "pxr_set_skeleton",
@@ -295,6 +308,60 @@ class Scene:
                                                 int(step0), int(env0), poses.data_ptr(), frames.data_ptr(),
                                                 None if ids is None else ids.data_ptr(), C.c_void_p(stream)))
         return frames, ids, poses
+
+
+class Conv:
+    """Owns one pxr_conv handle: the policy's first convolutional layer (3x3, stride 2, 32 channels) on the frame stack."""
+
+    def __init__(self, in_h, in_w, n_stack, weights, bias, relu=True, c_out=32, kernel=3, stride=2):
+        w = np.ascontiguousarray(weights, dtype=np.float32)
+        b = np.ascontiguousarray(bias, dtype=np.float32)
+        assert w.shape == (kernel, kernel, 3 * n_stack, c_out) and b.shape == (c_out,), (w.shape, b.shape)
+        d = ConvDesc()
+        d.in_h, d.in_w, d.n_stack = int(in_h), int(in_w), int(n_stack)
+        d.c_out, d.kernel, d.stride = int(c_out), int(kernel), int(stride)
+        d.weights, d.bias, d.relu = w.ctypes.data, b.ctypes.data, 1 if relu else 0
+        h = C.c_void_p()
+        _check(lib().pxr_conv_create(C.byref(d), C.byref(h)))
+        self._h = h
+        self.H, self.W, self.S, self.C = int(in_h), int(in_w), int(n_stack), int(c_out)
+        i = self.info()
+        self.Ho, self.Wo = i["out_h"], i["out_w"]
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _check(lib().pxr_conv_destroy(self._h))
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def info(self):
+        v = [C.c_uint32() for _ in range(5)]
+        _check(lib().pxr_conv_info(self._h, *[C.byref(x) for x in v]))
+        return dict(zip(("out_h", "out_w", "band_rows", "lds_bytes", "n_groups"), (x.value for x in v)))
+
+    def set_tuning(self, band_rows=0, n_groups=0):
+        _check(lib().pxr_conv_set_tuning(self._h, int(band_rows), int(n_groups)))
+
+    def forward(self, frames, out=None, stream=None):
+        """frames: CUDA uint8 [B,S,H,W,3] -> CUDA bfloat16 [B,Ho,Wo,32]; enqueue only."""
+        import torch
+        assert frames.is_cuda and frames.dtype == torch.uint8 and frames.is_contiguous()
+        B = int(frames.shape[0])
+        assert tuple(frames.shape) == (B, self.S, self.H, self.W, 3), tuple(frames.shape)
+        if out is None:
+            out = torch.empty((B, self.Ho, self.Wo, self.C), dtype=torch.bfloat16, device=frames.device)
+        else:
+            assert out.is_cuda and out.is_contiguous() and out.dtype == torch.bfloat16
+            assert tuple(out.shape) == (B, self.Ho, self.Wo, self.C)
+        if stream is None:
+            stream = torch.cuda.current_stream(frames.device).cuda_stream
+        _check(lib().pxr_conv_forward(self._h, frames.data_ptr(), B, out.data_ptr(), C.c_void_p(stream)))
+        return out
 
 
 def make_skeleton_desc(skel, n_free, n_angles):
