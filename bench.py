@@ -60,7 +60,7 @@ def algorithmic_bytes_per_frame(K, npix, mode, has_shapes, S):
     return b
 
 
-def cpu_baseline(w, budget_frames_1core=1536, budget_frames_per_thread=768):
+def cpu_baseline(w, budget_frames_1core=6144, budget_frames_per_thread=6144):
     """The oracle as it stands on the host cores: 1 core, then one single-threaded instance per core."""
     from oracle import orc
     scene = orc.Scene(w["desc"])
@@ -93,6 +93,75 @@ def cpu_baseline(w, budget_frames_1core=1536, budget_frames_per_thread=768):
             "value_1core": one_core}
 
 
+def time_next_stages(torch, pxr, w, reps=10):
+    """The stages in front of and behind the renderer on the headline workload: joint angles -> poses
+    (pxr_pose_batch) and frame stack -> first conv layer of the policy (pxr_conv_forward, matrix cores), each
+    timed on its own with HIP events, and the three enqueued back to back (angles in, features out)."""
+    fk = w["fk"]
+    scene = pxr.Scene(w["desc"])
+    scene.set_skeleton(fk["skel"], fk["free_poses"].shape[-2], fk["angles"].shape[-1])
+    dis = w["distractor"]
+    if dis is not None:
+        d = dict(dis)
+        if d["mode"] == "video":
+            d["video"] = torch.from_numpy(d["video"]).cuda()
+        scene.apply_distractor(d)
+    free = torch.from_numpy(fk["free_poses"]).cuda()
+    ang = torch.from_numpy(fk["angles"]).cuda()
+    shapes = None if w["shapes"] is None else torch.from_numpy(w["shapes"]).cuda()
+    B, S = free.shape[0], free.shape[1]
+    K = scene.K
+    poses = torch.empty((B, S, K, 7), dtype=torch.float32, device="cuda")
+    frames = torch.empty((B, S, scene.H, scene.W, 3), dtype=torch.uint8, device="cuda")
+    rng = np.random.default_rng(0)
+    conv = pxr.Conv(scene.H, scene.W, S, (rng.standard_normal((3, 3, 3 * S, 32)) * 0.1).astype(np.float32),
+                    np.zeros(32, np.float32))
+    feat = torch.empty((B, conv.Ho, conv.Wo, 32), dtype=torch.bfloat16, device="cuda")
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    ms_fk = timed(lambda: scene.pose_batch(free, ang, poses=poses))
+    scene.render_batch(poses, shapes, frames=frames)
+    ms_conv = timed(lambda: conv.forward(frames, out=feat))
+
+    def whole():
+        scene.render_batch_kinematic(free, ang, shapes, poses=poses, frames=frames)
+        conv.forward(frames, out=feat)
+
+    ms_all = timed(whole)
+    n = B * S
+    fk_bytes = 4 * (free[0, 0].numel() + ang[0, 0].numel() + K * 7) * n
+    conv_bytes = frames.numel() + feat.numel() * 2
+    conv_flops = 2.0 * B * conv.Ho * conv.Wo * 32 * 27 * S
+    out = {
+        "kinematics-" + w["name"]: {"kernel": "fk_kernel", "avg_launch_ms": ms_fk, "frames_per_s": n / (1e-3 * ms_fk),
+                                   "roofline": {"bound": "hbm", "achieved": fk_bytes / ms_fk / 1e6, "peak": HBM_PEAK_GBS,
+                                                "unit": "GB/s", "frac": fk_bytes / ms_fk / 1e6 / HBM_PEAK_GBS}},
+        "conv-consumer-" + w["name"]: {"kernel": "conv_kernel", "avg_launch_ms": ms_conv,
+                                      "stacks_per_s": B / (1e-3 * ms_conv), "frames_per_s": n / (1e-3 * ms_conv),
+                                      "tflops_bf16": conv_flops / ms_conv / 1e9,
+                                      "roofline": {"bound": "hbm", "achieved": conv_bytes / ms_conv / 1e6,
+                                                   "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                                   "frac": conv_bytes / ms_conv / 1e6 / HBM_PEAK_GBS,
+                                                   "algorithmic_bytes_per_stack": conv_bytes / B}},
+        "angles-to-features-" + w["name"]: {"ms_per_step": ms_all, "frames_per_s": n / (1e-3 * ms_all),
+                                           "kernels": "fk_kernel + render_kernel + conv_kernel on one stream"},
+    }
+    conv.close()
+    scene.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -106,6 +175,8 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy kernel (the known-size reference that "
                          "scales the FETCH_SIZE / WRITE_SIZE counters of a profiler run)")
+    ap.add_argument("--next-stages-only", action="store_true",
+                    help="time only the kinematics and conv-consumer stages of the chosen workload (for profiler runs)")
     ap.add_argument("--extras", action="store_true", help="also time the other configurations (reported under 'others')")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -165,6 +236,9 @@ def main():
         return res
 
     cfg = int(args.workload[3:])
+    if args.next_stages_only:
+        print(json.dumps(time_next_stages(torch, pxr, workloads.make(cfg, B=args.envs), reps=args.steps)))
+        return
     r = time_workload(cfg, args.envs, args.steps, args.warmup, not args.no_distractor, args.threads)
     n_frames = r["B"] * r["S"]
     ms_per_step = 1e3 * r["wall"] / args.steps
@@ -195,6 +269,7 @@ def main():
     }
     if args.extras:
         others = {}
+        others.update(time_next_stages(torch, pxr, r["w"]))
         for name, c, envs, dis in [("cfg2-chain-64", 2, 256, True), ("cfg3-quadruped-64-colour", 3, 4096, True),
                                    ("cfg3-quadruped-64-no-distractor", 3, 4096, False),
                                    ("cfg4-humanoid-84-video", 4, 16384, True),

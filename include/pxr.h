@@ -189,7 +189,7 @@ typedef struct {
 } pxr_conv_desc;
 
 /* Host only.  Errors: INVALID_ARG (null, non-finite weight or bias); UNSUPPORTED (other layer shapes,
- * n_stack outside [1,4], in_h outside [3,512], in_w outside [4,512] or not a multiple of 4); OOM; DEVICE. */
+ * n_stack outside [1,4], in_h outside [3,512], in_w outside [4,256] or not a multiple of 4); OOM; DEVICE. */
 int pxr_conv_create(const pxr_conv_desc* desc, pxr_conv** out);
 int pxr_conv_destroy(pxr_conv* c); /* NULL accepted; synchronise streams still using it first */
 

@@ -16,7 +16,8 @@
 // (the 36 registers of weights per lane are loaded once per wave) and walk the
 // items with a grid stride:
 //   load   the band's input rows of all S frames: 12-byte loads (4 RGB pixels),
-//          uint8 -> bf16 (exact), written to LDS as [frame][row][pixel][R,G,B,0]
+//          issued one work item ahead into registers, then uint8 -> bf16
+//          (exact) and written to LDS as [frame][row][pixel][R,G,B,0]
 //   mma    one wavefront per (output row, 32-pixel tile): for each (frame, ky)
 //          ONE aligned 16-byte LDS read per lane is the B operand
 //          (2 pixels x 4 channels; lanes 0-31 take pixels 2ox, 2ox+1, lanes
@@ -40,6 +41,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr uint32_t kConvThreads = 256;
 constexpr uint32_t kStageBytes = 2048;  // per wave: 32 pixels x 32 channels x bf16
+constexpr uint32_t kConvTrips = 4;      // 12-byte input quads a thread carries per work item
 
 // float(n) for a byte n has at most 8 significant bits: its upper half IS bfloat16(n).
 __device__ __forceinline__ uint32_t bf16_pair(float lo, float hi) {
@@ -71,32 +73,67 @@ __global__ __launch_bounds__(kConvThreads) void conv_kernel(const ConvConsts cc,
 #pragma unroll
     for (int i = 0; i < 16; ++i) bias[i] = cc.bias[16 * g + i];
 
+    // A work item's input: rows 2*oy0 .. 2*oy0 + rows - 1 of each of the S frames, as "quads" of 4 pixels
+    // (12 bytes).  Quad f of the item (f = tid + 256 p) belongs to frame s = f / n_quads.  An item's quads
+    // are fetched into registers one item ahead, so that HBM latency hides behind the previous item's
+    // matrix work; the host guarantees S * n_quads <= 256 * kConvTrips.
+    struct alignas(4) Quad {
+        uint32_t a, b, c;
+    };
+    Quad pre[kConvTrips];
     const uint32_t quads_per_row = cc.W >> 2;
-    for (uint32_t item = blockIdx.x; item < n_items; item += gridDim.x) {
+    auto fetch = [&](uint32_t item) {
+        const uint32_t env = item / cc.bands, oy0 = (item - env * cc.bands) * cc.band_rows;
+        const uint32_t n_quads = (2u * min(cc.band_rows, cc.Ho - oy0) + 1u) * quads_per_row;
+        const unsigned char* base = frames + (((size_t)env * S) * cc.H + 2u * oy0) * cc.W * 3u;
+#pragma unroll
+        for (uint32_t p = 0; p < kConvTrips; ++p) {
+            const uint32_t f = tid + p * kConvThreads;
+            uint32_t s = 0, q = f;
+#pragma unroll
+            for (int t = 1; t < S; ++t)
+                if (f >= t * n_quads) {
+                    s = t;
+                    q = f - t * n_quads;
+                }
+            if (f < S * n_quads)
+                pre[p] = *reinterpret_cast<const Quad*>(base + (size_t)s * cc.H * cc.W * 3u + (size_t)q * 12u);
+        }
+    };
+
+    uint32_t item = blockIdx.x;
+    if (item < n_items) fetch(item);
+    while (item < n_items) {
         const uint32_t env = item / cc.bands, band = item - env * cc.bands;
         const uint32_t oy0 = band * cc.band_rows;
         const uint32_t rows_out = min(cc.band_rows, cc.Ho - oy0);
-        const uint32_t rows = 2u * rows_out + 1u;  // input rows 2*oy0 .. 2*oy0 + rows - 1 (<= H - 1)
-        const uint32_t n_quads = rows * quads_per_row;
+        const uint32_t n_quads = (2u * rows_out + 1u) * quads_per_row;
 
-        // ---- load + convert: 4 pixels (12 bytes) per lane and trip
+        // ---- convert the fetched quads to bf16 and lay them out in LDS
 #pragma unroll
-        for (int s = 0; s < S; ++s) {
-            const uint32_t* src =
-                reinterpret_cast<const uint32_t*>(frames + (((size_t)env * S + s) * cc.H + 2u * oy0) * cc.W * 3u);
-            unsigned char* dst = lds + s * frame_lds;
-            for (uint32_t q = tid; q < n_quads; q += kConvThreads) {
-                const uint32_t d0 = src[q * 3 + 0], d1 = src[q * 3 + 1], d2 = src[q * 3 + 2];
+        for (uint32_t p = 0; p < kConvTrips; ++p) {
+            const uint32_t f = tid + p * kConvThreads;
+            uint32_t s = 0, q = f;
+#pragma unroll
+            for (int t = 1; t < S; ++t)
+                if (f >= t * n_quads) {
+                    s = t;
+                    q = f - t * n_quads;
+                }
+            if (f < S * n_quads) {
+                const uint32_t d0 = pre[p].a, d1 = pre[p].b, d2 = pre[p].c;
                 const float r0 = (float)(d0 & 0xFFu), g0 = (float)((d0 >> 8) & 0xFFu), b0 = (float)((d0 >> 16) & 0xFFu);
                 const float r1 = (float)(d0 >> 24), g1 = (float)(d1 & 0xFFu), b1 = (float)((d1 >> 8) & 0xFFu);
                 const float r2 = (float)((d1 >> 16) & 0xFFu), g2 = (float)(d1 >> 24), b2 = (float)(d2 & 0xFFu);
                 const float r3 = (float)((d2 >> 8) & 0xFFu), g3 = (float)((d2 >> 16) & 0xFFu), b3 = (float)(d2 >> 24);
-                uint4* o = reinterpret_cast<uint4*>(dst + (size_t)q * 32u);
+                uint4* o = reinterpret_cast<uint4*>(lds + s * frame_lds + (size_t)q * 32u);
                 o[0] = make_uint4(bf16_pair(r0, g0), __float_as_uint(b0) >> 16, bf16_pair(r1, g1), __float_as_uint(b1) >> 16);
                 o[1] = make_uint4(bf16_pair(r2, g2), __float_as_uint(b2) >> 16, bf16_pair(r3, g3), __float_as_uint(b3) >> 16);
             }
         }
         __syncthreads();
+        const uint32_t next = item + gridDim.x;
+        if (next < n_items) fetch(next);
 
         // ---- one wavefront per (output row, 32-pixel tile)
         const uint32_t n_tasks = rows_out * cc.tiles_x;
@@ -139,11 +176,14 @@ __global__ __launch_bounds__(kConvThreads) void conv_kernel(const ConvConsts cc,
             }
             __builtin_amdgcn_wave_barrier();  // the next tile's staging writes stay behind these reads
         }
-        __syncthreads();  // the next item's load overwrites the band
+        __syncthreads();  // the next item's conversion overwrites the band
+        item = next;
     }
 }
 
 }  // namespace
+
+uint32_t conv_max_quads() { return kConvThreads * kConvTrips; }
 
 uint32_t conv_lds_bytes(const ConvConsts& cc) {
     return cc.S * cc.rows_in * cc.W * 8u + (kConvThreads / 64u) * kStageBytes;

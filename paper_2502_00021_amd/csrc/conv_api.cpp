@@ -45,8 +45,8 @@ int pxr_conv_create(const pxr_conv_desc* d, pxr_conv** out) {
     if (d->kernel != 3 || d->stride != 2 || d->c_out != 32)
         return set_error(PXR_ERR_UNSUPPORTED, "pxr_conv_create: only kernel 3, stride 2, 32 output channels are built");
     if (d->n_stack < 1 || d->n_stack > 4) return set_error(PXR_ERR_UNSUPPORTED, "pxr_conv_create: n_stack must lie in [1,4]");
-    if (d->in_h < 3 || d->in_h > 512 || d->in_w < 4 || d->in_w > 512 || (d->in_w & 3u))
-        return set_error(PXR_ERR_UNSUPPORTED, "pxr_conv_create: height in [3,512], width in [4,512] and a multiple of 4");
+    if (d->in_h < 3 || d->in_h > 512 || d->in_w < 4 || d->in_w > 256 || (d->in_w & 3u))
+        return set_error(PXR_ERR_UNSUPPORTED, "pxr_conv_create: height in [3,512], width in [4,256] and a multiple of 4");
     const uint32_t S = d->n_stack, cin = 3 * S;
     for (uint32_t i = 0; i < 9 * cin * 32; ++i)
         if (!std::isfinite(d->weights[i])) return set_error(PXR_ERR_INVALID_ARG, "pxr_conv_create: non-finite weight");
@@ -65,11 +65,14 @@ int pxr_conv_create(const pxr_conv_desc* d, pxr_conv** out) {
     cc.relu = d->relu ? 1u : 0u;
     // band height: about 40 KB of LDS per workgroup so that four of them share a compute unit
     uint32_t band = 1;
-    while (band < cc.Ho && S * (2 * (band + 1) + 1) * cc.W * 8u + 8192u <= 40u * 1024u) ++band;
+    // (and the band's input must fit the registers that prefetch it)
+    while (band < cc.Ho && S * (2 * (band + 1) + 1) * cc.W * 8u + 8192u <= 40u * 1024u &&
+           S * (2 * (band + 1) + 1) * (cc.W / 4u) <= pxr::conv_max_quads())
+        ++band;
     plan(c, band);
-    if (pxr::conv_lds_bytes(cc) > 160u * 1024u) {
+    if (pxr::conv_lds_bytes(cc) > 160u * 1024u || S * cc.rows_in * (cc.W / 4u) > pxr::conv_max_quads()) {
         delete c;
-        return set_error(PXR_ERR_UNSUPPORTED, "pxr_conv_create: one output row of this input does not fit 160 KB of LDS");
+        return set_error(PXR_ERR_UNSUPPORTED, "pxr_conv_create: one output row of this input does not fit a workgroup");
     }
 
     // A operands: for instruction j = s*3 + ky, lane (g = lane/32, m = lane%32) holds matrix row m,
@@ -141,9 +144,9 @@ int pxr_conv_set_tuning(pxr_conv* c, uint32_t band_rows, uint32_t n_groups) {
     if (!c) return pxr::set_error(PXR_ERR_INVALID_ARG, "pxr_conv_set_tuning: null handle");
     const pxr::ConvConsts saved = c->cc;
     plan(c, band_rows ? std::min(band_rows, c->cc.Ho) : c->default_band);
-    if (pxr::conv_lds_bytes(c->cc) > 160u * 1024u) {
+    if (pxr::conv_lds_bytes(c->cc) > 160u * 1024u || c->cc.S * c->cc.rows_in * (c->cc.W / 4u) > pxr::conv_max_quads()) {
         c->cc = saved;
-        return pxr::set_error(PXR_ERR_UNSUPPORTED, "pxr_conv_set_tuning: band does not fit 160 KB of LDS");
+        return pxr::set_error(PXR_ERR_UNSUPPORTED, "pxr_conv_set_tuning: band does not fit a workgroup");
     }
     c->n_groups = n_groups ? n_groups : c->default_groups;
     return PXR_OK;

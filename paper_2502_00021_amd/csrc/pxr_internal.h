@@ -132,6 +132,7 @@ int set_error(int code, const std::string& msg);
 
 // conv.hip
 uint32_t conv_lds_bytes(const ConvConsts& cc);
+uint32_t conv_max_quads();  // 12-byte input quads (4 pixels) one work item may hold: S * rows_in * W / 4
 int prepare_conv_kernels(std::string& err);
 int launch_conv(const ConvConsts& cc, const uint8_t* d_frames, uint32_t B, uint16_t* d_out, uint32_t n_groups,
                 void* stream, std::string& err);

@@ -106,7 +106,7 @@ def test_tuning_does_not_change_output(torch, pxr):
     frames = rng.integers(0, 256, (9, 3, 64, 64, 3), dtype=np.uint8)
     w, b = _layer(rng, 3)
     base = _run(torch, pxr, frames, w, b)
-    for tuning in [(1, 0), (3, 7), (31, 1), (16, 100000), (5, 2)]:
+    for tuning in [(1, 0), (3, 7), (10, 1), (8, 100000), (5, 2)]:
         assert np.array_equal(_run(torch, pxr, frames, w, b, tuning=tuning), base), tuning
 
 
