@@ -268,6 +268,10 @@ def main():
         "checksum": r["checksum"],
     }
     if args.extras:
+        # the same fractions against what this GPU sustains right now (microbenchmarks in the library)
+        pk = pxr.measure_peaks()
+        out["measured_peaks"] = dict(pk, alu_frac_of_measured_fma=achieved_tops / pk["fma_tlaneops"],
+                                     hbm_frac_of_measured_copy=out["roofline"]["hbm"]["achieved"] / pk["copy_gbs"])
         others = {}
         others.update(time_next_stages(torch, pxr, r["w"]))
         for name, c, envs, dis in [("cfg2-chain-64", 2, 256, True), ("cfg3-quadruped-64-colour", 3, 4096, True),

@@ -321,6 +321,13 @@ int pxr_host_tables(const pxr_scene_desc* desc, uint32_t* n_verts, uint32_t* n_t
     return PXR_OK;
 }
 
+int pxr_measure_peaks(double* fma_tlaneops, double* imad_tlaneops, double* copy_gbs) {
+    std::string err;
+    const int rc = pxr::measure_peaks(fma_tlaneops, imad_tlaneops, copy_gbs, err);
+    if (rc != PXR_OK) return fail(rc, "pxr_measure_peaks: " + err);
+    return PXR_OK;
+}
+
 int pxr_set_block_threads(pxr_scene* s, uint32_t threads) {
     if (!s) return fail(PXR_ERR_INVALID_ARG, "pxr_set_block_threads: null scene");
     if (threads == 0) threads = s->default_threads;

@@ -137,6 +137,10 @@ int prepare_conv_kernels(std::string& err);
 int launch_conv(const ConvConsts& cc, const uint8_t* d_frames, uint32_t B, uint16_t* d_out, uint32_t n_groups,
                 void* stream, std::string& err);
 
+// peaks.hip: sustained fp32-FMA and 24-bit integer multiply-add rates (T lane-operations/s) and the
+// read+write bandwidth of a plain 1 GiB copy (GB/s) on the current device.
+int measure_peaks(double* fma_tlaneops, double* imad_tlaneops, double* copy_gbs, std::string& err);
+
 // kinematics.hip: joint angles -> poses, one lane per frame.
 uint32_t fk_lds_bytes(const SkeletonConsts& sk);
 int prepare_fk_kernel(std::string& err);
