@@ -75,8 +75,10 @@ typedef struct {
  *          step t shows frame (env_offset[e] + t) mod n_frames, alpha-blended
  *          onto pixels whose winner is the ground or the background.
  *          d_env_offset: device uint32 [B] (indexed by the env's position in
- *          the batch), or NULL = drawn from the generator.  Both buffers are
- *          caller-owned and must stay alive while bound. */
+ *          the batch), or NULL = drawn from the generator.  With n_videos > 1
+ *          every environment plays one clip of a set (the paper: "a random
+ *          video" per environment), chosen by d_env_video or drawn from the
+ *          generator.  All buffers are caller-owned and must stay alive while bound. */
 typedef struct {
     uint32_t mode;
     uint64_t seed;
@@ -85,6 +87,9 @@ typedef struct {
     uint32_t n_frames;
     float alpha;
     const uint32_t* d_env_offset;
+    uint32_t n_videos;            /* VIDEO: 0 or 1 = one clip; > 1: d_video is [n_videos,n_frames,H,W,3] */
+    const uint32_t* d_env_video;  /* VIDEO, n_videos > 1: device uint32 [B], the clip of each environment
+                                     (values >= n_videos are reduced modulo n_videos), or NULL = drawn */
 } pxr_distractor_desc;
 
 /* Build a scene on the current HIP device: validate, tessellate, derive the
@@ -92,7 +97,7 @@ typedef struct {
  * not on the hot path.
  * Errors: INVALID_ARG (null pointer, root_body out of range, unknown body
  * type, non-finite or non-positive parameter, degenerate camera);
- * UNSUPPORTED (width or height outside [8,128], n_bodies outside [1,64], more
+ * UNSUPPORTED (width or height outside [8,512], n_bodies outside [1,64], more
  * than 65535 vertices or triangles, tessellation counts outside [3,64]x[1,32]
  * (box [1,16]), or a frame that does not fit the 160 KB of LDS of one
  * compute unit); OOM; DEVICE. */

@@ -572,7 +572,17 @@ int orc_render(const orc_scene* s, const float* poses, const float* shapes, uint
                     eo = r[0] % dis->n_frames;
                 }
                 uint32_t fi = (uint32_t)(((uint64_t)eo + (uint64_t)step) % dis->n_frames);
-                vframe = dis->video + (size_t)fi * npix * 3;
+                // which clip: the paper plays "a random video" of its set in each environment (section 2)
+                uint32_t clip = 0;
+                if (dis->n_videos > 1) {
+                    if (dis->env_video) clip = dis->env_video[e] % dis->n_videos;
+                    else {
+                        uint32_t r[4];
+                        philox(dis->seed, env, 0xFFFFFFFFu, 3u, 0u, r);
+                        clip = r[0] % dis->n_videos;
+                    }
+                }
+                vframe = dis->video + ((size_t)clip * dis->n_frames + fi) * npix * 3;
             }
             // G + S + X per pixel
             const float inv_ez = 1.0f / fx.eye[2];

@@ -104,6 +104,8 @@ typedef struct {
     uint32_t n_frames;
     float alpha;
     const uint32_t* env_offset;                     /* [B] or NULL -> drawn from the generator */
+    uint32_t n_videos;                              /* 0 or 1: one clip; > 1: video is [n_videos,n_frames,H,W,3] */
+    const uint32_t* env_video;                      /* [B] clip of each environment, or NULL -> drawn (stream 3) */
 } orc_distractor;
 
 /* Full path: poses[B,S,K,7], shapes[B,K,4] or NULL, frames[B,S,H,W,3] out,

@@ -36,7 +36,7 @@ class _Distractor(C.Structure):
                 ("scale_lo", C.c_float), ("scale_hi", C.c_float),
                 ("offset_lo", C.c_float), ("offset_hi", C.c_float),
                 ("video", C.c_void_p), ("n_frames", C.c_uint32), ("alpha", C.c_float),
-                ("env_offset", C.c_void_p)]
+                ("env_offset", C.c_void_p), ("n_videos", C.c_uint32), ("env_video", C.c_void_p)]
 
 
 _lib = None
@@ -184,7 +184,16 @@ def _make_distractor(d, B):
         v = np.ascontiguousarray(d["video"], dtype=np.uint8)
         keep.append(v)
         s.video = v.ctypes.data
-        s.n_frames = v.shape[0]
+        if v.ndim == 5:  # several clips [n_videos, n_frames, H, W, 3]
+            s.n_videos, s.n_frames = v.shape[0], v.shape[1]
+            ev = d.get("env_video")
+            if ev is not None:
+                ev = np.ascontiguousarray(ev, dtype=np.uint32)
+                assert ev.shape == (B,)
+                keep.append(ev)
+                s.env_video = ev.ctypes.data
+        else:
+            s.n_frames = v.shape[0]
         s.alpha = float(d.get("alpha", 0.5))
         eo = d.get("env_offset")
         if eo is not None:

@@ -152,13 +152,18 @@ int pxr_apply_distractor(pxr_scene* s, const pxr_distractor_desc* d) {
                 return fail(PXR_ERR_INVALID_ARG, "pxr_apply_distractor: video mode needs d_video and n_frames > 0");
             if (!(d->alpha >= 0.0f && d->alpha <= 1.0f))
                 return fail(PXR_ERR_INVALID_ARG, "pxr_apply_distractor: alpha must lie in [0,1]");
-            if ((reinterpret_cast<uintptr_t>(d->d_video) & 3u) || (reinterpret_cast<uintptr_t>(d->d_env_offset) & 3u))
-                return fail(PXR_ERR_INVALID_ARG, "pxr_apply_distractor: d_video and d_env_offset must be 4-byte aligned");
+            if ((reinterpret_cast<uintptr_t>(d->d_video) & 3u) || (reinterpret_cast<uintptr_t>(d->d_env_offset) & 3u) ||
+                (reinterpret_cast<uintptr_t>(d->d_env_video) & 3u))
+                return fail(PXR_ERR_INVALID_ARG, "pxr_apply_distractor: d_video, d_env_offset and d_env_video must be 4-byte aligned");
+            if ((uint64_t)(d->n_videos ? d->n_videos : 1u) * d->n_frames > 0xFFFFFFFFull)
+                return fail(PXR_ERR_INVALID_ARG, "pxr_apply_distractor: n_videos * n_frames overflows 32 bits");
             dc.mode = PXR_DISTRACT_VIDEO;
             dc.video = d->d_video;
             dc.n_frames = d->n_frames;
             dc.alpha = d->alpha;
             dc.env_offset = d->d_env_offset;
+            dc.n_videos = d->n_videos ? d->n_videos : 1u;
+            dc.env_video = dc.n_videos > 1 ? d->d_env_video : nullptr;
         } else {
             return fail(PXR_ERR_INVALID_ARG, "pxr_apply_distractor: unknown mode");
         }

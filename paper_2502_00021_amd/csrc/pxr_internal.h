@@ -57,7 +57,7 @@ struct SceneConsts {
     // sizes
     uint32_t W, H, npix, K, root, V, T, P;  // P = entries of the pair table
     uint32_t band_rows;                     // rows of the frame held by the LDS key buffer at a time
-    uint32_t magicW;  // ceil(2^32 / W): p / W == mulhi(p, magicW) for p < 2^14 * 2^7
+    uint32_t magicW;  // ceil(2^32 / W): p / W == mulhi(p, magicW) for every pixel index p < 512 * W
     // device tables
     const float* vtmpl;       // [V][4]  ux,uy,uz, bits = body<<2 | (s+1)
     const uint32_t* tri_idx;  // [T][2]  v0 | v1<<16 ,  v2 | body<<16
@@ -80,6 +80,8 @@ struct DistractConsts {
     uint32_t n_frames;
     float alpha;
     const uint32_t* env_offset;
+    uint32_t n_videos;          // >= 1
+    const uint32_t* env_video;  // [B] or null
 };
 
 // Skeleton bound by pxr_set_skeleton (device tables live in their own allocation).

@@ -464,7 +464,17 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
                 counter_rng(dc.seed_lo, dc.seed_hi, env, 0xFFFFFFFFu, 2u, 0u, r);
                 first = r[0] % dc.n_frames;
             }
-            fu->video_frame = (uint32_t)(((u64)first + (u64)step) % dc.n_frames);
+            uint32_t clip = 0;  // each environment plays one clip of the set
+            if (dc.n_videos > 1) {
+                if (dc.env_video) {
+                    clip = dc.env_video[e] % dc.n_videos;
+                } else {
+                    uint32_t r[4];
+                    counter_rng(dc.seed_lo, dc.seed_hi, env, 0xFFFFFFFFu, 3u, 0u, r);
+                    clip = r[0] % dc.n_videos;
+                }
+            }
+            fu->video_frame = clip * dc.n_frames + (uint32_t)(((u64)first + (u64)step) % dc.n_frames);
         }
         // Background and the two ground greys are the same for every pixel that shows them:
         // run them through the colour distractor and the quantiser once per frame.

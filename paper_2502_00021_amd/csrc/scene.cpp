@@ -201,8 +201,8 @@ bool finite_all(const float* p, int n) {
 
 int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
     SceneConsts& c = hs.c;
-    if (d.width < 8 || d.width > 128 || d.height < 8 || d.height > 128) {
-        err = "width and height must lie in [8,128]";
+    if (d.width < 8 || d.width > 512 || d.height < 8 || d.height > 512) {
+        err = "width and height must lie in [8,512]";
         return PXR_ERR_UNSUPPORTED;
     }
     if (d.n_bodies < 1 || d.n_bodies > 64) {
@@ -381,7 +381,7 @@ int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
         c.lds_total = align(o, 16);
         return c.lds_total;
     };
-    const uint32_t kHalf = 80u * 1024u, kAll = 160u * 1024u, kMaxBands = 8;
+    const uint32_t kHalf = 80u * 1024u, kAll = 160u * 1024u, kMaxBands = 128;
     uint32_t chosen = 0;
     for (uint32_t nb = 1; nb <= kMaxBands && !chosen; ++nb)
         if (layout(nb) <= kHalf) chosen = nb;

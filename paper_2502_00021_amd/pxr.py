@@ -45,7 +45,7 @@ class DistractorDesc(C.Structure):
     _fields_ = [("mode", C.c_uint32), ("seed", C.c_uint64),
                 ("scale_lo", C.c_float), ("scale_hi", C.c_float), ("offset_lo", C.c_float), ("offset_hi", C.c_float),
                 ("d_video", C.c_void_p), ("n_frames", C.c_uint32), ("alpha", C.c_float),
-                ("d_env_offset", C.c_void_p)]
+                ("d_env_offset", C.c_void_p), ("n_videos", C.c_uint32), ("d_env_video", C.c_void_p)]
 
 
 class SkeletonDesc(C.Structure):
@@ -205,9 +205,18 @@ class Scene:
         s.offset_lo, s.offset_hi = d.get("offset", (0.0, 0.0))
         if d["mode"] == "video":
             v = d["video"]
-            assert v.is_cuda and v.is_contiguous() and v.dtype.itemsize == 1 and tuple(v.shape[1:]) == (self.H, self.W, 3)
+            assert v.is_cuda and v.is_contiguous() and v.dtype.itemsize == 1 and tuple(v.shape[-3:]) == (self.H, self.W, 3)
             s.d_video = v.data_ptr()
-            s.n_frames = v.shape[0]
+            if v.dim() == 5:  # a set of clips [n_videos, n_frames, H, W, 3]
+                s.n_videos, s.n_frames = v.shape[0], v.shape[1]
+                ev = d.get("env_video")
+                if ev is not None:
+                    assert ev.is_cuda and ev.is_contiguous() and ev.dtype.itemsize == 4
+                    s.d_env_video = ev.data_ptr()
+                    self._bound.append(ev)
+            else:
+                assert v.dim() == 4
+                s.n_frames = v.shape[0]
             s.alpha = float(d.get("alpha", 0.5))
             self._bound.append(v)
             eo = d.get("env_offset")

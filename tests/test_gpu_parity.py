@@ -37,6 +37,8 @@ def _bind(torch, scene, dis):
         d["video"] = torch.from_numpy(np.ascontiguousarray(d["video"])).cuda()
         if d.get("env_offset") is not None:
             d["env_offset"] = torch.from_numpy(np.asarray(d["env_offset"]).astype(np.int32)).cuda()
+        if d.get("env_video") is not None:
+            d["env_video"] = torch.from_numpy(np.asarray(d["env_video"]).astype(np.int32)).cuda()
     scene.apply_distractor(d)
 
 
@@ -149,6 +151,35 @@ def test_image_shapes_including_unpacked_store_path(torch, pxr, orc, W, H):
     assert_parity(gpu_render(torch, pxr, w, step0=2), oracle_render(orc, w, step0=2))
 
 
+@pytest.mark.parametrize("cfg,W,H,B", [(5, 256, 256, 3), (4, 200, 312, 2), (3, 512, 512, 2), (2, 500, 36, 3), (5, 132, 130, 3)])
+def test_frames_larger_than_one_key_buffer(torch, pxr, orc, cfg, W, H, B):
+    """Up to 512x512: the pixel keys are held a band of rows at a time (dozens of bands at the top end)."""
+    w = wl.make(cfg, B=B)
+    w["desc"]["width"], w["desc"]["height"] = W, H
+    if w["distractor"] is not None and w["distractor"]["mode"] == "video":
+        rng = np.random.default_rng(W + H)
+        w["distractor"] = dict(w["distractor"], video=rng.integers(0, 256, (5, H, W, 3), dtype=np.uint8))
+    ref = oracle_render(orc, w, step0=1)
+    assert (ref["ids"] < GROUND).mean() > 0.001
+    assert_parity(gpu_render(torch, pxr, w, step0=1), ref)
+
+
+def test_close_up_at_512(torch, pxr, orc):
+    """Triangles hundreds of pixels wide crossing many bands."""
+    rng = np.random.default_rng(77)
+    B = 2
+    poses = np.zeros((B, 1, 3, 7), np.float32)
+    poses[:, 0, 0, :3] = (0, 0, 1)
+    poses[:, 0, 0, 3:] = wl.random_quats(rng, (B,))
+    for b in (1, 2):
+        poses[:, 0, b, :3] = np.array([0, 0, 1]) + rng.uniform(-0.5, 0.5, (B, 3))
+        poses[:, 0, b, 3:] = wl.random_quats(rng, (B,))
+    w = dict(desc=_close_up(512, 384), poses=poses, shapes=None, distractor=None)
+    ref = oracle_render(orc, w)
+    assert (ref["ids"] < GROUND).mean() > 0.3
+    assert_parity(gpu_render(torch, pxr, w), ref)
+
+
 # ---------------------------------------------------------------- large triangles, clipping, rejects
 
 def _close_up(W=64, H=64, offset=(-0.9, 0.1, 0.35)):
@@ -258,6 +289,25 @@ def test_video_distractor_offsets_alpha_and_wrap(torch, pxr, orc):
         assert_parity(gpu_render(torch, pxr, w2, step0=step0, env0=5), ref)
     plain = gpu_render(torch, pxr, dict(w, distractor=None))
     assert np.array_equal(plain["frames"], gpu_render(torch, pxr, w2, step0=3)["frames"])  # alpha = 0
+
+
+def test_video_sets_one_clip_per_environment(torch, pxr, orc):
+    """A set of clips [n_videos, n_frames, H, W, 3]: each environment plays one, drawn from the generator or given."""
+    w = wl.make(4, B=14)
+    rng = np.random.default_rng(21)
+    clips = rng.integers(0, 256, (5, 9, 84, 84, 3), dtype=np.uint8)
+    for dis, step0 in [(dict(mode="video", seed=4, video=clips, alpha=0.5), 0),
+                       (dict(mode="video", seed=77, video=clips, alpha=0.7, env_offset=np.arange(14) * 3), 8),
+                       (dict(mode="video", seed=4, video=clips, alpha=0.5, env_video=np.arange(14) % 5), 2),
+                       (dict(mode="video", seed=4, video=clips, alpha=0.5, env_video=np.arange(14) + 3,
+                             env_offset=np.arange(14)[::-1].copy()), 0xFFFFFFF8),
+                       (dict(mode="video", seed=4, video=clips[:1], alpha=0.5), 3)]:
+        w2 = dict(w, distractor=dis)
+        assert_parity(gpu_render(torch, pxr, w2, step0=step0, env0=3), oracle_render(orc, w2, step0=step0, env0=3))
+    # a set of one clip is the single-clip case
+    a = gpu_render(torch, pxr, dict(w, distractor=dict(mode="video", seed=4, video=clips[:1], alpha=0.5)), step0=3)
+    b = gpu_render(torch, pxr, dict(w, distractor=dict(mode="video", seed=4, video=clips[0], alpha=0.5)), step0=3)
+    assert np.array_equal(a["frames"], b["frames"])
 
 
 def test_rebinding_and_unbinding(torch, pxr, orc):

@@ -83,7 +83,7 @@ def _expect(desc, code):
 def test_scene_validation_errors():
     base = wl.make(1, B=1)["desc"]
     _expect(dict(base, width=4), pxr.ERR_UNSUPPORTED)
-    _expect(dict(base, height=129), pxr.ERR_UNSUPPORTED)
+    _expect(dict(base, height=513), pxr.ERR_UNSUPPORTED)
     _expect(dict(base, bodies=[]), pxr.ERR_UNSUPPORTED)
     _expect(dict(base, bodies=base["bodies"] * 17), pxr.ERR_UNSUPPORTED)  # 68 bodies
     _expect(dict(base, root_body=4), pxr.ERR_INVALID_ARG)
@@ -117,7 +117,7 @@ def test_null_arguments_are_errors_not_crashes():
 
 def test_row_division_constant():
     """p // W == (p * ceil(2^32 / W)) >> 32 for every pixel index of every supported width."""
-    for W in range(8, 129):
+    for W in range(8, 513):
         magic = ((1 << 32) + W - 1) // W
-        p = np.arange(128 * W, dtype=np.uint64)
+        p = np.arange(512 * W, dtype=np.uint64)
         assert np.array_equal((p * np.uint64(magic)) >> np.uint64(32), p // np.uint64(W))

@@ -175,6 +175,37 @@ def test_video_alpha_limits_mask_and_frame_advance(orc, small):
         assert np.array_equal(auto["frames"][e, 0][m], video[fi][m])
 
 
+def test_video_sets_play_one_clip_per_environment(orc, small):
+    """Several clips: environment e shows clip c(e) (given, reduced modulo the count, or drawn from stream 3 at
+    step word 0xFFFFFFFF), i.e. exactly what a single-clip render with that clip shows."""
+    s = orc.Scene(small["desc"])
+    H = W = 40
+    rng = np.random.default_rng(9)
+    clips = rng.integers(0, 256, (4, 5, H, W, 3), dtype=np.uint8)
+    eo = np.array([0, 1, 2, 3, 4, 7], np.uint32)
+    ev = np.array([3, 0, 1, 2, 6, 9], np.uint32)  # 6 -> 2, 9 -> 1
+    got = s.render(small["poses"], distractor=dict(mode="video", video=clips, alpha=0.6, env_offset=eo, env_video=ev), step0=4)
+    for e in range(6):
+        one = s.render(small["poses"][e:e + 1], env0=e, step0=4,
+                       distractor=dict(mode="video", video=clips[int(ev[e]) % 4], alpha=0.6, env_offset=eo[e:e + 1]))
+        assert np.array_equal(got["frames"][e], one["frames"][0])
+    auto = s.render(small["poses"], distractor=dict(mode="video", video=clips, alpha=1.0, seed=55), step0=3, env0=9)
+    plain = s.render(small["poses"])
+    masked = (plain["ids"] == BG) | (plain["ids"] == GROUND)
+    for e in range(6):
+        clip = int(orc.philox(55, 9 + e, MASK, 3, 0)[0]) % 4
+        fi = (int(orc.philox(55, 9 + e, MASK, 2, 0)[0]) % 5 + 3) % 5
+        m = masked[e, 0]
+        assert np.array_equal(auto["frames"][e, 0][m], clips[clip, fi][m])
+    # the drawn clip index is spread over the set
+    picks = [int(orc.philox(1, e, MASK, 3, 0)[0]) % 4 for e in range(4000)]
+    assert min(np.bincount(picks, minlength=4)) > 900
+    # one clip given as a set of one
+    a = s.render(small["poses"], distractor=dict(mode="video", video=clips[:1], alpha=0.5, seed=2), step0=1)
+    b = s.render(small["poses"], distractor=dict(mode="video", video=clips[0], alpha=0.5, seed=2), step0=1)
+    assert np.array_equal(a["frames"], b["frames"])
+
+
 # ---------------------------------------------------------------- whole path
 
 @pytest.mark.parametrize("cfg,B", [(1, 16), (2, 6), (3, 6), (4, 4), (5, 4)])
