@@ -219,6 +219,33 @@ void build_box(MeshOut out, uint32_t base, uint32_t n) {
     }
 }
 
+// Arbitrary triangle mesh given by the caller: vertices are taken as they are (fp32, selector 0, scaled
+// per axis by the body's shape like any other template), triangles keep their order, the normal of a
+// triangle is the unit cross product (v1-v0) x (v2-v0) of its unscaled vertices in double (zero for a
+// triangle without area), the colour multiplier is the caller's (1 if none).  Returns false on an index
+// out of range.
+bool build_mesh(MeshOut out, uint32_t base, uint32_t nv, const float* verts, uint32_t nt, const uint32_t* tris,
+                const float* mul) {
+    for (uint32_t v = 0; v < nv; ++v) {
+        for (int c = 0; c < 3; ++c) out.uv.push_back(verts[(size_t)v * 3 + c]);
+        out.uv.push_back(0.0f);
+    }
+    for (uint32_t t = 0; t < nt; ++t) {
+        const uint32_t* ix = tris + (size_t)t * 3;
+        if (ix[0] >= nv || ix[1] >= nv || ix[2] >= nv) return false;
+        D3 p[3];
+        for (int q = 0; q < 3; ++q) p[q] = D3{verts[(size_t)ix[q] * 3], verts[(size_t)ix[q] * 3 + 1], verts[(size_t)ix[q] * 3 + 2]};
+        D3 n = unit_normal(p[0], p[1], p[2]);
+        if (!(std::isfinite(n.x) && std::isfinite(n.y) && std::isfinite(n.z))) n = D3{0.0, 0.0, 0.0};
+        for (int q = 0; q < 3; ++q) out.tri.push_back(base + ix[q]);
+        out.nrm.push_back((float)n.x);
+        out.nrm.push_back((float)n.y);
+        out.nrm.push_back((float)n.z);
+        out.mul.push_back(mul ? mul[t] : 1.0f);
+    }
+    return true;
+}
+
 // ---------------------------------------------------------------- V: vertices
 
 struct FrameXform {
@@ -410,6 +437,17 @@ orc_scene* orc_scene_create(uint32_t width, uint32_t height, uint32_t n_bodies, 
                             const uint32_t* kinds, const float* shapes, const float* rgbs,
                             const uint32_t* n_lon, const uint32_t* n_lat, const float* cam,
                             const float* light, const float* ground, const float* bg) {
+    return orc_scene_create_meshes(width, height, n_bodies, root_body, kinds, shapes, rgbs, n_lon, n_lat, cam, light,
+                                   ground, bg, nullptr, nullptr, nullptr, nullptr, nullptr);
+}
+
+orc_scene* orc_scene_create_meshes(uint32_t width, uint32_t height, uint32_t n_bodies, uint32_t root_body,
+                                   const uint32_t* kinds, const float* shapes, const float* rgbs,
+                                   const uint32_t* n_lon, const uint32_t* n_lat, const float* cam,
+                                   const float* light, const float* ground, const float* bg,
+                                   const uint32_t* mesh_nv, const uint32_t* mesh_nt, const float* mesh_verts,
+                                   const uint32_t* mesh_tris, const float* mesh_mul) {
+    size_t mesh_v0 = 0, mesh_t0 = 0;  // running offsets into the concatenated mesh arrays
     if (!kinds || !shapes || !rgbs || !n_lon || !n_lat || !cam || !light || !ground || !bg) return nullptr;
     if (width < 1 || height < 1 || n_bodies < 1 || root_body >= n_bodies) return nullptr;
     orc_scene* s = new orc_scene();
@@ -427,6 +465,12 @@ orc_scene* orc_scene_create(uint32_t width, uint32_t height, uint32_t n_bodies, 
         if (bd.kind == ORC_CAPSULE && bd.n_lon >= 3 && bd.n_lat >= 1) build_round(out, bd.vert_base, bd.n_lon, bd.n_lat, true);
         else if (bd.kind == ORC_SPHERE && bd.n_lon >= 3 && bd.n_lat >= 1) build_round(out, bd.vert_base, bd.n_lon, bd.n_lat, false);
         else if (bd.kind == ORC_BOX && bd.n_lon >= 1) build_box(out, bd.vert_base, bd.n_lon);
+        else if (bd.kind == ORC_MESH && mesh_nv && mesh_nt && mesh_verts && mesh_tris && mesh_nv[b] >= 1 && mesh_nt[b] >= 1) {
+            ok = build_mesh(out, bd.vert_base, mesh_nv[b], mesh_verts + mesh_v0 * 3, mesh_nt[b], mesh_tris + mesh_t0 * 3,
+                            mesh_mul ? mesh_mul + mesh_t0 : nullptr);
+            mesh_v0 += mesh_nv[b];
+            mesh_t0 += mesh_nt[b];
+        }
         else ok = false;
         if (!ok) { delete s; return nullptr; }
         bd.n_verts = (uint32_t)(s->uv.size() / 4) - bd.vert_base;

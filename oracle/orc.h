@@ -43,6 +43,7 @@ extern "C" {
 #define ORC_CAPSULE 0u
 #define ORC_SPHERE  1u
 #define ORC_BOX     2u
+#define ORC_MESH    3u
 
 /* distractor modes (paper section 2: "color" or "video") */
 #define ORC_DIS_NONE  0u
@@ -62,6 +63,19 @@ orc_scene* orc_scene_create(uint32_t width, uint32_t height, uint32_t n_bodies, 
                             const uint32_t* kinds, const float* shapes, const float* rgbs,
                             const uint32_t* n_lon, const uint32_t* n_lat,
                             const float* cam, const float* light, const float* ground, const float* bg);
+/* The same, with caller-supplied triangle meshes for the bodies of kind ORC_MESH (the paper names mesh
+ * rendering as the renderer's next step).  mesh_nv[K], mesh_nt[K]: vertex / triangle counts per body (0 for
+ * the other kinds); mesh_verts / mesh_tris / mesh_mul: the meshes of the ORC_MESH bodies concatenated in body
+ * order ([sum nv][3] body-frame positions, [sum nt][3] indices local to the body's own vertices,
+ * counter-clockwise seen from outside, [sum nt] colour multipliers or NULL = 1).  A mesh vertex is posed
+ * like any template vertex (scaled per axis by shape[0..2]); a triangle's normal is the unit cross product
+ * of its unscaled vertices. */
+orc_scene* orc_scene_create_meshes(uint32_t width, uint32_t height, uint32_t n_bodies, uint32_t root_body,
+                                   const uint32_t* kinds, const float* shapes, const float* rgbs,
+                                   const uint32_t* n_lon, const uint32_t* n_lat,
+                                   const float* cam, const float* light, const float* ground, const float* bg,
+                                   const uint32_t* mesh_nv, const uint32_t* mesh_nt, const float* mesh_verts,
+                                   const uint32_t* mesh_tris, const float* mesh_mul);
 void orc_scene_destroy(orc_scene* s);
 
 /* total template vertices / triangles */

@@ -16,7 +16,7 @@ _LIB = os.path.join(_HERE, "liborc.so")
 
 ID_GROUND = 0xFFFFFFFE
 ID_BG = 0xFFFFFFFF
-KINDS = {"capsule": 0, "sphere": 1, "box": 2}
+KINDS = {"capsule": 0, "sphere": 1, "box": 2, "mesh": 3}
 MODES = {"none": 0, "color": 1, "video": 2}
 
 CXXFLAGS = ["-O2", "-std=c++17", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared", "-Wall", "-Wextra"]
@@ -49,6 +49,8 @@ def lib():
         vp, u32, u64, f32 = C.c_void_p, C.c_uint32, C.c_uint64, C.c_float
         _lib.orc_scene_create.restype = vp
         _lib.orc_scene_create.argtypes = [u32, u32, u32, u32] + [vp] * 9
+        _lib.orc_scene_create_meshes.restype = vp
+        _lib.orc_scene_create_meshes.argtypes = [u32, u32, u32, u32] + [vp] * 14
         _lib.orc_scene_destroy.argtypes = [vp]
         _lib.orc_scene_destroy.restype = None
         _lib.orc_scene_counts.argtypes = [vp, vp, vp]
@@ -99,8 +101,19 @@ class Scene:
         ground = _f32([1.0 if desc["ground_enabled"] else 0.0, desc["ground_cell"], *desc["ground_grey"]])
         bg = _f32(desc["background_rgb"])
         self.W, self.H, self.K = int(desc["width"]), int(desc["height"]), K
-        self._h = L.orc_scene_create(self.W, self.H, K, int(desc["root_body"]), _p(kinds), _p(shapes), _p(rgbs),
-                                     _p(nlon), _p(nlat), _p(cam), _p(light), _p(ground), _p(bg))
+        meshes = [b for b in bodies if b["kind"] == "mesh"]
+        mesh_nv = np.array([len(b["verts"]) if b["kind"] == "mesh" else 0 for b in bodies], dtype=np.uint32)
+        mesh_nt = np.array([len(b["tris"]) if b["kind"] == "mesh" else 0 for b in bodies], dtype=np.uint32)
+        if meshes:
+            mv = _f32(np.concatenate([np.asarray(b["verts"], np.float32).reshape(-1, 3) for b in meshes]))
+            mt = np.ascontiguousarray(np.concatenate([np.asarray(b["tris"]).reshape(-1, 3) for b in meshes]), dtype=np.uint32)
+            mm = _f32(np.concatenate([np.ones(len(b["tris"]), np.float32) if b.get("mul") is None
+                                      else np.asarray(b["mul"], np.float32) for b in meshes]))
+        else:
+            mv = mt = mm = None
+        self._h = L.orc_scene_create_meshes(self.W, self.H, K, int(desc["root_body"]), _p(kinds), _p(shapes), _p(rgbs),
+                                            _p(nlon), _p(nlat), _p(cam), _p(light), _p(ground), _p(bg),
+                                            _p(mesh_nv), _p(mesh_nt), _p(mv), _p(mt), _p(mm))
         if not self._h:
             raise ValueError("orc_scene_create rejected the scene description")
         nv, nt = C.c_uint32(), C.c_uint32()

@@ -42,6 +42,76 @@ def box(ex, ey, ez, rgb, n=4):
                 rgb=tuple(float(c) for c in rgb), n_lon=n, n_lat=0)
 
 
+def mesh(verts, tris, rgb, scale=(1.0, 1.0, 1.0), mul=None):
+    """A caller-supplied triangle mesh body: verts [nv,3] fp32 body-frame positions, tris [nt,3] indices,
+    counter-clockwise seen from outside; scale = per-axis factors (the body's shape); mul = per-triangle colour
+    multipliers or None."""
+    return dict(kind="mesh", shape=(float(scale[0]), float(scale[1]), float(scale[2]), 0.0),
+                rgb=tuple(float(c) for c in rgb), n_lon=0, n_lat=0,
+                verts=np.ascontiguousarray(verts, dtype=np.float32).reshape(-1, 3),
+                tris=np.ascontiguousarray(tris, dtype=np.uint32).reshape(-1, 3),
+                mul=None if mul is None else np.ascontiguousarray(mul, dtype=np.float32))
+
+
+# ------------------------------------------------------------------ procedural meshes (stand-ins for user assets)
+
+def torus_mesh(R=0.3, r=0.1, n_major=16, n_minor=8):
+    """Torus around the z axis: (nv, nt) = (n_major*n_minor, 2*n_major*n_minor), outward-facing."""
+    u = 2.0 * np.pi * np.arange(n_major) / n_major
+    v = 2.0 * np.pi * np.arange(n_minor) / n_minor
+    uu, vv = np.meshgrid(u, v, indexing="ij")
+    verts = np.stack([(R + r * np.cos(vv)) * np.cos(uu), (R + r * np.cos(vv)) * np.sin(uu), r * np.sin(vv)], axis=-1)
+    idx = lambda i, j: (i % n_major) * n_minor + (j % n_minor)
+    tris = []
+    for i in range(n_major):
+        for j in range(n_minor):
+            a, b, c, d = idx(i, j), idx(i + 1, j), idx(i + 1, j + 1), idx(i, j + 1)
+            tris += [(a, b, c), (a, c, d)]
+    return verts.reshape(-1, 3).astype(np.float32), np.array(tris, np.uint32)
+
+
+def icosphere_mesh(radius=0.2, subdivisions=1):
+    """Subdivided icosahedron: 20 * 4^s triangles, vertices pushed to the sphere, outward-facing."""
+    t = (1.0 + 5.0 ** 0.5) / 2.0
+    v = [(-1, t, 0), (1, t, 0), (-1, -t, 0), (1, -t, 0), (0, -1, t), (0, 1, t), (0, -1, -t), (0, 1, -t),
+         (t, 0, -1), (t, 0, 1), (-t, 0, -1), (-t, 0, 1)]
+    f = [(0, 11, 5), (0, 5, 1), (0, 1, 7), (0, 7, 10), (0, 10, 11), (1, 5, 9), (5, 11, 4), (11, 10, 2), (10, 7, 6),
+         (7, 1, 8), (3, 9, 4), (3, 4, 2), (3, 2, 6), (3, 6, 8), (3, 8, 9), (4, 9, 5), (2, 4, 11), (6, 2, 10), (8, 6, 7),
+         (9, 8, 1)]
+    v = [np.array(p, np.float64) / np.linalg.norm(p) for p in v]
+    for _ in range(subdivisions):
+        cache, nf = {}, []
+
+        def mid(a, b):
+            key = (min(a, b), max(a, b))
+            if key not in cache:
+                m = v[a] + v[b]
+                v.append(m / np.linalg.norm(m))
+                cache[key] = len(v) - 1
+            return cache[key]
+        for a, b, c in f:
+            ab, bc, ca = mid(a, b), mid(b, c), mid(c, a)
+            nf += [(a, ab, ca), (b, bc, ab), (c, ca, bc), (ab, bc, ca)]
+        f = nf
+    return (radius * np.array(v)).astype(np.float32), np.array(f, np.uint32)
+
+
+def heightfield_mesh(rng, n=12, size=1.0, height=0.15):
+    """Open n x n-cell terrain patch in the x-y plane with random heights, facing +z."""
+    xs = np.linspace(-size / 2, size / 2, n + 1)
+    xx, yy = np.meshgrid(xs, xs, indexing="ij")
+    zz = height * rng.uniform(0.0, 1.0, xx.shape)
+    verts = np.stack([xx, yy, zz], axis=-1).reshape(-1, 3)
+    idx = lambda i, j: i * (n + 1) + j
+    tris, mul = [], []
+    for i in range(n):
+        for j in range(n):
+            a, b, c, d = idx(i, j), idx(i + 1, j), idx(i + 1, j + 1), idx(i, j + 1)
+            tris += [(a, b, c), (a, c, d)]
+            mul += [1.0 if (i + j) & 1 else 0.6] * 2
+    return verts.astype(np.float32), np.array(tris, np.uint32), np.array(mul, np.float32)
+
+
 # ------------------------------------------------------------------ quaternion helpers (w,x,y,z), float64
 
 def q_mul(a, b):
@@ -315,6 +385,30 @@ def cfg5(B=65536, S=3):
     fk = dict(skel=skel, free_poses=np.ascontiguousarray(poses[:, :, [0, 14]]), angles=all_angles)
     return dict(name="cfg5-humanoid-box-64-stack3", desc=default_scene(64, 64, bodies),
                 poses=poses, shapes=shapes, distractor=dis, step0=0, fk=fk)
+
+
+def cfg_mesh(B=64, W=64, H=64):
+    """Mesh bodies (the paper's stated next step for its renderer): a free-floating torus, an icosphere and a
+    terrain patch given as vertex / index buffers, next to one capsule, with the colour distractor."""
+    rng = np.random.default_rng(SEED_BASE + 6)
+    tv, tt = torus_mesh(0.3, 0.1, 20, 10)
+    iv, it = icosphere_mesh(0.2, 2)
+    hv, ht, hm = heightfield_mesh(rng, 12, 1.6, 0.25)
+    bodies = [capsule(0.08, 0.25, (0.8, 0.3, 0.3), 12, 6), mesh(tv, tt, (0.3, 0.7, 0.4)),
+              mesh(iv, it, (0.4, 0.4, 0.9), scale=(1.0, 1.4, 0.7)), mesh(hv, ht, (0.7, 0.6, 0.4), mul=hm)]
+    K = 4
+    pos = np.zeros((B, 1, K, 3))
+    quat = np.zeros((B, 1, K, 4))
+    pos[:, 0, 0] = (0.0, 0.0, 1.0)
+    quat[:, 0, 0] = random_quats(rng, (B,))
+    for k in (1, 2):
+        pos[:, 0, k] = np.array([0.3, 0.0, 1.0]) + rng.uniform(-0.7, 0.7, (B, 3)) * np.array([1.0, 1.0, 0.5])
+        quat[:, 0, k] = random_quats(rng, (B,))
+    pos[:, 0, 3] = np.array([1.0, 0.0, 0.05]) + rng.uniform(-0.3, 0.3, (B, 3)) * np.array([1.0, 1.0, 0.0])
+    quat[:, 0, 3] = q_axis_angle(EZ, rng.uniform(0.0, 2.0 * np.pi, B))
+    dis = dict(mode="color", seed=SEED_BASE + 6, scale=(0.5, 1.5), offset=(-0.2, 0.2))
+    return dict(name="mesh-bodies-64", desc=default_scene(W, H, bodies), poses=_pose(pos, quat), shapes=None,
+                distractor=dis, step0=0)
 
 
 CONFIGS = {1: cfg1, 2: cfg2, 3: cfg3, 4: cfg4, 5: cfg5}

@@ -151,3 +151,87 @@ def test_bodies_concatenate_in_descriptor_order(orc):
     assert np.array_equal(m["tri_body"], np.repeat(np.arange(3), nt))
     vb = m["vert_body"][m["tris"].astype(np.int64)]
     assert np.all(vb == m["tri_body"][:, None]), "a triangle indexes another body's vertices"
+
+
+# ---------------------------------------------------------------- caller-supplied triangle meshes
+
+def _as_mesh_body(orc, prim, rgb):
+    """The primitive's own template, handed back as a vertex / index buffer."""
+    m = orc.Scene(wl.default_scene(16, 16, [prim])).mesh()
+    assert np.all(m["uverts"][:, 3] == 0)  # no cap selector: boxes and spheres only
+    return wl.mesh(m["uverts"][:, :3], m["tris"], rgb, scale=prim["shape"][:3], mul=m["mul"])
+
+
+def test_mesh_body_reproduces_the_box_primitive(orc):
+    """Same vertices, same triangle order, axis-aligned faces (cross products are exact): identical frames."""
+    rgb = (0.7, 0.5, 0.3)
+    box = wl.box(0.3, 0.2, 0.25, rgb, 3)
+    rng = np.random.default_rng(3)
+    poses = np.zeros((6, 1, 1, 7), np.float32)
+    poses[:, 0, 0, :3] = (0, 0, 1)
+    poses[:, 0, 0, 3:] = wl.random_quats(rng, (6,))
+    a = orc.Scene(wl.default_scene(48, 40, [box])).render(poses)
+    sm = orc.Scene(wl.default_scene(48, 40, [_as_mesh_body(orc, box, rgb)]))
+    b = sm.render(poses)
+    assert np.array_equal(a["ids"], b["ids"]) and np.array_equal(a["frames"], b["frames"])
+    assert (a["ids"] < 0xFFFFFFFE).mean() > 0.02
+    assert np.array_equal(sm.mesh()["normals"], orc.Scene(wl.default_scene(16, 16, [box])).mesh()["normals"])
+
+
+def test_mesh_body_reproduces_the_sphere_up_to_normal_rounding(orc):
+    """Same vertices and order: coverage identical; the normals are recomputed from the fp32 vertices, so
+    shading may move by one quantisation step."""
+    rgb = (0.4, 0.6, 0.8)
+    sph = wl.sphere(0.3, rgb, 10, 4)
+    rng = np.random.default_rng(4)
+    poses = np.zeros((4, 1, 1, 7), np.float32)
+    poses[:, 0, 0, :3] = (0, 0, 1)
+    poses[:, 0, 0, 3:] = wl.random_quats(rng, (4,))
+    a = orc.Scene(wl.default_scene(64, 64, [sph])).render(poses)
+    sm = orc.Scene(wl.default_scene(64, 64, [_as_mesh_body(orc, sph, rgb)]))
+    b = sm.render(poses)
+    assert np.array_equal(a["ids"], b["ids"])
+    assert np.abs(a["frames"].astype(int) - b["frames"].astype(int)).max() <= 1
+    n = sm.mesh()["normals"].astype(np.float64)
+    assert np.allclose(np.linalg.norm(n, axis=1), 1.0, atol=1e-6)
+    assert np.abs(n - orc.Scene(wl.default_scene(16, 16, [sph])).mesh()["normals"]).max() < 1e-6
+
+
+def test_mesh_normals_scale_multipliers_and_errors(orc):
+    verts = np.array([[0, 0, 0], [1, 0, 0], [0, 1, 0], [0, 0, 1], [2, 0, 0]], np.float32)
+    tris = np.array([[0, 1, 2], [0, 2, 1], [0, 3, 1], [0, 1, 4]], np.uint32)  # the last one has no area
+    body = wl.mesh(verts, tris, (0.5, 0.5, 0.5), scale=(2.0, 3.0, 4.0), mul=[1.0, 0.5, 0.25, 1.0])
+    s = orc.Scene(wl.default_scene(16, 16, [body]))
+    m = s.mesh()
+    assert (s.V, s.T) == (5, 4)
+    assert np.array_equal(m["normals"], np.array([[0, 0, 1], [0, 0, -1], [0, 1, 0], [0, 0, 0]], np.float32))
+    assert np.array_equal(m["mul"], np.array([1.0, 0.5, 0.25, 1.0], np.float32))
+    assert np.array_equal(m["uverts"], np.concatenate([verts, np.zeros((5, 1), np.float32)], axis=1))
+    # posed like any template: scaled per axis, then rotated and translated
+    vs = s.vertex_stage(np.array([[0, 0, 1, 1, 0, 0, 0]], np.float32))
+    ref = orc.Scene(wl.default_scene(16, 16, [wl.mesh(verts * np.array([2, 3, 4], np.float32), tris, (0.5,) * 3)]))
+    vr = ref.vertex_stage(np.array([[0, 0, 1, 1, 0, 0, 0]], np.float32))
+    assert np.array_equal(vs["X"], vr["X"]) and np.array_equal(vs["Y"], vr["Y"])
+    bad = wl.mesh(verts, np.array([[0, 1, 5]], np.uint32), (0.5,) * 3)
+    with pytest.raises(ValueError):
+        orc.Scene(wl.default_scene(16, 16, [bad]))
+
+
+def test_mesh_workload_structure(orc):
+    w = wl.cfg_mesh(B=6)
+    s = orc.Scene(w["desc"])
+    tv, tt = wl.torus_mesh(0.3, 0.1, 20, 10)
+    iv, it = wl.icosphere_mesh(0.2, 2)
+    assert (s.V, s.T) == (2 * 12 * 6 + 2 + len(tv) + len(iv) + 13 * 13, 288 + len(tt) + len(it) + 288)
+    assert (len(tv), len(tt), len(iv), len(it)) == (200, 400, 162, 320)
+    # closed, consistently outward meshes: every edge is used once in each direction, volume matches the solid
+    for v, t, vol in [(tv, tt, 2 * np.pi ** 2 * 0.3 * 0.1 ** 2), (iv, it, 4 / 3 * np.pi * 0.2 ** 3)]:
+        edges = np.concatenate([t[:, [0, 1]], t[:, [1, 2]], t[:, [2, 0]]]).astype(np.int64)
+        fwd = set(map(tuple, edges))
+        assert len(fwd) == len(edges) and fwd == set(map(tuple, edges[:, ::-1]))
+        v64 = v.astype(np.float64)
+        got = np.einsum("ij,ij->i", v64[t[:, 0]], np.cross(v64[t[:, 1]], v64[t[:, 2]])).sum() / 6
+        assert 0.8 * vol < got < vol
+    out = s.render(w["poses"], distractor=w["distractor"])
+    for lo, hi in [(0, 288), (288, 688), (688, 1008), (1008, 1296)]:  # every body is seen somewhere
+        assert ((out["ids"] >= lo) & (out["ids"] < hi)).any()

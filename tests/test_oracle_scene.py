@@ -218,6 +218,49 @@ def test_triangle_ids_match_brute_force_ray_cast(orc):
     assert checked > 0.9 * 6 * W * H and owned > 500
 
 
+def test_mesh_triangle_ids_match_brute_force_ray_cast(orc):
+    """Caller-supplied closed meshes (a non-convex torus, an icosphere, a tetrahedron) against the same ray cast."""
+    W = H = 24
+    tv, tt = wl.torus_mesh(0.3, 0.12, 8, 5)
+    iv, it = wl.icosphere_mesh(0.2, 1)
+    tet_v = np.array([[0.3, 0, -0.2], [-0.2, 0.3, -0.2], [-0.2, -0.3, -0.2], [0, 0, 0.35]], np.float32)
+    tet_t = np.array([[0, 2, 1], [0, 1, 3], [1, 2, 3], [2, 0, 3]], np.uint32)
+    bodies = [wl.mesh(tv, tt, RGB), wl.mesh(iv, it, RGB, scale=(1.0, 1.5, 0.8)), wl.mesh(tet_v, tet_t, RGB)]
+    desc = wl.default_scene(W, H, bodies)
+    desc["cam_offset"] = (-1.3, 0.0, 0.6)
+    desc["ground_enabled"] = False
+    s = orc.Scene(desc)
+    mesh = s.mesh()
+    tris = mesh["tris"].astype(np.int64)
+    shapes = [b["shape"] for b in bodies]
+    rng = np.random.default_rng(31)
+    checked = owned = 0
+    for _ in range(6):
+        poses = np.zeros((3, 7), np.float32)
+        poses[0] = pose_row((0, 0, 1), wl.random_quats(rng, ()))
+        for b in (1, 2):
+            poses[b] = pose_row((rng.uniform(-0.2, 0.3), rng.uniform(-0.5, 0.5), 1 + rng.uniform(-0.3, 0.3)),
+                                wl.random_quats(rng, ()))
+        out = s.render(poses[None, None], want_depth=True)
+        ids = out["ids"][0, 0].astype(np.int64)
+        world = world_positions(mesh, shapes, poses.astype(np.float64))
+        ref, t1, t2 = _brute_force_ids(desc, world, tris, poses[0, :3])
+        eps = 3.0 / 256.0
+        stable = np.ones_like(ref, dtype=bool)
+        for di, dj in [(-eps, 0), (eps, 0), (0, -eps), (0, eps), (-eps, -eps), (eps, eps), (-eps, eps), (eps, -eps)]:
+            stable &= _brute_force_ids(desc, world, tris, poses[0, :3], di, dj)[0] == ref
+        with np.errstate(divide="ignore", invalid="ignore"):
+            tie = np.abs(0.1 / t1 - 0.1 / t2) < 1e-5
+        stable &= ~np.where(np.isfinite(t2), tie, False)
+        assert np.array_equal(ids[stable], ref[stable])
+        hit = stable & (ref != BG)
+        depth = out["depth_bits"][0, 0].view(np.float32)
+        assert np.allclose(depth[hit], 0.1 / t1[hit], rtol=3e-3)
+        checked += int(stable.sum())
+        owned += int(hit.sum())
+    assert checked > 0.85 * 6 * W * H and owned > 400
+
+
 # ---------------------------------------------------------------- ground plane
 
 def test_horizon_row_and_checker_parity(orc):
