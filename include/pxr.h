@@ -28,7 +28,7 @@ extern "C" {
 typedef struct pxr_scene pxr_scene; /* opaque, owned by the library */
 
 enum { PXR_OK = 0, PXR_ERR_INVALID_ARG = 1, PXR_ERR_UNSUPPORTED = 2, PXR_ERR_OOM = 3, PXR_ERR_DEVICE = 4 };
-enum { PXR_CAPSULE = 0, PXR_SPHERE = 1, PXR_BOX = 2 };
+enum { PXR_CAPSULE = 0, PXR_SPHERE = 1, PXR_BOX = 2, PXR_MESH = 3 };
 enum { PXR_DISTRACT_NONE = 0, PXR_DISTRACT_COLOR = 1, PXR_DISTRACT_VIDEO = 2 };
 
 /* Winning-id values that are not triangles. */
@@ -44,12 +44,23 @@ enum { PXR_DISTRACT_NONE = 0, PXR_DISTRACT_COLOR = 1, PXR_DISTRACT_VIDEO = 2 };
  *   n_lon, n_lat: capsule/sphere: longitudes, latitude steps PER HEMISPHERE
  *          (capsule 4*n_lon*n_lat triangles, sphere 2*n_lon*(2*n_lat-1));
  *          box: n_lon = cells per face edge (12*n_lon^2 triangles, checker
- *          colour multiplier 1 / 0.5 per cell), n_lat ignored. */
+ *          colour multiplier 1 / 0.5 per cell), n_lat ignored.
+ *   PXR_MESH (the paper names mesh rendering as its renderer's next step): the caller's own triangle mesh.
+ *          mesh_verts [n_mesh_verts*3] body-frame positions, used as the template as they are (selector 0,
+ *          scaled per axis by shape[0..2], shape[3] ignored); mesh_tris [n_mesh_tris*3] indices into them,
+ *          counter-clockwise seen from outside (back faces are culled); mesh_tri_mul [n_mesh_tris] colour
+ *          multiplier per triangle, or NULL = 1.  Host arrays, copied at scene creation; ignored for the
+ *          other types.  A triangle's normal is the unit cross product of its unscaled vertices (zero for
+ *          a triangle without area: it is shaded with the ambient term only). */
 typedef struct {
     uint32_t type;
     float shape[4];
     float rgb[3];
     uint32_t n_lon, n_lat;
+    const float* mesh_verts;
+    const uint32_t* mesh_tris;
+    const float* mesh_tri_mul;
+    uint32_t n_mesh_verts, n_mesh_tris;
 } pxr_body_desc;
 
 /* Scene = what is common to all environments: image size, bodies, camera rig,
@@ -96,7 +107,8 @@ typedef struct {
  * camera constants, upload (one allocation, one synchronous copy).  Host only,
  * not on the hot path.
  * Errors: INVALID_ARG (null pointer, root_body out of range, unknown body
- * type, non-finite or non-positive parameter, degenerate camera);
+ * type, non-finite or non-positive parameter, degenerate camera, mesh index out of
+ * range or non-finite mesh vertex);
  * UNSUPPORTED (width or height outside [8,512], n_bodies outside [1,64], more
  * than 65535 vertices or triangles, tessellation counts outside [3,64]x[1,32]
  * (box [1,16]), or a frame that does not fit the 160 KB of LDS of one

@@ -191,6 +191,69 @@ void pair_triangles(const BodyMesh& m, uint32_t vbase, uint32_t tbase, std::vect
     }
 }
 
+// A caller-supplied mesh: vertices and triangle order are kept; normals from the unscaled vertices.
+void tessellate_mesh(BodyMesh& m, const pxr_body_desc& bd) {
+    for (uint32_t v = 0; v < bd.n_mesh_verts; ++v) {
+        m.pos.push_back({(double)bd.mesh_verts[3 * v], (double)bd.mesh_verts[3 * v + 1], (double)bd.mesh_verts[3 * v + 2]});
+        m.cap.push_back(0);
+    }
+    for (uint32_t t = 0; t < bd.n_mesh_tris; ++t) {
+        const uint32_t a = bd.mesh_tris[3 * t], b = bd.mesh_tris[3 * t + 1], c = bd.mesh_tris[3 * t + 2];
+        const Vec3d n = cross(sub(m.pos[b], m.pos[a]), sub(m.pos[c], m.pos[a]));
+        const double len = norm(n);
+        Vec3d unit{n.x / len, n.y / len, n.z / len};
+        if (!(std::isfinite(unit.x) && std::isfinite(unit.y) && std::isfinite(unit.z))) unit = {0.0, 0.0, 0.0};
+        m.tri(a, b, c, unit, bd.mesh_tri_mul ? bd.mesh_tri_mul[t] : 1.0f);
+    }
+}
+
+// Pairing for meshes of unknown structure: every triangle is matched greedily with a not yet matched
+// triangle that shares one of its edges (any orientation; the binning test only looks at the two
+// vertex sets).  Same table format as pair_triangles.
+void pair_triangles_general(const BodyMesh& m, uint32_t vbase, uint32_t tbase, std::vector<uint32_t>& tbl) {
+    const uint32_t nt = (uint32_t)m.mul.size();
+    auto key = [](uint32_t a, uint32_t b) { return ((uint64_t)std::min(a, b) << 32) | std::max(a, b); };
+    std::vector<std::pair<uint64_t, uint32_t>> edges;  // (edge, triangle), sorted: neighbours sit together
+    edges.reserve((size_t)nt * 3);
+    for (uint32_t t = 0; t < nt; ++t)
+        for (int e = 0; e < 3; ++e) edges.push_back({key(m.idx[3 * t + e], m.idx[3 * t + (e + 1) % 3]), t});
+    std::sort(edges.begin(), edges.end());
+    std::vector<uint32_t> mate(nt, kNoTriangle);
+    for (uint32_t t = 0; t < nt; ++t) {
+        if (mate[t] != kNoTriangle) continue;
+        for (int e = 0; e < 3 && mate[t] == kNoTriangle; ++e) {
+            const uint32_t x = m.idx[3 * t + e], y = m.idx[3 * t + (e + 1) % 3];
+            if (x == y) continue;
+            const uint64_t k = key(x, y);
+            for (auto it = std::lower_bound(edges.begin(), edges.end(), std::make_pair(k, 0u));
+                 it != edges.end() && it->first == k; ++it) {
+                const uint32_t u = it->second;
+                if (u != t && mate[u] == kNoTriangle) {
+                    mate[t] = u;
+                    mate[u] = t;
+                    // q0, q2 = the shared edge; q1, q3 = the two remaining corners
+                    const uint32_t a3 = m.idx[3 * t + (e + 2) % 3];
+                    uint32_t b3 = x;
+                    for (int q = 0; q < 3; ++q)
+                        if (m.idx[3 * u + q] != x && m.idx[3 * u + q] != y) b3 = m.idx[3 * u + q];
+                    tbl.push_back((vbase + x) | ((vbase + a3) << 16));
+                    tbl.push_back((vbase + y) | ((vbase + b3) << 16));
+                    tbl.push_back((tbase + t) | ((tbase + u) << 16));
+                    tbl.push_back(0u);
+                    break;
+                }
+            }
+        }
+        if (mate[t] == kNoTriangle) {
+            mate[t] = t;
+            tbl.push_back((vbase + m.idx[3 * t]) | ((vbase + m.idx[3 * t + 1]) << 16));
+            tbl.push_back((vbase + m.idx[3 * t + 2]) | ((vbase + m.idx[3 * t + 2]) << 16));
+            tbl.push_back((tbase + t) | (kNoTriangle << 16));
+            tbl.push_back(0u);
+        }
+    }
+}
+
 bool finite_all(const float* p, int n) {
     for (int i = 0; i < n; ++i)
         if (!std::isfinite(p[i])) return false;
@@ -263,6 +326,26 @@ int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
                 return PXR_ERR_UNSUPPORTED;
             }
             tessellate_box(m, bd.n_lon);
+        } else if (bd.type == PXR_MESH) {
+            if (!bd.mesh_verts || !bd.mesh_tris || bd.n_mesh_verts == 0 || bd.n_mesh_tris == 0) {
+                err = "body " + std::to_string(b) + ": a mesh needs vertices and triangles";
+                return PXR_ERR_INVALID_ARG;
+            }
+            if (bd.n_mesh_verts > 65535u || bd.n_mesh_tris >= kNoTriangle) {
+                err = "scene exceeds 65535 vertices or triangles";
+                return PXR_ERR_UNSUPPORTED;
+            }
+            if (!finite_all(bd.mesh_verts, (int)bd.n_mesh_verts * 3) ||
+                (bd.mesh_tri_mul && !finite_all(bd.mesh_tri_mul, (int)bd.n_mesh_tris))) {
+                err = "body " + std::to_string(b) + ": non-finite mesh vertex or multiplier";
+                return PXR_ERR_INVALID_ARG;
+            }
+            for (uint32_t i = 0; i < bd.n_mesh_tris * 3; ++i)
+                if (bd.mesh_tris[i] >= bd.n_mesh_verts) {
+                    err = "body " + std::to_string(b) + ": mesh index out of range";
+                    return PXR_ERR_INVALID_ARG;
+                }
+            tessellate_mesh(m, bd);
         } else {
             err = "body " + std::to_string(b) + ": unknown primitive type";
             return PXR_ERR_INVALID_ARG;
@@ -287,7 +370,10 @@ int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
             hs.tri_shade.push_back((float)m.nrm[t].z);
             hs.tri_shade.push_back(m.mul[t]);
         }
-        pair_triangles(m, vbase, tbase, hs.pair_tbl);
+        if (bd.type == PXR_MESH)
+            pair_triangles_general(m, vbase, tbase, hs.pair_tbl);
+        else
+            pair_triangles(m, vbase, tbase, hs.pair_tbl);
         for (int i = 0; i < 4; ++i) hs.body_const[(size_t)b * 8 + i] = bd.shape[i];
         for (int i = 0; i < 3; ++i) hs.body_const[(size_t)b * 8 + 4 + i] = bd.rgb[i];
         vbase += nv;

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libpxr.so")
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_OOM, ERR_DEVICE = range(5)
 ID_GROUND = 0xFFFFFFFE
 ID_BG = 0xFFFFFFFF
-KINDS = {"capsule": 0, "sphere": 1, "box": 2}
+KINDS = {"capsule": 0, "sphere": 1, "box": 2, "mesh": 3}
 MODES = {"none": 0, "color": 1, "video": 2}
 
 
@@ -28,7 +28,9 @@ class PxrError(RuntimeError):
 
 class BodyDesc(C.Structure):
     _fields_ = [("type", C.c_uint32), ("shape", C.c_float * 4), ("rgb", C.c_float * 3),
-                ("n_lon", C.c_uint32), ("n_lat", C.c_uint32)]
+                ("n_lon", C.c_uint32), ("n_lat", C.c_uint32),
+                ("mesh_verts", C.c_void_p), ("mesh_tris", C.c_void_p), ("mesh_tri_mul", C.c_void_p),
+                ("n_mesh_verts", C.c_uint32), ("n_mesh_tris", C.c_uint32)]
 
 
 class SceneDesc(C.Structure):
@@ -108,12 +110,24 @@ def make_scene_desc(desc):
     """Plain-dict scene description (see workloads.default_scene) -> (SceneDesc, keep-alive list)."""
     bodies = desc["bodies"]
     arr = (BodyDesc * max(1, len(bodies)))()
+    keep = [arr]
     for i, b in enumerate(bodies):
         arr[i].type = KINDS[b["kind"]] if isinstance(b["kind"], str) else int(b["kind"])
         arr[i].shape = (C.c_float * 4)(*b["shape"])
         arr[i].rgb = (C.c_float * 3)(*b["rgb"])
         arr[i].n_lon = int(b["n_lon"])
         arr[i].n_lat = int(b.get("n_lat", 0))
+        if b.get("verts") is not None:  # caller-supplied mesh
+            v = np.ascontiguousarray(b["verts"], dtype=np.float32).reshape(-1, 3)
+            t = np.ascontiguousarray(b["tris"], dtype=np.uint32).reshape(-1, 3)
+            keep += [v, t]
+            arr[i].mesh_verts, arr[i].mesh_tris = v.ctypes.data, t.ctypes.data
+            arr[i].n_mesh_verts, arr[i].n_mesh_tris = v.shape[0], t.shape[0]
+            if b.get("mul") is not None:
+                m = np.ascontiguousarray(b["mul"], dtype=np.float32)
+                assert m.shape == (t.shape[0],)
+                keep.append(m)
+                arr[i].mesh_tri_mul = m.ctypes.data
     d = SceneDesc()
     d.width, d.height = int(desc["width"]), int(desc["height"])
     d.n_bodies, d.root_body = len(bodies), int(desc["root_body"])
@@ -128,7 +142,7 @@ def make_scene_desc(desc):
     d.ground_cell = desc["ground_cell"]
     d.ground_grey = (C.c_float * 2)(*desc["ground_grey"])
     d.background_rgb = (C.c_float * 3)(*desc["background_rgb"])
-    return d, [arr]
+    return d, keep
 
 
 def host_tables(desc):

@@ -180,6 +180,42 @@ def test_close_up_at_512(torch, pxr, orc):
     assert_parity(gpu_render(torch, pxr, w), ref)
 
 
+# ---------------------------------------------------------------- caller-supplied meshes
+
+@pytest.mark.parametrize("W,H,B,threads", [(64, 64, 40, None), (84, 84, 17, 512), (32, 32, 24, 256), (200, 160, 5, None)])
+def test_mesh_bodies_match_oracle(torch, pxr, orc, W, H, B, threads):
+    w = wl.cfg_mesh(B=B, W=W, H=H)
+    ref = oracle_render(orc, w, step0=2, env0=5)
+    for lo, hi in [(0, 288), (288, 688), (688, 1008), (1008, 1296)]:
+        assert ((ref["ids"] >= lo) & (ref["ids"] < hi)).any()
+    assert_parity(gpu_render(torch, pxr, w, step0=2, env0=5, threads=threads), ref)
+
+
+def test_mesh_close_up_and_degenerate_triangles(torch, pxr, orc):
+    """Mesh triangles tens of pixels wide, a mesh with zero-area and repeated-vertex triangles, per-env scales."""
+    rng = np.random.default_rng(12)
+    tv, tt = wl.torus_mesh(0.35, 0.15, 7, 5)
+    fan_v = np.array([[0, 0, 0]] + [[0.4 * np.cos(a), 0.4 * np.sin(a), 0.05 * a] for a in np.linspace(0, 5, 8)], np.float32)
+    fan_t = np.array([[0, i, i + 1] for i in range(1, 8)] + [[0, i + 1, i] for i in range(1, 8)] + [[3, 3, 4], [5, 6, 5]], np.uint32)
+    hv, ht, hm = wl.heightfield_mesh(rng, 5, 1.2, 0.4)
+    bodies = [wl.mesh(tv, tt, (0.8, 0.5, 0.3)), wl.mesh(fan_v, fan_t, (0.3, 0.7, 0.5), mul=rng.uniform(0.3, 1.0, len(fan_t))),
+              wl.mesh(hv, ht, (0.6, 0.6, 0.3), mul=hm)]
+    d = wl.default_scene(96, 72, bodies)
+    d["cam_offset"] = (-1.0, 0.1, 0.4)
+    B = 20
+    poses = np.zeros((B, 1, 3, 7), np.float32)
+    poses[:, 0, 0, :3] = (0, 0, 1)
+    poses[:, 0, 0, 3:] = wl.random_quats(rng, (B,))
+    for b in (1, 2):
+        poses[:, 0, b, :3] = np.array([0.1, 0, 1]) + rng.uniform(-0.5, 0.5, (B, 3))
+        poses[:, 0, b, 3:] = wl.random_quats(rng, (B,))
+    shapes = rng.uniform(0.6, 1.5, (B, 3, 4)).astype(np.float32)
+    w = dict(desc=d, poses=poses, shapes=shapes, distractor=None)
+    ref = oracle_render(orc, w)
+    assert (ref["ids"] < GROUND).mean() > 0.25
+    assert_parity(gpu_render(torch, pxr, w), ref)
+
+
 # ---------------------------------------------------------------- large triangles, clipping, rejects
 
 def _close_up(W=64, H=64, offset=(-0.9, 0.1, 0.35)):

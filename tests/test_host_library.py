@@ -73,6 +73,46 @@ def test_pair_table_covers_every_triangle_once(cfg):
     assert paired >= 0.45 * t["T"] if cfg != 1 else paired > 0
 
 
+def test_mesh_bodies_tables_and_pairing(orc):
+    """Caller-supplied meshes: tables equal the oracle's, every triangle sits in exactly one binning entry."""
+    rng = np.random.default_rng(2)
+    desc = wl.cfg_mesh(B=1)["desc"]
+    fan_v = np.array([[0, 0, 0]] + [[np.cos(a), np.sin(a), 0.1 * a] for a in np.linspace(0, 5, 8)], np.float32)
+    fan_t = np.array([[0, i, i + 1] for i in range(1, 8)] + [[3, 3, 4], [5, 6, 5]], np.uint32)  # incl. degenerate ones
+    desc["bodies"] = desc["bodies"] + [wl.mesh(fan_v, fan_t, (0.5, 0.5, 0.5), mul=rng.uniform(0.2, 1.0, 9))]
+    t = pxr.host_tables(desc)
+    s = orc.Scene(desc)
+    m = s.mesh()
+    assert (t["V"], t["T"]) == (s.V, s.T)
+    for k in ("uverts", "tris", "normals", "mul", "vert_body", "tri_body"):
+        assert np.array_equal(t[k], m[k]), k
+    tris, quads, pt = t["tris"], t["pair_quads"], t["pair_tris"]
+    seen = np.concatenate([pt[:, 0], pt[pt[:, 1] != 0xFFFF, 1]])
+    assert np.array_equal(np.sort(seen), np.arange(t["T"]))
+    for (q0, q1, q2, q3), (ta, tb) in zip(quads, pt):
+        assert set(tris[ta]) <= {q0, q1, q2}
+        if tb != 0xFFFF:
+            assert set(tris[ta]) == {q0, q1, q2} and set(tris[tb]) == {q0, q2, q3}
+            assert t["tri_body"][ta] == t["tri_body"][tb]
+    mesh_tris = t["tri_body"] >= 1
+    assert (pt[:, 1] != 0xFFFF).sum() * 2 >= 0.9 * mesh_tris.sum()
+
+
+def test_mesh_validation():
+    base = wl.cfg_mesh(B=1)["desc"]
+    tv, tt = wl.torus_mesh()
+    bad_idx = tt.copy()
+    bad_idx[5, 1] = len(tv)
+    _expect(dict(base, bodies=[wl.mesh(tv, bad_idx, (0.5,) * 3)]), pxr.ERR_INVALID_ARG)
+    bad_v = tv.copy()
+    bad_v[3, 2] = np.nan
+    _expect(dict(base, bodies=[wl.mesh(bad_v, tt, (0.5,) * 3)]), pxr.ERR_INVALID_ARG)
+    _expect(dict(base, bodies=[wl.mesh(tv, tt, (0.5,) * 3, mul=np.full(len(tt), np.inf))]), pxr.ERR_INVALID_ARG)
+    _expect(dict(base, bodies=[dict(wl.mesh(tv, tt, (0.5,) * 3), verts=None, tris=None)]), pxr.ERR_INVALID_ARG)
+    big_v, big_t = wl.torus_mesh(0.3, 0.1, 300, 120)  # 36 000 vertices, 72 000 triangles
+    _expect(dict(base, bodies=[wl.mesh(big_v, big_t, (0.5,) * 3)]), pxr.ERR_UNSUPPORTED)
+
+
 def _expect(desc, code):
     with pytest.raises(pxr.PxrError) as ei:
         pxr.host_tables(desc)
