@@ -285,8 +285,11 @@ void body_transforms(const orc_scene* s, const float* poses, FrameXform& fx) {
     }
 }
 
+// rej[v]: 0 = projected and snapped; 2 = behind the near plane (pv.z < z_near): its triangles are clipped;
+// 1 = unusable (outside the guard band, or a non-finite depth): its triangles are dropped.
+// PV (optional) receives the view-space position of every vertex.
 void vertex_stage(const orc_scene* s, const float* poses, const float* shapes, FrameXform& fx,
-                  int32_t* X, int32_t* Y, float* D, uint8_t* rej) {
+                  int32_t* X, int32_t* Y, float* D, uint8_t* rej, float* PV = nullptr) {
     body_transforms(s, poses, fx);
     const uint32_t V = (uint32_t)s->vbody.size();
     for (uint32_t v = 0; v < V; ++v) {
@@ -305,6 +308,7 @@ void vertex_stage(const orc_scene* s, const float* poses, const float* shapes, F
         float sx = std::fmaf(s->f, pv[0] * inv, s->halfW);
         float sy = std::fmaf(-s->f, pv[1] * inv, s->halfH);
         bool ok = (pv[2] >= s->z_near) && (std::fabs(sx) <= 16384.0f) && (std::fabs(sy) <= 16384.0f);
+        if (PV) for (int r = 0; r < 3; ++r) PV[(size_t)v * 3 + r] = pv[r];
         if (ok) {
             X[v] = (int32_t)std::floor(std::fmaf(sx, 256.0f, 0.5f));
             Y[v] = (int32_t)std::floor(std::fmaf(sy, 256.0f, 0.5f));
@@ -314,7 +318,7 @@ void vertex_stage(const orc_scene* s, const float* poses, const float* shapes, F
             X[v] = 0;
             Y[v] = 0;
             D[v] = 0.0f;
-            rej[v] = 1;
+            rej[v] = (pv[2] < s->z_near) ? 2 : 1;
         }
     }
 }
@@ -359,7 +363,7 @@ void raster_triangle(uint32_t W, uint32_t H, const int32_t* X, const int32_t* Y,
                      const uint8_t* rej, const uint32_t* tri, uint32_t g, uint32_t cull, ZBuf* zb,
                      uint32_t* cover) {
     uint32_t v0 = tri[0], v1 = tri[1], v2 = tri[2];
-    if (rej[v0] || rej[v1] || rej[v2]) return;  // no clipping: dropped whole
+    if (rej[v0] || rej[v1] || rej[v2]) return;  // an unusable corner (or, for a bare soup, one behind the near plane)
     // screen order: swapping two vertices turns world-CCW front faces into
     // positive orientation in the y-down raster frame
     uint32_t ia = v0, ib = v2, ic = v1;
@@ -399,6 +403,62 @@ void raster_triangle(uint32_t W, uint32_t H, const int32_t* X, const int32_t* Y,
                 zb->test(pix, dp, g);
             }
         }
+}
+
+// Near-plane clipping of one triangle whose vertices are partly behind z_near (view space).
+// Walk the edges v0->v1, v1->v2, v2->v0 (Sutherland-Hodgman against the single plane z = z_near): a
+// vertex in front is kept; an edge that crosses the plane adds its intersection, always computed from
+// the endpoint in front (P) towards the one behind (Q), so two triangles sharing the edge get the same
+// point:  t = (z_near - P.z) / (Q.z - P.z),  I = (fma(t, Q.x - P.x, P.x), fma(t, Q.y - P.y, P.y), z_near).
+// The 3 or 4 resulting corners w0.. keep the winding; they are projected and snapped exactly like
+// template vertices (a corner outside the guard band is unusable) and rastered as (w0,w1,w2) and
+// (w0,w2,w3) under the parent's id by the ordinary rule.
+void clip_and_raster(const orc_scene* s, const float* PV, const int32_t* X, const int32_t* Y, const float* D,
+                     const uint8_t* rej, const uint32_t* tri, uint32_t g, ZBuf* zb) {
+    float wx[4], wy[4], wz[4];
+    int from_vertex[4];  // index 0..2 of the original corner, or -1 for an intersection
+    int n = 0;
+    for (int e = 0; e < 3; ++e) {
+        const uint32_t vs = tri[e], ve = tri[(e + 1) % 3];
+        const bool s_in = rej[vs] != 2, e_in = rej[ve] != 2;
+        if (s_in) {
+            from_vertex[n] = e;
+            wx[n] = wy[n] = wz[n] = 0.0f;
+            ++n;
+        }
+        if (s_in != e_in) {
+            const float* P = PV + (size_t)(s_in ? vs : ve) * 3;
+            const float* Q = PV + (size_t)(s_in ? ve : vs) * 3;
+            const float t = (s->z_near - P[2]) / (Q[2] - P[2]);
+            from_vertex[n] = -1;
+            wx[n] = std::fmaf(t, Q[0] - P[0], P[0]);
+            wy[n] = std::fmaf(t, Q[1] - P[1], P[1]);
+            wz[n] = s->z_near;
+            ++n;
+        }
+    }
+    if (n < 3) return;  // nothing in front
+    int32_t cX[4], cY[4];
+    float cD[4];
+    uint8_t cr[4];
+    for (int k = 0; k < n; ++k) {
+        if (from_vertex[k] >= 0) {
+            const uint32_t v = tri[from_vertex[k]];
+            cX[k] = X[v]; cY[k] = Y[v]; cD[k] = D[v]; cr[k] = rej[v];
+            continue;
+        }
+        const float inv = 1.0f / wz[k];
+        const float sx = std::fmaf(s->f, wx[k] * inv, s->halfW);
+        const float sy = std::fmaf(-s->f, wy[k] * inv, s->halfH);
+        const bool ok = (std::fabs(sx) <= 16384.0f) && (std::fabs(sy) <= 16384.0f);
+        cr[k] = ok ? 0 : 1;
+        cX[k] = ok ? (int32_t)std::floor(std::fmaf(sx, 256.0f, 0.5f)) : 0;
+        cY[k] = ok ? (int32_t)std::floor(std::fmaf(sy, 256.0f, 0.5f)) : 0;
+        cD[k] = s->z_near * inv;
+    }
+    const uint32_t first[3] = {0, 1, 2}, second[3] = {0, 2, 3};
+    raster_triangle(s->W, s->H, cX, cY, cD, cr, first, g, 0, zb, nullptr);
+    if (n == 4) raster_triangle(s->W, s->H, cX, cY, cD, cr, second, g, 0, zb, nullptr);
 }
 
 // ---------------------------------------------------------------- X: generator
@@ -581,6 +641,7 @@ int orc_render(const orc_scene* s, const float* poses, const float* shapes, uint
     std::vector<int32_t> X(V), Y(V);
     std::vector<float> D(V);
     std::vector<uint8_t> rej(V);
+    std::vector<float> PV((size_t)V * 3);
     FrameXform fx;
     ZBuf zb;
     for (uint32_t e = 0; e < B; ++e) {
@@ -591,12 +652,17 @@ int orc_render(const orc_scene* s, const float* poses, const float* shapes, uint
             const size_t frame = (size_t)e * S + st;
             const float* pose = poses + frame * K * 7;
             // V
-            vertex_stage(s, pose, shp, fx, X.data(), Y.data(), D.data(), rej.data());
-            // R
+            vertex_stage(s, pose, shp, fx, X.data(), Y.data(), D.data(), rej.data(), PV.data());
+            // R (triangles reaching behind the near plane are clipped first)
             zb.reset(npix);
             for (uint32_t k = 0; k < T; ++k) {
                 uint32_t g = order ? order[k] : k;
-                raster_triangle(W, H, X.data(), Y.data(), D.data(), rej.data(), &s->tri[(size_t)g * 3], g, 0, &zb, nullptr);
+                const uint32_t* tri = &s->tri[(size_t)g * 3];
+                const uint8_t r0 = rej[tri[0]], r1 = rej[tri[1]], r2 = rej[tri[2]];
+                if (r0 != 1 && r1 != 1 && r2 != 1 && (r0 | r1 | r2) == 2)
+                    clip_and_raster(s, PV.data(), X.data(), Y.data(), D.data(), rej.data(), tri, g, &zb);
+                else
+                    raster_triangle(W, H, X.data(), Y.data(), D.data(), rej.data(), tri, g, 0, &zb, nullptr);
             }
             // X: per-frame draws
             float scale[3] = {1.0f, 1.0f, 1.0f}, offs[3] = {0.0f, 0.0f, 0.0f};

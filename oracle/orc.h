@@ -92,8 +92,10 @@ void orc_scene_camera(const orc_scene* s, float* Rv, float* f, float* cx, float*
 
 /* Vertex stage for ONE frame: poses[K*7] = (px,py,pz,qw,qx,qy,qz) per body,
  * shapes[K*4] or NULL (scene shapes).  Writes snapped X[V], Y[V] (8 sub-pixel
- * bits), reversed depth D[V] and rejected[V] (1 = fails the near/guard test;
- * X,Y,D are then 0).  eye[3] (may be NULL) receives the camera position. */
+ * bits), reversed depth D[V] and rejected[V] (0 = usable; 2 = behind the near
+ * plane, its triangles are clipped by orc_render; 1 = outside the guard band or
+ * non-finite, its triangles are dropped; X,Y,D are 0 unless usable).  eye[3]
+ * (may be NULL) receives the camera position. */
 void orc_vertex_stage(const orc_scene* s, const float* poses, const float* shapes,
                       int32_t* X, int32_t* Y, float* D, uint8_t* rejected, float* eye);
 
@@ -125,7 +127,11 @@ typedef struct {
 /* Full path: poses[B,S,K,7], shapes[B,K,4] or NULL, frames[B,S,H,W,3] out,
  * ids[B,S,H,W] out or NULL, depth_bits[B,S,H,W] out or NULL.  env0 is the
  * global index of the first environment (the generator is keyed by global
- * environment index).  order = optional triangle submission order. */
+ * environment index).  order = optional triangle submission order.
+ * A triangle with corners on both sides of the near plane is clipped against it in view space (corners in
+ * front kept, crossing edges cut from the corner in front towards the one behind, 3 or 4 corners
+ * re-projected, snapped and rastered as one or two triangles under the same id); orc_raster, which sees only
+ * snapped coordinates, drops such triangles. */
 int orc_render(const orc_scene* s, const float* poses, const float* shapes, uint32_t B, uint32_t S,
                uint32_t step0, uint32_t env0, const orc_distractor* dis, const uint32_t* order,
                uint8_t* frames, uint32_t* ids, uint32_t* depth_bits);
