@@ -11,9 +11,12 @@
 
 namespace pxr {
 
-// Sentinel stored in the snapped-X array for a vertex that failed the
-// near-plane / guard-band test; any triangle touching it is dropped.
+// Sentinel stored in the snapped-X array for a vertex that is unusable (outside the
+// guard band, or a non-finite depth); any triangle touching it is dropped.
 constexpr int32_t kRejectedX = INT32_MIN;
+// Sentinel for a vertex behind the near plane: its triangles are clipped against the plane in the
+// raster phase.  (Snapped coordinates stay within +-2^22, so both sentinels sort below every real one.)
+constexpr int32_t kBehindX = INT32_MIN + 1;
 
 // Raster bins by the number of pixel centres in a surviving triangle's clamped
 // bounding box (both fixed-point extents must also be below 2^15):

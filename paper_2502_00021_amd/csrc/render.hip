@@ -151,10 +151,12 @@ __device__ __forceinline__ void raster_rows(const TriSetup& s, uint32_t tri, uin
 }
 
 // Gather a triangle's snapped vertices and its clamped pixel-centre range.
-// Returns false if a vertex was rejected or no pixel centre is inside the
-// bounding box.  `small_extent` = both fixed-point extents below 2^15.
-__device__ __forceinline__ bool tri_gather(const SceneConsts& sc, uint32_t t, const int* vx, const int* vy, TriSetup& s,
-                                           uint32_t& v0, uint32_t& v1, uint32_t& v2, bool& small_extent) {
+// Returns kTriNone if a vertex is unusable, all of them lie behind the near plane or no pixel centre is
+// inside the bounding box; kTriClip if the triangle straddles the near plane (nothing else is valid
+// then); kTriPlain otherwise.  `small_extent` = both fixed-point extents below 2^15.
+enum { kTriNone = 0, kTriPlain = 1, kTriClip = 2 };
+__device__ __forceinline__ int tri_gather(const SceneConsts& sc, uint32_t t, const int* vx, const int* vy, TriSetup& s,
+                                          uint32_t& v0, uint32_t& v1, uint32_t& v2, bool& small_extent) {
     const uint2 ti = reinterpret_cast<const uint2*>(sc.tri_idx)[t];
     v0 = ti.x & 0xFFFFu;
     v1 = ti.x >> 16;
@@ -162,11 +164,14 @@ __device__ __forceinline__ bool tri_gather(const SceneConsts& sc, uint32_t t, co
     s.ax = vx[v0];
     s.bx = vx[v2];
     s.cx = vx[v1];
-    if (s.ax == kRejectedX || s.bx == kRejectedX || s.cx == kRejectedX) return false;
+    const int minx = imin3(s.ax, s.bx, s.cx), maxx = imax3(s.ax, s.bx, s.cx);
+    if (minx <= kBehindX) {  // a sentinel among the three (rare)
+        if (minx == kRejectedX) return kTriNone;
+        return maxx == kBehindX ? kTriNone : kTriClip;
+    }
     s.ay = vy[v0];
     s.by = vy[v2];
     s.cy = vy[v1];
-    const int minx = imin3(s.ax, s.bx, s.cx), maxx = imax3(s.ax, s.bx, s.cx);
     const int miny = imin3(s.ay, s.by, s.cy), maxy = imax3(s.ay, s.by, s.cy);
     // pixel centres sit at 256 i + 128: first centre >= min, last centre <= max
     s.i0 = max(0, (minx + 127) >> 8);
@@ -174,17 +179,126 @@ __device__ __forceinline__ bool tri_gather(const SceneConsts& sc, uint32_t t, co
     s.j0 = max(0, (miny + 127) >> 8);
     s.j1 = min((int)sc.H - 1, (maxy - 128) >> 8);
     small_extent = ((maxx - minx) | (maxy - miny)) < 32768;
-    return s.i0 <= s.i1 && s.j0 <= s.j1;
+    return (s.i0 <= s.i1 && s.j0 <= s.j1) ? kTriPlain : kTriNone;
+}
+
+// View-space position of template vertex v (the instancing arithmetic of phase 1; also used when a
+// triangle has to be clipped).  Returns the body record the vertex belongs to.
+__device__ __forceinline__ void view_position(const SceneConsts& sc, const float* body, uint32_t v, float& pvx, float& pvy,
+                                              float& pvz) {
+    const float4 tv = reinterpret_cast<const float4*>(sc.vtmpl)[v];
+    const uint32_t code = __float_as_uint(tv.w);
+    const float* o = body + __umul24(code >> 2, kBodyStride);
+    const float sel = (float)((int)(code & 3u) - 1);
+    const float lx = o[16] * tv.x;
+    const float ly = o[17] * tv.y;
+    const float lz = __builtin_fmaf(o[18], tv.z, sel * o[19]);
+    pvx = __builtin_fmaf(o[0], lx, __builtin_fmaf(o[1], ly, __builtin_fmaf(o[2], lz, o[9])));
+    pvy = __builtin_fmaf(o[3], lx, __builtin_fmaf(o[4], ly, __builtin_fmaf(o[5], lz, o[10])));
+    pvz = __builtin_fmaf(o[6], lx, __builtin_fmaf(o[7], ly, __builtin_fmaf(o[8], lz, o[11])));
+}
+
+// One piece (a, b, c in screen order) of a clipped triangle, rastered by a whole wavefront.
+__device__ __forceinline__ void raster_piece(const SceneConsts& sc, uint32_t t, int ax, int ay, float Da, int bx, int by,
+                                             float Db, int cx, int cy, float Dc, bool usable, u64* keys, int lane,
+                                             int row_lo, int row_hi) {
+    if (!usable) return;
+    if (!((long long)(bx - ax) * (long long)(cy - ay) > (long long)(by - ay) * (long long)(cx - ax))) return;  // back face
+    TriSetup s;
+    s.ax = ax; s.ay = ay; s.bx = bx; s.by = by; s.cx = cx; s.cy = cy;
+    const int minx = imin3(ax, bx, cx), maxx = imax3(ax, bx, cx), miny = imin3(ay, by, cy), maxy = imax3(ay, by, cy);
+    s.i0 = max(0, (minx + 127) >> 8);
+    s.i1 = min((int)sc.W - 1, (maxx - 128) >> 8);
+    s.j0 = max(max(0, (miny + 127) >> 8), row_lo);
+    s.j1 = min(min((int)sc.H - 1, (maxy - 128) >> 8), row_hi - 1);
+    if (s.i0 > s.i1 || s.j0 > s.j1) return;
+    s.Da = Da;
+    s.dDb = Db - Da;
+    s.dDc = Dc - Da;
+    if (((maxx - minx) | (maxy - miny)) < 32768)
+        raster_rows<int>(s, t, sc.W, keys, lane, 6, row_lo);
+    else
+        raster_rows<long long>(s, t, sc.W, keys, lane, 6, row_lo);
+}
+
+// A triangle with corners on both sides of the near plane (every lane of the wavefront computes the
+// same clip).  Walk the edges v0->v1, v1->v2, v2->v0: a corner in front is kept, an edge that crosses
+// the plane adds its intersection, computed from the corner in front (P) towards the one behind (Q) so
+// that both triangles sharing the edge get the same point:
+//   t = (z_near - P.z) / (Q.z - P.z),  I = (fma(t, Q.x - P.x, P.x), fma(t, Q.y - P.y, P.y), z_near).
+// The 3 or 4 corners w0.. keep the winding; new ones are projected and snapped like template vertices
+// (outside the guard band = unusable) and the pieces (w0,w1,w2), (w0,w2,w3) are rastered under id t.
+//
+// Which corner the walk emits k-th depends only on which of the three vertices are in front: a 4-bit
+// code per corner (P << 2 | Q, P == Q for a kept vertex), four corners per pattern, patterns indexed by
+// the in-front mask (bit e = vertex e in front).  Corners are recomputed per piece rather than kept, so
+// that this rarely taken path does not raise the kernel's register count.
+__device__ __forceinline__ void raster_clipped(const SceneConsts& sc, uint32_t t, const float* body, const int* vx, const int* vy,
+                                               const float* vd, u64* keys, int lane, int row_lo, int row_hi) {
+#pragma unroll 1
+    for (uint32_t piece = 0; piece < 2u; ++piece) {
+        // everything is re-derived per piece so that nothing but `t` stays live across the raster loops
+        const uint2 ti = reinterpret_cast<const uint2*>(sc.tri_idx)[t];
+        const uint32_t v0 = ti.x & 0xFFFFu, v1 = ti.x >> 16, v2 = ti.y & 0xFFFFu;
+        const uint32_t mask = (vx[v0] != kBehindX ? 1u : 0u) | (vx[v1] != kBehindX ? 2u : 0u) | (vx[v2] != kBehindX ? 4u : 0u);
+        // corners k = 0..3 in bits 4k..4k+3; V_e = e<<2|e, I_pq = p<<2|q
+        //   001: V0 I01 I02      010: I10 V1 I12      100: I21 V2 I20
+        //   011: V0 V1 I12 I02   110: I10 V1 V2 I20   101: V0 I01 I21 V2
+        const uint32_t pattern = mask == 1u ? 0x0210u : mask == 2u ? 0x0654u : mask == 4u ? 0x08A9u
+                               : mask == 3u ? 0x2650u : mask == 6u ? 0x8A54u : 0xA910u;
+        if (piece == 1u && (mask == 1u || mask == 2u || mask == 4u)) break;  // one corner in front: one piece
+        const float inv = 1.0f / sc.z_near;
+        // screen order (a, b, c) = (w0, w2, w1), then (w0, w3, w2)
+        const uint32_t order = piece == 0 ? 0x120u : 0x230u;
+        int cX[3], cY[3];
+        float cD[3];
+        bool usable = true;
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            const uint32_t code = (pattern >> (4u * ((order >> (4 * c)) & 15u))) & 15u;
+            const uint32_t p = code >> 2, q = code & 3u;
+            const uint32_t vp = p == 0 ? v0 : (p == 1 ? v1 : v2), vq = q == 0 ? v0 : (q == 1 ? v1 : v2);
+            if (p == q) {
+                cX[c] = vx[vp];
+                cY[c] = vy[vp];
+                cD[c] = vd[vp];
+            } else {
+                float px, py, pz, qx, qy, qz;
+                view_position(sc, body, vp, px, py, pz);
+                __builtin_amdgcn_sched_barrier(0);  // one vertex at a time: keeps this path within the register budget
+                view_position(sc, body, vq, qx, qy, qz);
+                __builtin_amdgcn_sched_barrier(0);
+                const float tt = (sc.z_near - pz) / (qz - pz);
+                const float ix = __builtin_fmaf(tt, qx - px, px);
+                const float iy = __builtin_fmaf(tt, qy - py, py);
+                const float sx = __builtin_fmaf(sc.f, ix * inv, sc.halfW);
+                const float sy = __builtin_fmaf(-sc.f, iy * inv, sc.halfH);
+                const bool ok = (__builtin_fabsf(sx) <= 16384.0f) && (__builtin_fabsf(sy) <= 16384.0f);
+                usable = usable && ok;
+                cX[c] = ok ? (int)__builtin_floorf(__builtin_fmaf(sx, 256.0f, 0.5f)) : 0;
+                cY[c] = ok ? (int)__builtin_floorf(__builtin_fmaf(sy, 256.0f, 0.5f)) : 0;
+                cD[c] = sc.z_near * inv;
+            }
+        }
+        raster_piece(sc, t, cX[0], cY[0], cD[0], cX[1], cY[1], cD[1], cX[2], cY[2], cD[2], usable, keys, lane, row_lo, row_hi);
+    }
 }
 
 // Raster one binned triangle with lane `r` of the 2^shift lanes that share it, restricted to
 // the rows [row_lo, row_hi) that the key buffer currently holds.
-__device__ __forceinline__ void raster_binned(const SceneConsts& sc, uint32_t t, const int* vx, const int* vy,
-                                              const float* vd, u64* keys, int r, int shift, int row_lo, int row_hi) {
+// MAY_CLIP: the bin (the wave-per-triangle one) also holds the triangles that straddle the near plane.
+template <bool MAY_CLIP>
+__device__ __forceinline__ void raster_binned(const SceneConsts& sc, uint32_t t, const float* body, const int* vx,
+                                              const int* vy, const float* vd, u64* keys, int r, int shift, int row_lo,
+                                              int row_hi) {
     TriSetup s;
     uint32_t v0, v1, v2;
     bool small_extent;
-    tri_gather(sc, t, vx, vy, s, v0, v1, v2, small_extent);
+    const int kind = tri_gather(sc, t, vx, vy, s, v0, v1, v2, small_extent);
+    if (MAY_CLIP && kind == kTriClip) {
+        raster_clipped(sc, t, body, vx, vy, vd, keys, r, row_lo, row_hi);
+        return;
+    }
     s.j0 = max(s.j0, row_lo);
     s.j1 = min(s.j1, row_hi - 1);
     if (s.j0 > s.j1) return;
@@ -505,22 +619,14 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
 
     // ---- phase 1: instancing + projection + snap + cell code (one lane per template vertex)
     for (uint32_t v = tid; v < sc.V; v += NT) {
-        const float4 tv = reinterpret_cast<const float4*>(sc.vtmpl)[v];
-        const uint32_t code = __float_as_uint(tv.w);
-        const float* o = body + __umul24(code >> 2, kBodyStride);
-        const float sel = (float)((int)(code & 3u) - 1);
-        const float lx = o[16] * tv.x;
-        const float ly = o[17] * tv.y;
-        const float lz = __builtin_fmaf(o[18], tv.z, sel * o[19]);
-        const float pvx = __builtin_fmaf(o[0], lx, __builtin_fmaf(o[1], ly, __builtin_fmaf(o[2], lz, o[9])));
-        const float pvy = __builtin_fmaf(o[3], lx, __builtin_fmaf(o[4], ly, __builtin_fmaf(o[5], lz, o[10])));
-        const float pvz = __builtin_fmaf(o[6], lx, __builtin_fmaf(o[7], ly, __builtin_fmaf(o[8], lz, o[11])));
+        float pvx, pvy, pvz;
+        view_position(sc, body, v, pvx, pvy, pvz);
         const float inv = 1.0f / pvz;
         const float sx = __builtin_fmaf(sc.f, pvx * inv, sc.halfW);
         const float sy = __builtin_fmaf(-sc.f, pvy * inv, sc.halfH);
         const bool ok = (pvz >= sc.z_near) && (__builtin_fabsf(sx) <= 16384.0f) && (__builtin_fabsf(sy) <= 16384.0f);
-        int X = kRejectedX, Y = 0;
-        uint32_t m = 0xFFFFFFFFu;  // a rejected vertex never lets a triangle be discarded early
+        int X = pvz < sc.z_near ? kBehindX : kRejectedX, Y = 0;
+        uint32_t m = 0xFFFFFFFFu;  // an unusable or clipped vertex never lets a triangle be discarded early
         if (ok) {
             X = (int)__builtin_floorf(__builtin_fmaf(sx, 256.0f, 0.5f));
             Y = (int)__builtin_floorf(__builtin_fmaf(sy, 256.0f, 0.5f));
@@ -577,7 +683,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
             TriSetup s;
             uint32_t v0, v1, v2;
             bool small_extent;
-            if (tri_gather(sc, t, vx, vy, s, v0, v1, v2, small_extent)) {
+            const int kind = tri_gather(sc, t, vx, vy, s, v0, v1, v2, small_extent);
+            if (kind == kTriClip) cls = 4;  // clipped, then rastered, by a whole wavefront
+            if (kind == kTriPlain) {
                 bool front;
                 if (small_extent)
                     front = __mul24(s.bx - s.ax, s.cy - s.ay) > __mul24(s.by - s.ay, s.cx - s.ax);
@@ -626,15 +734,16 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         const uint32_t n_tiny = (uint32_t)bins & 0xFFFFu, n_small = ((uint32_t)bins >> 16);
         const uint32_t n_mid = (uint32_t)(bins >> 32) & 0xFFFFu, n_large = (uint32_t)(bins >> 48);
 
-        for (uint32_t k = tid; k < n_tiny; k += NT) raster_binned(sc, list[k], vx, vy, vd, keys, 0, 0, (int)row_lo, (int)row_hi);
+        for (uint32_t k = tid; k < n_tiny; k += NT)
+            raster_binned<false>(sc, list[k], body, vx, vy, vd, keys, 0, 0, (int)row_lo, (int)row_hi);
         for (uint32_t k = NT - 1 - tid; k < n_small; k += NT)
-            raster_binned(sc, list[sc.T - 1 - k], vx, vy, vd, keys, 0, 0, (int)row_lo, (int)row_hi);
+            raster_binned<false>(sc, list[sc.T - 1 - k], body, vx, vy, vd, keys, 0, 0, (int)row_lo, (int)row_hi);
         // mid: 8 lanes per triangle, starting in the middle waves
         for (uint32_t k = ((tid >> 3) + NT / 16) % (NT / 8); k < n_mid; k += NT / 8)
-            raster_binned(sc, list2[k], vx, vy, vd, keys, (int)(tid & 7u), 3, (int)row_lo, (int)row_hi);
+            raster_binned<false>(sc, list2[k], body, vx, vy, vd, keys, (int)(tid & 7u), 3, (int)row_lo, (int)row_hi);
         // large: a whole wave per triangle
         for (uint32_t k = ((tid >> 6) + NT / 128) % (NT / 64); k < n_large; k += NT / 64)
-            raster_binned(sc, list2[sc.T - 1 - k], vx, vy, vd, keys, (int)lane, 6, (int)row_lo, (int)row_hi);
+            raster_binned<true>(sc, list2[sc.T - 1 - k], body, vx, vy, vd, keys, (int)lane, 6, (int)row_lo, (int)row_hi);
         __syncthreads();
         PXR_PHASE_MARK(5);
 

@@ -216,6 +216,73 @@ def test_mesh_close_up_and_degenerate_triangles(torch, pxr, orc):
     assert_parity(gpu_render(torch, pxr, w), ref)
 
 
+# ---------------------------------------------------------------- near-plane clipping
+
+def _clip_scenes():
+    RGB = (0.6, 0.4, 0.8)
+    rng = np.random.default_rng(41)
+    out = []
+    # a terrain grid running under and behind the camera, 1 and 2 corners in front, several yaws
+    hv, ht, hm = wl.heightfield_mesh(rng, 5, 9.0, 0.25)
+    d = wl.default_scene(72, 56, [wl.sphere(0.05, RGB, 6, 2), wl.mesh(hv, ht, (0.7, 0.6, 0.4), mul=hm)])
+    d["cam_offset"] = (-1.0, 0.0, 0.5)
+    B = 12
+    poses = np.zeros((B, 1, 2, 7), np.float32)
+    poses[:, 0, 0] = (0, 0, 1, 1, 0, 0, 0)
+    poses[:, 0, 1, :3] = np.array([-1.0, 0.0, 0.85]) + rng.uniform(-0.3, 0.3, (B, 3)) * np.array([1, 1, 0.2])
+    poses[:, 0, 1, 3:] = wl.q_axis_angle(wl.EZ, rng.uniform(0, 2 * np.pi, B))
+    out.append(dict(desc=d, poses=poses, shapes=None, distractor=None))
+    # a long capsule and a big box passing the camera; colour distractor; tumbling
+    bodies = [wl.sphere(0.05, RGB, 6, 2), wl.capsule(0.3, 3.0, (0.8, 0.3, 0.3), 10, 3), wl.box(0.8, 0.6, 0.4, (0.3, 0.5, 0.8), 3)]
+    d = wl.default_scene(64, 64, bodies)
+    d["cam_offset"] = (-1.5, 0.0, 0.4)
+    B = 16
+    poses = np.zeros((B, 1, 3, 7), np.float32)
+    poses[:, 0, 0] = (0, 0, 1, 1, 0, 0, 0)
+    poses[:, 0, 1, :3] = np.array([-1.0, 0.2, 1.1]) + rng.uniform(-0.4, 0.4, (B, 3))
+    poses[:, 0, 1, 3:] = wl.random_quats(rng, (B,))
+    poses[:, 0, 2, :3] = np.array([-1.2, -0.6, 1.2]) + rng.uniform(-0.4, 0.4, (B, 3))
+    poses[:, 0, 2, 3:] = wl.random_quats(rng, (B,))
+    out.append(dict(desc=d, poses=poses, shapes=None,
+                    distractor=dict(mode="color", seed=3, scale=(0.5, 1.5), offset=(-0.2, 0.2))))
+    # the camera inside a huge sphere and next to a huge box (everything visible is clipped or enormous)
+    bodies = [wl.sphere(0.05, RGB, 6, 2), wl.sphere(3.0, (0.5, 0.7, 0.5), 12, 5), wl.box(2.0, 2.0, 0.05, (0.7, 0.7, 0.3), 4)]
+    d = wl.default_scene(48, 40, bodies)
+    d["cam_offset"] = (-0.8, 0.0, 0.3)
+    B = 10
+    poses = np.zeros((B, 1, 3, 7), np.float32)
+    poses[:, 0, 0] = (0, 0, 1, 1, 0, 0, 0)
+    poses[:, 0, 1, :3] = np.array([2.0, 0.0, 1.0]) + rng.uniform(-0.5, 0.5, (B, 3))
+    poses[:, 0, 1, 3:] = wl.random_quats(rng, (B,))
+    poses[:, 0, 2, :3] = np.array([-0.5, 0.0, 1.0]) + rng.uniform(-0.3, 0.3, (B, 3))
+    poses[:, 0, 2, 3:] = wl.random_quats(rng, (B,))
+    out.append(dict(desc=d, poses=poses, shapes=None, distractor=None))
+    return out
+
+
+@pytest.mark.parametrize("which", [0, 1, 2])
+def test_triangles_crossing_the_near_plane_are_clipped(torch, pxr, orc, which):
+    w = _clip_scenes()[which]
+    o = orc.Scene(w["desc"])
+    tris = o.mesh()["tris"]
+    n_straddling = 0
+    for e in range(w["poses"].shape[0]):
+        behind = o.vertex_stage(w["poses"][e, 0])["rejected"] == 2
+        n_straddling += int((behind[tris].any(axis=1) & ~behind[tris].all(axis=1)).sum())
+    assert n_straddling > 20 * w["poses"].shape[0] // 4
+    ref = oracle_render(orc, w, step0=1)
+    assert (ref["ids"] < GROUND).mean() > 0.15
+    for threads in (None, 256, 1024):
+        assert_parity(gpu_render(torch, pxr, w, step0=1, threads=threads), ref)
+
+
+def test_clipping_in_banded_frames(torch, pxr, orc):
+    w = _clip_scenes()[1]
+    w["desc"]["width"], w["desc"]["height"] = 260, 200
+    w = dict(w, poses=w["poses"][:4])
+    assert_parity(gpu_render(torch, pxr, w), oracle_render(orc, w))
+
+
 # ---------------------------------------------------------------- large triangles, clipping, rejects
 
 def _close_up(W=64, H=64, offset=(-0.9, 0.1, 0.35)):
