@@ -390,33 +390,35 @@ __device__ __forceinline__ u64 ground_key(const SceneConsts& sc, const ResolveCt
 // -> 24-bit RGB.  `low` returns ~id.  `vbytes` = the pixel's three video bytes
 // (R | G<<8 | B<<16), only read in video mode.
 // UNIT_CELL: the checkerboard cell is 1 m, so the division by the cell size is the identity.
-template <bool UNIT_CELL>
+// Triangle g as a 24-bit colour: flat Lambert + ambient in the body frame, then the colour distractor.
+__device__ __forceinline__ uint32_t shade_triangle(const SceneConsts& sc, const ResolveCtx& rc, const float* body, uint32_t g) {
+    const float4 ns = reinterpret_cast<const float4*>(sc.tri_shade)[g];
+    const float* o = body + (sc.tri_idx[g * 2 + 1] >> 16) * kBodyStride;
+    float I = __builtin_fmaf(ns.x, o[12], __builtin_fmaf(ns.y, o[13], ns.z * o[14]));
+    I = I > 0.0f ? I : 0.0f;
+    const float sh = __builtin_fmaf(sc.diffuse, I, sc.ambient);
+    uint32_t rgb = 0;
+#pragma unroll
+    for (int ch = 0; ch < 3; ++ch) {
+        float v = (o[20 + ch] * ns.w) * sh;
+        v = v < 1.0f ? v : 1.0f;
+        if (rc.mode == PXR_DISTRACT_COLOR) {
+            v = __builtin_fmaf(v, rc.scale[ch], rc.offs[ch]);
+            v = v > 0.0f ? v : 0.0f;
+            v = v < 1.0f ? v : 1.0f;
+        }
+        rgb |= quantise(v) << (8 * ch);
+    }
+    return rgb;
+}
+
+// DEFER_TRIANGLES: a triangle pixel returns 0 here; the caller shades it (compacted over the wavefront).
+template <bool UNIT_CELL, bool DEFER_TRIANGLES = false>
 __device__ __forceinline__ uint32_t resolve_pixel(const SceneConsts& sc, const ResolveCtx& rc, const float* body, u64 key,
                                                   u64 gkey, float tg, float dwx, float dwy, uint32_t vbytes, uint32_t& low) {
     key = key > gkey ? key : gkey;
     low = (uint32_t)key;
-    if (low > 1u) {
-        // a triangle: flat Lambert + ambient in the body frame
-        const uint32_t g = 0xFFFFFFFFu - low;
-        const float4 ns = reinterpret_cast<const float4*>(sc.tri_shade)[g];
-        const float* o = body + (sc.tri_idx[g * 2 + 1] >> 16) * kBodyStride;
-        float I = __builtin_fmaf(ns.x, o[12], __builtin_fmaf(ns.y, o[13], ns.z * o[14]));
-        I = I > 0.0f ? I : 0.0f;
-        const float sh = __builtin_fmaf(sc.diffuse, I, sc.ambient);
-        uint32_t rgb = 0;
-#pragma unroll
-        for (int ch = 0; ch < 3; ++ch) {
-            float v = (o[20 + ch] * ns.w) * sh;
-            v = v < 1.0f ? v : 1.0f;
-            if (rc.mode == PXR_DISTRACT_COLOR) {
-                v = __builtin_fmaf(v, rc.scale[ch], rc.offs[ch]);
-                v = v > 0.0f ? v : 0.0f;
-                v = v < 1.0f ? v : 1.0f;
-            }
-            rgb |= quantise(v) << (8 * ch);
-        }
-        return rgb;
-    }
+    if (low > 1u) return DEFER_TRIANGLES ? 0u : shade_triangle(sc, rc, body, 0xFFFFFFFFu - low);
     // background or ground: one of three colours per frame
     int cls = 0;
     if (low == 1u) {
@@ -442,9 +444,10 @@ __device__ __forceinline__ uint32_t resolve_pixel(const SceneConsts& sc, const R
 // horizontal) so is the whole ground test, which then costs one division per lane, not four.
 template <int NT, bool UNIT_CELL, bool NO_ROLL>
 __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const ResolveCtx& rc, const float* body,
-                                              const float* cxcy, const u64* keys, uint8_t* out, uint32_t* out_ids,
+                                              const float* cxcy, u64* keys, uint8_t* out, uint32_t* out_ids,
                                               uint32_t tid, uint32_t p_begin, uint32_t p_end) {
     // pixels [p_begin, p_end) of the frame; keys[0] belongs to pixel p_begin
+    const uint32_t lane = tid & 63u;
     for (uint32_t q = (p_begin >> 2) + tid; q * 4 < p_end; q += NT) {
         const uint32_t p0 = q * 4;
         const uint32_t j = __umulhi(p0, sc.magicW);
@@ -475,7 +478,32 @@ __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const Resol
             if (!NO_ROLL) gkey = ground_key(sc, rc, -__builtin_fmaf(sc.Rt[2], cxs[k], rz), tg);
             const float dwx = __builtin_fmaf(sc.Rt[0], cxs[k], rx);
             const float dwy = __builtin_fmaf(sc.Rt[1], cxs[k], ry);
-            rgb[k] = resolve_pixel<UNIT_CELL>(sc, rc, body, keys[p0 - p_begin + k], gkey, tg, dwx, dwy, vb[k], low[k]);
+            rgb[k] = resolve_pixel<UNIT_CELL, true>(sc, rc, body, keys[p0 - p_begin + k], gkey, tg, dwx, dwy, vb[k], low[k]);
+        }
+        // Triangle pixels are few and clustered: instead of every lane walking the shading code four
+        // times, the wavefront compacts its triangle pixels into a list (in the LDS of its own, already
+        // consumed, pixel keys), shades the list densely, and the owners pick their colours up.
+        const u64 m0 = __ballot(low[0] > 1u), m1 = __ballot(low[1] > 1u), m2 = __ballot(low[2] > 1u), m3 = __ballot(low[3] > 1u);
+        if (m0 | m1 | m2 | m3) {
+            uint32_t* list = reinterpret_cast<uint32_t*>(keys + ((q - lane) * 4 - p_begin));  // 256 keys = 512 words
+            const uint32_t n0 = (uint32_t)__popcll(m0), n1 = n0 + (uint32_t)__popcll(m1), n2 = n1 + (uint32_t)__popcll(m2);
+            const uint32_t total = n2 + (uint32_t)__popcll(m3);
+            const uint32_t slot[4] = {lanes_below(m0), n0 + lanes_below(m1), n1 + lanes_below(m2), n2 + lanes_below(m3)};
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (low[k] > 1u) list[slot[k]] = low[k];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            const u64 active = __ballot(true);  // the last trip of a ragged band may run with fewer lanes
+            for (uint32_t i = lanes_below(active); i < total; i += (uint32_t)__popcll(active))
+                list[i] = shade_triangle(sc, rc, body, 0xFFFFFFFFu - list[i]);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if (low[k] > 1u) rgb[k] = list[slot[k]];
         }
         struct alignas(4) U3 {
             uint32_t a, b, c;
