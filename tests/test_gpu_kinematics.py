@@ -92,6 +92,28 @@ def test_free_only_and_rigid_only_skeletons(torch, pxr, orc):
     sc.close()
 
 
+def test_sixty_four_link_chain(torch, pxr, orc):
+    """The body-count limit as one chain of depth 63 (rounding accumulates identically on both sides)."""
+    rng = np.random.default_rng(66)
+    K = 64
+    bodies = [wl.capsule(0.03, 0.05, rng.uniform(0.2, 0.9, 3), 4, 1) for _ in range(K)]
+    skel = wl._skeleton(K)
+    skel["slot"][0] = 0
+    for k in range(1, K):
+        ax = wl.q_normalize(rng.standard_normal(3))
+        wl._hinge(skel, k, parent=k - 1, slot=(k - 1) if k % 5 else -1, anchor=(0, 0, 0.05), axis=ax, offset=(0, 0, 0.05))
+    sc = pxr.Scene(wl.default_scene(32, 32, bodies))
+    sc.set_skeleton(skel, 1, K - 1)
+    N = 130
+    free = np.zeros((N, 1, 7), np.float32)
+    free[:, 0, :3] = (0, 0, 1)
+    free[:, 0, 3:] = wl.random_quats(rng, (N,))
+    ang = rng.uniform(-1.5, 1.5, (N, K - 1)).astype(np.float32)
+    got = sc.pose_batch(torch.from_numpy(free).cuda(), torch.from_numpy(ang).cuda()).cpu().numpy()
+    assert np.array_equal(_bits(got), _bits(orc.fk(skel, free, ang)))
+    sc.close()
+
+
 @pytest.mark.parametrize("cfg,B", [(2, 40), (3, 24), (4, 20), (5, 16)])
 def test_angles_to_frames_match_oracle(torch, pxr, orc, cfg, B):
     from test_gpu_parity import _bind, assert_parity

@@ -216,6 +216,47 @@ def test_mesh_close_up_and_degenerate_triangles(torch, pxr, orc):
     assert_parity(gpu_render(torch, pxr, w), ref)
 
 
+# ---------------------------------------------------------------- maximum sizes
+
+def test_sixty_four_bodies(torch, pxr, orc):
+    """The body-count limit: 64 bodies of mixed kinds, per-environment shapes."""
+    rng = np.random.default_rng(64)
+    bodies = []
+    for k in range(64):
+        rgb = rng.uniform(0.2, 0.9, 3)
+        bodies.append([wl.capsule(0.05, 0.12, rgb, 5, 2), wl.sphere(0.08, rgb, 6, 2), wl.box(0.07, 0.05, 0.06, rgb, 1)][k % 3])
+    d = wl.default_scene(64, 48, bodies, root_body=63)
+    B = 10
+    poses = np.zeros((B, 1, 64, 7), np.float32)
+    poses[..., :3] = np.array([0.0, 0.0, 1.0]) + rng.uniform(-0.9, 0.9, (B, 1, 64, 3)) * np.array([1.0, 1.0, 0.6])
+    poses[..., 3:] = wl.random_quats(rng, (B, 1, 64))
+    shapes = np.array([b["shape"] for b in bodies], np.float32)[None] * rng.uniform(0.7, 1.4, (B, 64, 1)).astype(np.float32)
+    w = dict(desc=d, poses=poses, shapes=np.ascontiguousarray(shapes), distractor=None)
+    ref = oracle_render(orc, w)
+    assert len(np.unique(ref["ids"])) > 300
+    assert_parity(gpu_render(torch, pxr, w), ref)
+
+
+def test_scene_at_the_lds_limit(torch, pxr, orc):
+    """The finest tessellation that still fits one compute unit's LDS (one workgroup per unit, many bands)."""
+    bodies = [wl.sphere(0.5, (0.7, 0.4, 0.3), 64, 32), wl.capsule(0.2, 0.4, (0.3, 0.6, 0.8), 64, 8)]
+    d = wl.default_scene(128, 96, bodies)
+    d["cam_offset"] = (-1.8, 0.0, 0.5)
+    sc = pxr.Scene(d)
+    info = sc.info()
+    assert info["lds_bytes"] > 120 * 1024 and info["n_verts"] > 5000 and info["n_tris"] > 10000
+    rng = np.random.default_rng(65)
+    B = 3
+    poses = np.zeros((B, 1, 2, 7), np.float32)
+    poses[:, 0, 0, :3] = (0, 0, 1)
+    poses[:, 0, 0, 3:] = wl.random_quats(rng, (B,))
+    poses[:, 0, 1, :3] = np.array([0.0, 0.6, 1.0]) + rng.uniform(-0.2, 0.2, (B, 3))
+    poses[:, 0, 1, 3:] = wl.random_quats(rng, (B,))
+    w = dict(desc=d, poses=poses, shapes=None, distractor=None)
+    assert_parity(gpu_render(torch, pxr, w, scene=sc), oracle_render(orc, w))
+    sc.close()
+
+
 # ---------------------------------------------------------------- near-plane clipping
 
 def _clip_scenes():
