@@ -143,6 +143,9 @@ def time_next_stages(torch, pxr, w, reps=10):
     fk_bytes = 4 * (free[0, 0].numel() + ang[0, 0].numel() + K * 7) * n
     conv_bytes = frames.numel() + feat.numel() * 2
     conv_flops = 2.0 * B * conv.Ho * conv.Wo * 32 * 27 * S
+    pk = pxr.measure_peaks()
+    # the time this machine's HBM needs for the layer's bytes: reads at its read-stream rate plus writes at its write-stream rate
+    conv_bound_ms = 1e3 * (frames.numel() / (pk["read_gbs"] * 1e9) + feat.numel() * 2 / (pk["write_gbs"] * 1e9))
     out = {
         "kinematics-" + w["name"]: {"kernel": "fk_kernel", "avg_launch_ms": ms_fk, "frames_per_s": n / (1e-3 * ms_fk),
                                    "roofline": {"bound": "hbm", "achieved": fk_bytes / ms_fk / 1e6, "peak": HBM_PEAK_GBS,
@@ -153,7 +156,9 @@ def time_next_stages(torch, pxr, w, reps=10):
                                       "roofline": {"bound": "hbm", "achieved": conv_bytes / ms_conv / 1e6,
                                                    "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                                    "frac": conv_bytes / ms_conv / 1e6 / HBM_PEAK_GBS,
-                                                   "algorithmic_bytes_per_stack": conv_bytes / B}},
+                                                   "algorithmic_bytes_per_stack": conv_bytes / B,
+                                                   "measured_stream_bound_ms": conv_bound_ms,
+                                                   "frac_of_measured_stream_bound": conv_bound_ms / ms_conv}},
         "angles-to-features-" + w["name"]: {"ms_per_step": ms_all, "frames_per_s": n / (1e-3 * ms_all),
                                            "kernels": "fk_kernel + render_kernel + conv_kernel on one stream"},
     }

@@ -237,10 +237,11 @@ int pxr_set_block_threads(pxr_scene* s, uint32_t threads);
 
 /* Measurement aid (synchronous, allocates 2 GiB for the duration of the call): the rates this GPU sustains
  * on a dependent-free fp32 FMA loop and on a 24-bit integer multiply-add loop (both in T lane-operations/s,
- * 32 waves per compute unit) and the read+write bandwidth of a plain 1 GiB device-to-device copy (GB/s).
- * Lets a roofline fraction be quoted against the machine as it runs.  Any pointer may be NULL.
- * Errors: OOM, DEVICE. */
-int pxr_measure_peaks(double* fma_tlaneops, double* imad_tlaneops, double* copy_gbs);
+ * 32 waves per compute unit), the read+write bandwidth of a plain 1 GiB device-to-device copy and the
+ * bandwidths of a 2 GiB read-only and a 2 GiB write-only stream (GB/s; HBM does not give both directions
+ * the same rate).  Lets a roofline fraction be quoted against the machine as it runs.  Any pointer may be
+ * NULL.  Errors: OOM, DEVICE. */
+int pxr_measure_peaks(double* fma_tlaneops, double* imad_tlaneops, double* copy_gbs, double* read_gbs, double* write_gbs);
 
 /* Host-only introspection: run the scene builder of pxr_create_scene without
  * touching a device and copy out its tables, so that the tessellation and the

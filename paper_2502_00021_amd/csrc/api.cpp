@@ -326,9 +326,9 @@ int pxr_host_tables(const pxr_scene_desc* desc, uint32_t* n_verts, uint32_t* n_t
     return PXR_OK;
 }
 
-int pxr_measure_peaks(double* fma_tlaneops, double* imad_tlaneops, double* copy_gbs) {
+int pxr_measure_peaks(double* fma_tlaneops, double* imad_tlaneops, double* copy_gbs, double* read_gbs, double* write_gbs) {
     std::string err;
-    const int rc = pxr::measure_peaks(fma_tlaneops, imad_tlaneops, copy_gbs, err);
+    const int rc = pxr::measure_peaks(fma_tlaneops, imad_tlaneops, copy_gbs, read_gbs, write_gbs, err);
     if (rc != PXR_OK) return fail(rc, "pxr_measure_peaks: " + err);
     return PXR_OK;
 }

@@ -38,6 +38,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr uint32_t kConvThreads = 256;
 constexpr uint32_t kStageBytes = 2048;  // per wave: 32 pixels x 32 channels x bf16
@@ -172,7 +173,9 @@ __global__ __launch_bounds__(kConvThreads) void conv_kernel(const ConvConsts cc,
 #pragma unroll
             for (uint32_t h = 0; h < 2; ++h) {
                 const uint32_t off = h * 1024u + lane * 16u;
-                if (off < n_bytes) *reinterpret_cast<uint4*>(dst + off) = *reinterpret_cast<const uint4*>(stage + off);
+                // the features are not read again by this kernel: streaming stores keep them out of the caches' way
+                if (off < n_bytes)
+                    __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(stage + off), reinterpret_cast<u32x4*>(dst + off));
             }
             __builtin_amdgcn_wave_barrier();  // the next tile's staging writes stay behind these reads
         }

@@ -45,6 +45,24 @@ __global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
 
+// read-only and write-only streams: HBM does not give both directions the same rate
+__global__ __launch_bounds__(256) void read_kernel(const uint4* __restrict__ src, uint4* __restrict__ sink, size_t n) {
+    uint4 acc = make_uint4(0, 0, 0, 0);
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
+        const uint4 v = src[i];
+        acc.x ^= v.x;
+        acc.y ^= v.y;
+        acc.z ^= v.z;
+        acc.w ^= v.w;
+    }
+    if (acc.x == 0x12345678u && acc.y == 0x9ABCDEF0u) sink[0] = acc;  // keeps the loads alive
+}
+
+__global__ __launch_bounds__(256) void write_kernel(uint4* __restrict__ dst, size_t n) {
+    const uint4 v = make_uint4(threadIdx.x, 2u, 3u, 4u);
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = v;
+}
+
 template <typename F>
 int timed(hipStream_t st, int reps, F launch, double& seconds, std::string& err) {
     hipEvent_t e0, e1;
@@ -71,7 +89,8 @@ int timed(hipStream_t st, int reps, F launch, double& seconds, std::string& err)
 
 }  // namespace
 
-int measure_peaks(double* fma_tlaneops, double* imad_tlaneops, double* copy_gbs, std::string& err) {
+int measure_peaks(double* fma_tlaneops, double* imad_tlaneops, double* copy_gbs, double* read_gbs, double* write_gbs,
+                  std::string& err) {
     int dev = 0;
     hipDeviceProp_t prop;
     if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
@@ -104,6 +123,16 @@ int measure_peaks(double* fma_tlaneops, double* imad_tlaneops, double* copy_gbs,
                                (uint4*)((char*)buf + copy_bytes), copy_bytes / 16);
         }, t, err);
     if (rc == PXR_OK && copy_gbs) *copy_gbs = 2.0 * (double)copy_bytes / t / 1e9;  // bytes read + bytes written
+    const uint32_t stream_blocks = (uint32_t)prop.multiProcessorCount * 8u;
+    if (rc == PXR_OK)
+        rc = timed(st, 5, [&] {
+            hipLaunchKernelGGL(read_kernel, dim3(stream_blocks), dim3(256), 0, st, (const uint4*)buf, (uint4*)buf, 2 * copy_bytes / 16);
+        }, t, err);
+    if (rc == PXR_OK && read_gbs) *read_gbs = 2.0 * (double)copy_bytes / t / 1e9;
+    if (rc == PXR_OK)
+        rc = timed(st, 5, [&] { hipLaunchKernelGGL(write_kernel, dim3(stream_blocks), dim3(256), 0, st, (uint4*)buf, 2 * copy_bytes / 16); },
+                   t, err);
+    if (rc == PXR_OK && write_gbs) *write_gbs = 2.0 * (double)copy_bytes / t / 1e9;
     (void)hipFree(buf);
     return rc;
 }

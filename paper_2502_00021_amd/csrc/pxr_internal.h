@@ -143,8 +143,9 @@ int launch_conv(const ConvConsts& cc, const uint8_t* d_frames, uint32_t B, uint1
                 void* stream, std::string& err);
 
 // peaks.hip: sustained fp32-FMA and 24-bit integer multiply-add rates (T lane-operations/s) and the
-// read+write bandwidth of a plain 1 GiB copy (GB/s) on the current device.
-int measure_peaks(double* fma_tlaneops, double* imad_tlaneops, double* copy_gbs, std::string& err);
+// read+write bandwidth of a plain 1 GiB copy and of 2 GiB read-only / write-only streams (GB/s) on the current device.
+int measure_peaks(double* fma_tlaneops, double* imad_tlaneops, double* copy_gbs, double* read_gbs, double* write_gbs,
+                  std::string& err);
 
 // kinematics.hip: joint angles -> poses, one lane per frame.
 uint32_t fk_lds_bytes(const SkeletonConsts& sk);

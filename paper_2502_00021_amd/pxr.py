@@ -90,7 +90,7 @@ def lib():
         L.pxr_conv_set_tuning.argtypes = [vp, u32, u32]
         for name in ("pxr_conv_create", "pxr_conv_destroy", "pxr_conv_forward", "pxr_conv_info", "pxr_conv_set_tuning"):
             getattr(L, name).restype = C.c_int
-        L.pxr_measure_peaks.argtypes = [vp, vp, vp]
+        L.pxr_measure_peaks.argtypes = [vp, vp, vp, vp, vp]
         L.pxr_measure_peaks.restype = C.c_int
         L.pxr_last_error.restype = C.c_char_p
         for name in ("pxr_create_scene", "pxr_destroy_scene", "pxr_apply_distractor", "pxr_render_batch",
@@ -404,10 +404,10 @@ def make_skeleton_desc(skel, n_free, n_angles):
 
 
 def measure_peaks():
-    """pxr_measure_peaks: dict(fma_tlaneops, imad_tlaneops, copy_gbs) measured on the current device."""
-    a, b, c = C.c_double(), C.c_double(), C.c_double()
-    _check(lib().pxr_measure_peaks(C.byref(a), C.byref(b), C.byref(c)))
-    return dict(fma_tlaneops=a.value, imad_tlaneops=b.value, copy_gbs=c.value)
+    """pxr_measure_peaks: dict(fma_tlaneops, imad_tlaneops, copy_gbs, read_gbs, write_gbs) measured on the current device."""
+    v = [C.c_double() for _ in range(5)]
+    _check(lib().pxr_measure_peaks(*[C.byref(x) for x in v]))
+    return dict(zip(("fma_tlaneops", "imad_tlaneops", "copy_gbs", "read_gbs", "write_gbs"), (x.value for x in v)))
 
 
 def ids_to_numpy(ids):

@@ -13,3 +13,5 @@ def test_measured_peaks_are_plausible():
     assert 15.0 < pk["fma_tlaneops"] <= 40.0, pk
     assert 15.0 < pk["imad_tlaneops"] <= 40.0, pk
     assert 1500.0 < pk["copy_gbs"] <= 8000.0, pk
+    assert 1500.0 < pk["write_gbs"] <= 8000.0 and 1500.0 < pk["read_gbs"] <= 8000.0, pk
+    assert pk["read_gbs"] > 0.9 * pk["write_gbs"]
