@@ -167,6 +167,54 @@ def time_next_stages(torch, pxr, w, reps=10):
     return out
 
 
+def time_small_batch_graph(torch, pxr, reps=200):
+    """A launch-bound step (cfg2: 256 environments; angles -> poses -> frames -> conv features = three small
+    kernels) enqueued eagerly and replayed from a HIP graph captured once."""
+    w = workloads.make(2)
+    fk = w["fk"]
+    scene = pxr.Scene(w["desc"])
+    scene.set_skeleton(fk["skel"], fk["free_poses"].shape[-2], fk["angles"].shape[-1])
+    rng = np.random.default_rng(0)
+    conv = pxr.Conv(scene.H, scene.W, 1, (rng.standard_normal((3, 3, 3, 32)) * 0.1).astype(np.float32), np.zeros(32, np.float32))
+    free = torch.from_numpy(fk["free_poses"]).cuda()
+    ang = torch.from_numpy(fk["angles"]).cuda()
+    B = free.shape[0]
+    poses = torch.empty((B, 1, scene.K, 7), dtype=torch.float32, device="cuda")
+    frames = torch.empty((B, 1, scene.H, scene.W, 3), dtype=torch.uint8, device="cuda")
+    feat = torch.empty((B, conv.Ho, conv.Wo, 32), dtype=torch.bfloat16, device="cuda")
+
+    def step():
+        scene.render_batch_kinematic(free, ang, None, poses=poses, frames=frames)
+        conv.forward(frames, out=feat)
+
+    def wall(fn):
+        for _ in range(10):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return 1e6 * (time.perf_counter() - t0) / reps
+
+    us_eager = wall(step)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    us_graph = wall(graph.replay)
+    conv.close()
+    scene.close()
+    return {"small-batch-step-" + w["name"]: {"envs": B, "us_per_step_eager": us_eager, "us_per_step_hip_graph": us_graph,
+                                            "frames_per_s_hip_graph": B / (1e-6 * us_graph),
+                                            "kernels": "fk_kernel + render_kernel + conv_kernel, wall clock per step"}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -279,6 +327,7 @@ def main():
                                      hbm_frac_of_measured_copy=out["roofline"]["hbm"]["achieved"] / pk["copy_gbs"])
         others = {}
         others.update(time_next_stages(torch, pxr, r["w"]))
+        others.update(time_small_batch_graph(torch, pxr))
         for name, c, envs, dis in [("cfg2-chain-64", 2, 256, True), ("cfg3-quadruped-64-colour", 3, 4096, True),
                                    ("cfg3-quadruped-64-no-distractor", 3, 4096, False),
                                    ("cfg4-humanoid-84-video", 4, 16384, True),
