@@ -23,9 +23,8 @@
  * Moller-Trumbore ray casts; horizon row; shade extremes; RNG bijectivity and
  * statistics; distractor identities; kinematics against float64 quaternion algebra (an independent
  * numpy implementation) and libm sin/cos.
- * Parity unpinned: agreement of orc_philox with the published Philox-4x32-10
- * known-answer vectors (none are available offline; the method only needs a
- * reproducible, well-mixed counter-based generator, which the pins do check).
+ * The generator reproduces the published Philox-4x32-10 known-answer vectors
+ * (tests/golden/philox4x32_10_kat.txt).
  */
 #ifndef ORC_H
 #define ORC_H
