@@ -215,6 +215,49 @@ def time_small_batch_graph(torch, pxr, reps=200):
                                             "kernels": "fk_kernel + render_kernel + conv_kernel, wall clock per step"}}
 
 
+def time_paper_loop(torch, pxr, env_counts=(1, 10, 100, 1000, 10000), seconds=0.25):
+    """The shape of the paper's throughput experiment (its steps-per-second figure): for each of its four
+    environments (stand-in skeletons) and each number of parallel environments, one step = joint angles ->
+    poses -> one 64x64 frame per environment -> one convolutional layer, all on the device, physics left out.
+    Steps are enqueued back to back and the clock stops after a final synchronisation."""
+    out = {}
+    rng = np.random.default_rng(0)
+    wgt = (rng.standard_normal((3, 3, 3, 32)) * 0.1).astype(np.float32)
+    for name, make in workloads.PAPER_ENVIRONMENTS.items():
+        row = {}
+        for n in env_counts:
+            w = make(n)
+            fk = w["fk"]
+            scene = pxr.Scene(w["desc"])
+            scene.set_skeleton(fk["skel"], fk["free_poses"].shape[-2], fk["angles"].shape[-1])
+            conv = pxr.Conv(scene.H, scene.W, 1, wgt, np.zeros(32, np.float32))
+            free = torch.from_numpy(fk["free_poses"]).cuda()
+            ang = torch.from_numpy(fk["angles"]).cuda()
+            poses = torch.empty((n, 1, scene.K, 7), dtype=torch.float32, device="cuda")
+            frames = torch.empty((n, 1, scene.H, scene.W, 3), dtype=torch.uint8, device="cuda")
+            feat = torch.empty((n, conv.Ho, conv.Wo, 32), dtype=torch.bfloat16, device="cuda")
+
+            def run(k):
+                for i in range(k):
+                    scene.render_batch_kinematic(free, ang, None, step0=i, poses=poses, frames=frames)
+                    conv.forward(frames, out=feat)
+                torch.cuda.synchronize()
+
+            run(20)
+            t0 = time.perf_counter()
+            run(50)
+            per = (time.perf_counter() - t0) / 50
+            k = max(50, min(5000, int(seconds / per)))
+            t0 = time.perf_counter()
+            run(k)
+            dt = time.perf_counter() - t0
+            row[str(n)] = {"env_steps_per_s": n * k / dt, "iterations_per_s": k / dt}
+            conv.close()
+            scene.close()
+        out[name] = row
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -328,6 +371,7 @@ def main():
         others = {}
         others.update(time_next_stages(torch, pxr, r["w"]))
         others.update(time_small_batch_graph(torch, pxr))
+        out["paper_loop_steps_per_s"] = time_paper_loop(torch, pxr)
         for name, c, envs, dis in [("cfg2-chain-64", 2, 256, True), ("cfg3-quadruped-64-colour", 3, 4096, True),
                                    ("cfg3-quadruped-64-no-distractor", 3, 4096, False),
                                    ("cfg4-humanoid-84-video", 4, 16384, True),

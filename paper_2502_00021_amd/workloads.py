@@ -411,6 +411,65 @@ def cfg_mesh(B=64, W=64, H=64):
                 distractor=dis, step0=0)
 
 
+def _planar_walker(name, seed, B, W, H, torso, legs, torso_pitch):
+    """Planar (x-z plane) articulated figure described by its skeleton only: a free torso capsule lying along x
+    and `legs` = lists of (radius, half_length) chains hanging from torso anchors, all hinges about y.  Poses
+    are not generated here: these workloads enter through the kinematics stage (angles -> poses on the device)."""
+    rng = np.random.default_rng(SEED_BASE + seed)
+    (tr, th, tz), K = torso, 1 + sum(len(l[1]) for l in legs)
+    rgb = rng.uniform(0.2, 0.9, (K, 3))
+    bodies = [capsule(tr, th, rgb[0], 12, 6)]
+    skel = _skeleton(K)
+    skel["slot"][0] = 0
+    k, slot = 1, 0
+    for anchor_x, links in legs:
+        parent, anchor = 0, (0.0, 0.0, anchor_x)  # the torso's own axis is its local z (it is pitched to lie along x)
+        for (r, h) in links:
+            bodies.append(capsule(r, h, rgb[k], 12, 6))
+            _hinge(skel, k, parent=parent, slot=slot, anchor=anchor, axis=(0, 1, 0), offset=(0, 0, -h))
+            parent, anchor = k, (0.0, 0.0, -h)
+            k += 1
+            slot += 1
+    free = np.zeros((B, 1, 1, 7), np.float32)
+    free[..., :3] = (0.0, 0.0, tz)
+    free[:, 0, 0, 3:] = q_axis_angle(np.array([0.0, 1.0, 0.0]), torso_pitch + rng.uniform(-0.2, 0.2, B)).astype(np.float32)
+    angles = rng.uniform(-0.9, 0.9, (B, 1, slot))
+    first = np.cumsum([0] + [len(l[1]) for l in legs])[:-1]
+    angles[:, :, first] -= torso_pitch  # the first link of a leg turns back from the torso's frame: legs hang down
+    angles = angles.astype(np.float32)
+    desc = default_scene(W, H, bodies)
+    desc["cam_offset"] = (0.0, -2.6, 0.6)  # side view, as the planar tasks are usually shown
+    return dict(name=name, desc=desc, poses=None, shapes=None, distractor=None, step0=0,
+                fk=dict(skel=skel, free_poses=free, angles=angles))
+
+
+def halfcheetah_like(B=1000, W=64, H=64):
+    """Stand-in for the paper's HalfCheetah: torso + back and front leg of three links each (7 bodies, 6 hinges)."""
+    leg = [(0.046, 0.145), (0.046, 0.15), (0.046, 0.094)]
+    return _planar_walker("halfcheetah-like-64", 7, B, W, H, (0.046, 0.5, 0.7), [(-0.5, leg), (0.5, leg)], np.pi / 2)
+
+
+def walker2d_like(B=1000, W=64, H=64):
+    """Stand-in for the paper's Walker2d: upright torso + two legs of thigh, shin, foot (7 bodies, 6 hinges)."""
+    leg = [(0.05, 0.225), (0.04, 0.25), (0.06, 0.1)]
+    return _planar_walker("walker2d-like-64", 8, B, W, H, (0.05, 0.2, 1.25), [(-0.2, leg), (-0.2, leg)], 0.0)
+
+
+def ant_like(B=1000):
+    """Stand-in for the paper's Ant: the quadruped of configuration 3 without its distractor."""
+    w = cfg3(B)
+    return dict(w, name="ant-like-64", distractor=None)
+
+
+def humanoid_like(B=1000):
+    """Stand-in for the paper's Humanoid: the 14-body tree of configuration 4 at 64x64 without its distractor."""
+    w = cfg4(B)
+    desc = dict(w["desc"], width=64, height=64)
+    return dict(w, name="humanoid-like-64", desc=desc, distractor=None)
+
+
+PAPER_ENVIRONMENTS = {"halfcheetah": halfcheetah_like, "ant": ant_like, "walker2d": walker2d_like, "humanoid": humanoid_like}
+
 CONFIGS = {1: cfg1, 2: cfg2, 3: cfg3, 4: cfg4, 5: cfg5}
 
 

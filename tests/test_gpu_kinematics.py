@@ -136,6 +136,24 @@ def test_angles_to_frames_match_oracle(torch, pxr, orc, cfg, B):
     sc.close()
 
 
+@pytest.mark.parametrize("env", ["halfcheetah", "ant", "walker2d", "humanoid"])
+def test_paper_environment_stand_ins(torch, pxr, orc, env):
+    """The four environments the paper supports, as skeleton workloads: angles -> poses -> frames on the device."""
+    from test_gpu_parity import assert_parity
+    w = wl.PAPER_ENVIRONMENTS[env](B=70)
+    fk = w["fk"]
+    sc = _scene_with_skeleton(pxr, w)
+    frames, ids, poses = sc.render_batch_kinematic(torch.from_numpy(fk["free_poses"]).cuda(),
+                                                   torch.from_numpy(fk["angles"]).cuda(), None, want_ids=True)
+    torch.cuda.synchronize()
+    ref_poses = orc.fk(fk["skel"], fk["free_poses"], fk["angles"])
+    assert np.array_equal(_bits(poses.cpu().numpy()), _bits(ref_poses))
+    ref = orc.Scene(w["desc"]).render(ref_poses)
+    assert (ref["ids"] < 0xFFFFFFFE).mean() > 0.015
+    assert_parity(dict(frames=frames.cpu().numpy(), ids=pxr.ids_to_numpy(ids)), ref)
+    sc.close()
+
+
 def test_full_size_pose_batch_bit_exact(torch, pxr, orc):
     """The headline workload's 196 608 frames, every pose compared."""
     w = wl.make(5)
