@@ -12,8 +12,11 @@ SOURCES = ["api.cpp", "conv_api.cpp", "scene.cpp", "render.hip", "kinematics.hip
 # output contract (coverage is decided by integers derived from these floats),
 # so fusions are written out as fmaf and the compiler must not add its own.
 # packed-fp32-ops is switched off for the device pass (see the platform notes).
+# The LDS counters are already bumped once per wavefront by hand (ballot + popcount, lane 0 adds); the
+# compiler's own wave-aggregation of uniform atomic adds would wrap that single-lane add a second time.
 HIPFLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
             "-fno-fast-math", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+            "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
             "-Wall", "-Wextra", "-Wno-unused-parameter", "-x", "hip"]
 
 
