@@ -37,7 +37,7 @@ MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("cfg5", 65536): 2541.9e6, ("cfg4", 16384):
 
 
 def algorithmic_ops_per_frame(V, T, npix, mode):
-    """Lane-operations per frame that the method itself prescribes (DESIGN.md section 6).
+    """Lane-operations per frame that the method itself prescribes.
 
     Counted from the operation list of the specification, not from the kernel's
     instruction stream (an IEEE fp32 division counts as 10, memory and address
