@@ -64,3 +64,69 @@ def test_captured_step_replays_like_eager_calls():
         assert torch.equal(feat.view(torch.int16), c.view(torch.int16)), rep
     conv.close()
     scene.close()
+
+
+def test_two_scenes_on_two_streams_and_two_host_threads():
+    """Scenes are independent objects and the hot calls keep no hidden state: two host threads, each with its own
+    scene and its own (default-priority) stream, interleave launches; every result equals the single-stream one."""
+    import threading
+    import torch
+    from paper_2502_00021_amd import pxr
+    from test_gpu_parity import _bind
+    results, errors = {}, []
+
+    def reference(cfg, B):
+        w = wl.make(cfg, B=B)
+        sc = pxr.Scene(w["desc"])
+        _bind(torch, sc, w["distractor"])
+        poses = torch.from_numpy(w["poses"]).cuda()
+        shapes = None if w["shapes"] is None else torch.from_numpy(w["shapes"]).cuda()
+        out = [sc.render_batch(poses, shapes, step0=s)[0].clone() for s in range(6)]
+        torch.cuda.synchronize()
+        sc.close()
+        return out
+
+    refs = {3: reference(3, 64), 5: reference(5, 24)}
+
+    def worker(cfg, B):
+        try:
+            torch.cuda.set_device(0)
+            w = wl.make(cfg, B=B)
+            sc = pxr.Scene(w["desc"])
+            _bind(torch, sc, w["distractor"])
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                poses = torch.from_numpy(w["poses"]).cuda()
+                shapes = None if w["shapes"] is None else torch.from_numpy(w["shapes"]).cuda()
+                outs = []
+                for rep in range(4):
+                    outs = [sc.render_batch(poses, shapes, step0=s, stream=stream.cuda_stream)[0] for s in range(6)]
+                stream.synchronize()
+                results[cfg] = [o.clone() for o in outs]
+                stream.synchronize()
+            sc.close()
+        except Exception as e:  # surfaced in the main thread
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=worker, args=(3, 64)), threading.Thread(target=worker, args=(5, 24))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for cfg in (3, 5):
+        for a, b in zip(results[cfg], refs[cfg]):
+            assert torch.equal(a, b)
+    # an error on one thread does not leak into another thread's message
+    L = pxr.lib()
+    seen = {}
+
+    def bad_call():
+        L.pxr_destroy_scene(None)
+        L.pxr_scene_info(None, None, None, None, None)
+        seen["bad"] = L.pxr_last_error()
+
+    t = threading.Thread(target=bad_call)
+    t.start()
+    t.join()
+    assert b"pxr_scene_info" in seen["bad"]
