@@ -50,11 +50,23 @@ __device__ __forceinline__ uint32_t bf16_pair(float lo, float hi) {
 }
 
 __device__ __forceinline__ uint32_t to_bf16_pair(float lo, float hi) {
-    const __bf16 a = (__bf16)lo, b = (__bf16)hi;  // round to nearest even
-    return (uint32_t)__builtin_bit_cast(unsigned short, a) | ((uint32_t)__builtin_bit_cast(unsigned short, b) << 16);
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));  // v_cvt_pk_bf16_f32: round to nearest even
 }
 
-template <int S>
+// Streaming 16-byte store, written as an instruction so that the compiler's wait-count pass does not see a
+// vector-memory operation inside the per-tile loop: with a visible store there it drains the memory counter
+// before entering the loop, which would make every wave sit out the latency of the loads just issued for the
+// next work item instead of covering it with the matrix work.  (The counter is shared by loads and stores and
+// only ever over-waited by this: a later wait for "at most n operations outstanding" still implies that the
+// older loads have returned.)
+__device__ __forceinline__ void store_streaming_b128(void* dst, u32x4 v) {
+    asm volatile("global_store_dwordx4 %0, %1, off nt" : : "v"(dst), "v"(v) : "memory");
+}
+
+template <int S, bool RELU>
 __global__ __launch_bounds__(kConvThreads) void conv_kernel(const ConvConsts cc, const uint8_t* __restrict__ frames,
                                                             uint32_t n_items, uint16_t* __restrict__ out) {
     extern __shared__ __align__(16) unsigned char lds[];
@@ -73,6 +85,12 @@ __global__ __launch_bounds__(kConvThreads) void conv_kernel(const ConvConsts cc,
     float bias[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) bias[i] = cc.bias[16 * g + i];
+    // Let the weights arrive before the first input request goes out: the memory counter is in-order, so a
+    // later wait that has to cover a possibly pending weight register would also wait for every prefetched
+    // input behind it, in every tile of every work item.  (s_waitcnt vmcnt(0); other counters untouched.)
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    asm volatile("" ::: "memory");
 
     // A work item's input: rows 2*oy0 .. 2*oy0 + rows - 1 of each of the S frames, as "quads" of 4 pixels
     // (12 bytes).  Quad f of the item (f = tid + 256 p) belongs to frame s = f / n_quads.  An item's quads
@@ -86,10 +104,15 @@ __global__ __launch_bounds__(kConvThreads) void conv_kernel(const ConvConsts cc,
     auto fetch = [&](uint32_t item) {
         const uint32_t env = item / cc.bands, oy0 = (item - env * cc.bands) * cc.band_rows;
         const uint32_t n_quads = (2u * min(cc.band_rows, cc.Ho - oy0) + 1u) * quads_per_row;
-        const unsigned char* base = frames + (((size_t)env * S) * cc.H + 2u * oy0) * cc.W * 3u;
+        // (an environment's S frames are at most 1.5 MB: offsets inside them fit 32 bits)
+        const unsigned char* base = frames + (size_t)env * (S * cc.H * cc.W * 3u) + 2u * oy0 * cc.W * 3u;
+        const uint32_t frame_bytes = cc.H * cc.W * 3u;
+        // Unconditional loads (lanes past the item's last quad re-read it): with no branch around them the four
+        // requests of a thread are in flight together; a guarded load makes the compiler wait for the previous
+        // one before it reuses the guard's registers.
 #pragma unroll
         for (uint32_t p = 0; p < kConvTrips; ++p) {
-            const uint32_t f = tid + p * kConvThreads;
+            const uint32_t f = min(tid + p * kConvThreads, S * n_quads - 1u);
             uint32_t s = 0, q = f;
 #pragma unroll
             for (int t = 1; t < S; ++t)
@@ -97,8 +120,7 @@ __global__ __launch_bounds__(kConvThreads) void conv_kernel(const ConvConsts cc,
                     s = t;
                     q = f - t * n_quads;
                 }
-            if (f < S * n_quads)
-                pre[p] = *reinterpret_cast<const Quad*>(base + (size_t)s * cc.H * cc.W * 3u + (size_t)q * 12u);
+            pre[p] = *reinterpret_cast<const Quad*>(base + (s * frame_bytes + q * 12u));
         }
     };
 
@@ -139,15 +161,15 @@ __global__ __launch_bounds__(kConvThreads) void conv_kernel(const ConvConsts cc,
         // ---- one wavefront per (output row, 32-pixel tile)
         const uint32_t n_tasks = rows_out * cc.tiles_x;
         for (uint32_t task = wave; task < n_tasks; task += kConvThreads / 64) {
-            const uint32_t r_out = task / cc.tiles_x, tx = task - r_out * cc.tiles_x;
+            const uint32_t r_out = __umul24(task, cc.tiles_magic) >> 16, tx = task - __umul24(r_out, cc.tiles_x);  // task / tiles_x
             const uint32_t ox = min(tx * 32u + n, cc.Wo - 1u);  // lanes past the row's end recompute its last pixel
-            const unsigned char* bsrc = lds + ((size_t)(2u * r_out) * cc.W + 2u * ox + 2u * g) * 8u;
+            const unsigned char* bsrc = lds + (__umul24(2u * r_out, cc.W) + 2u * ox + 2u * g) * 8u;
             f32x16 acc = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
             for (int s = 0; s < S; ++s)
 #pragma unroll
                 for (int ky = 0; ky < 3; ++ky) {
-                    const uint4 v = *reinterpret_cast<const uint4*>(bsrc + s * frame_lds + (size_t)ky * cc.W * 8u);
+                    const uint4 v = *reinterpret_cast<const uint4*>(bsrc + (s * frame_lds + ky * cc.W * 8u));
                     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aw[s * 3 + ky], __builtin_bit_cast(bf16x8, v), acc, 0, 0, 0);
                 }
             uint32_t packed[8];
@@ -155,9 +177,9 @@ __global__ __launch_bounds__(kConvThreads) void conv_kernel(const ConvConsts cc,
             for (int i = 0; i < 8; ++i) {
                 float a = __builtin_fmaf(acc[2 * i], 1.0f / 255.0f, bias[2 * i]);
                 float b = __builtin_fmaf(acc[2 * i + 1], 1.0f / 255.0f, bias[2 * i + 1]);
-                if (cc.relu) {
-                    a = a > 0.0f ? a : 0.0f;
-                    b = b > 0.0f ? b : 0.0f;
+                if (RELU) {
+                    a = __builtin_fmaxf(a, 0.0f);
+                    b = __builtin_fmaxf(b, 0.0f);
                 }
                 packed[i] = to_bf16_pair(a, b);
             }
@@ -168,14 +190,14 @@ __global__ __launch_bounds__(kConvThreads) void conv_kernel(const ConvConsts cc,
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             const uint32_t n_bytes = min(32u, cc.Wo - tx * 32u) * 64u;
-            unsigned char* dst = reinterpret_cast<unsigned char*>(out) +
-                                 (((size_t)env * cc.Ho + oy0 + r_out) * cc.Wo + tx * 32u) * 64u;
+            // (an environment's features are below 2 GB: 32-bit offsets from its base)
+            unsigned char* dst = reinterpret_cast<unsigned char*>(out) + (size_t)env * (cc.Ho * cc.Wo * 64u) +
+                                 (__umul24(oy0 + r_out, cc.Wo) + tx * 32u) * 64u;
 #pragma unroll
             for (uint32_t h = 0; h < 2; ++h) {
                 const uint32_t off = h * 1024u + lane * 16u;
                 // the features are not read again by this kernel: streaming stores keep them out of the caches' way
-                if (off < n_bytes)
-                    __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(stage + off), reinterpret_cast<u32x4*>(dst + off));
+                if (off < n_bytes) store_streaming_b128(dst + off, *reinterpret_cast<const u32x4*>(stage + off));
             }
             __builtin_amdgcn_wave_barrier();  // the next tile's staging writes stay behind these reads
         }
@@ -193,8 +215,10 @@ uint32_t conv_lds_bytes(const ConvConsts& cc) {
 }
 
 int prepare_conv_kernels(std::string& err) {
-    const void* fns[4] = {reinterpret_cast<const void*>(&conv_kernel<1>), reinterpret_cast<const void*>(&conv_kernel<2>),
-                          reinterpret_cast<const void*>(&conv_kernel<3>), reinterpret_cast<const void*>(&conv_kernel<4>)};
+    const void* fns[8] = {reinterpret_cast<const void*>(&conv_kernel<1, true>), reinterpret_cast<const void*>(&conv_kernel<2, true>),
+                          reinterpret_cast<const void*>(&conv_kernel<3, true>), reinterpret_cast<const void*>(&conv_kernel<4, true>),
+                          reinterpret_cast<const void*>(&conv_kernel<1, false>), reinterpret_cast<const void*>(&conv_kernel<2, false>),
+                          reinterpret_cast<const void*>(&conv_kernel<3, false>), reinterpret_cast<const void*>(&conv_kernel<4, false>)};
     for (const void* f : fns) {
         const hipError_t rc = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (rc != hipSuccess) {
@@ -211,13 +235,20 @@ int launch_conv(const ConvConsts& cc, const uint8_t* d_frames, uint32_t B, uint1
     const uint32_t grid = min(n_items, n_groups);
     const uint32_t ldsb = conv_lds_bytes(cc);
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+#define PXR_CONV_LAUNCH(SS)                                                                                             \
+    if (cc.relu)                                                                                                        \
+        hipLaunchKernelGGL((conv_kernel<SS, true>), dim3(grid), dim3(kConvThreads), ldsb, st, cc, d_frames, n_items, d_out); \
+    else                                                                                                                \
+        hipLaunchKernelGGL((conv_kernel<SS, false>), dim3(grid), dim3(kConvThreads), ldsb, st, cc, d_frames, n_items, d_out); \
+    break
     switch (cc.S) {
-        case 1: hipLaunchKernelGGL(conv_kernel<1>, dim3(grid), dim3(kConvThreads), ldsb, st, cc, d_frames, n_items, d_out); break;
-        case 2: hipLaunchKernelGGL(conv_kernel<2>, dim3(grid), dim3(kConvThreads), ldsb, st, cc, d_frames, n_items, d_out); break;
-        case 3: hipLaunchKernelGGL(conv_kernel<3>, dim3(grid), dim3(kConvThreads), ldsb, st, cc, d_frames, n_items, d_out); break;
-        case 4: hipLaunchKernelGGL(conv_kernel<4>, dim3(grid), dim3(kConvThreads), ldsb, st, cc, d_frames, n_items, d_out); break;
+        case 1: PXR_CONV_LAUNCH(1);
+        case 2: PXR_CONV_LAUNCH(2);
+        case 3: PXR_CONV_LAUNCH(3);
+        case 4: PXR_CONV_LAUNCH(4);
         default: err = "frame stack depth must lie in [1,4]"; return PXR_ERR_UNSUPPORTED;
     }
+#undef PXR_CONV_LAUNCH
     const hipError_t rc = hipGetLastError();
     if (rc != hipSuccess) {
         err = std::string("kernel launch failed: ") + hipGetErrorString(rc);

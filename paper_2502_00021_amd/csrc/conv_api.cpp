@@ -62,6 +62,7 @@ int pxr_conv_create(const pxr_conv_desc* d, pxr_conv** out) {
     cc.Ho = (cc.H - 3) / 2 + 1;
     cc.Wo = (cc.W - 3) / 2 + 1;
     cc.tiles_x = (cc.Wo + 31) / 32;
+    cc.tiles_magic = (65536u + cc.tiles_x - 1) / cc.tiles_x;
     cc.relu = d->relu ? 1u : 0u;
     // band height: about 40 KB of LDS per workgroup so that four of them share a compute unit
     uint32_t band = 1;

@@ -124,6 +124,7 @@ struct ConvConsts {
     uint32_t H, W, S;        // input frames [S,H,W,3] per environment
     uint32_t Ho, Wo;         // output size
     uint32_t tiles_x;        // 32-pixel tiles per output row
+    uint32_t tiles_magic;    // ceil(2^16 / tiles_x): task / tiles_x == (task * tiles_magic) >> 16 for task < 2^13
     uint32_t band_rows;      // output rows per work item
     uint32_t bands;          // work items per environment
     uint32_t rows_in;        // input rows held in LDS per frame = 2 * band_rows + 1
