@@ -243,6 +243,15 @@ int pxr_set_block_threads(pxr_scene* s, uint32_t threads);
  * NULL.  Errors: OOM, DEVICE. */
 int pxr_measure_peaks(double* fma_tlaneops, double* imad_tlaneops, double* copy_gbs, double* read_gbs, double* write_gbs);
 
+/* Verification aid (synchronous, a few tens of milliseconds): the render kernel replaces two operations whose
+ * results decide integers by shorter instruction sequences - 1/x by the hardware estimate plus one fused
+ * Newton step, (int)floorf(x) by one converting instruction.  This call compares each with the plain form on
+ * the current device for EVERY 32-bit pattern in its domain (x in [2^-100, 2^100]; every x that is not NaN)
+ * and writes to the host array counts[4]: reciprocal mismatches, floor mismatches, patterns checked by the
+ * first and by the second comparison.  Both mismatch counts must be 0 on a device the library supports.
+ * Errors: INVALID_ARG (null), OOM, DEVICE. */
+int pxr_selftest_arithmetic(uint64_t* counts);
+
 /* Host-only introspection: run the scene builder of pxr_create_scene without
  * touching a device and copy out its tables, so that the tessellation and the
  * camera constants can be checked on a machine without a GPU.  Any output

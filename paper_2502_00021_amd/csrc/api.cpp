@@ -326,6 +326,16 @@ int pxr_host_tables(const pxr_scene_desc* desc, uint32_t* n_verts, uint32_t* n_t
     return PXR_OK;
 }
 
+int pxr_selftest_arithmetic(uint64_t* counts) {
+    if (!counts) return fail(PXR_ERR_INVALID_ARG, "pxr_selftest_arithmetic: null output");
+    std::string err;
+    unsigned long long c[4] = {0, 0, 0, 0};
+    const int rc = pxr::selftest_arithmetic(c, err);
+    if (rc != PXR_OK) return fail(rc, "pxr_selftest_arithmetic: " + err);
+    for (int i = 0; i < 4; ++i) counts[i] = c[i];
+    return PXR_OK;
+}
+
 int pxr_measure_peaks(double* fma_tlaneops, double* imad_tlaneops, double* copy_gbs, double* read_gbs, double* write_gbs) {
     std::string err;
     const int rc = pxr::measure_peaks(fma_tlaneops, imad_tlaneops, copy_gbs, read_gbs, write_gbs, err);

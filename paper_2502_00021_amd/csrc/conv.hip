@@ -62,8 +62,10 @@ __device__ __forceinline__ uint32_t to_bf16_pair(float lo, float hi) {
 // next work item instead of covering it with the matrix work.  (The counter is shared by loads and stores and
 // only ever over-waited by this: a later wait for "at most n operations outstanding" still implies that the
 // older loads have returned.)
+// The two idle cycles after it are the ones the hardware asks for between a store of more than 8 bytes and a
+// vector instruction that overwrites the stored registers; the compiler adds them for stores it can see.
 __device__ __forceinline__ void store_streaming_b128(void* dst, u32x4 v) {
-    asm volatile("global_store_dwordx4 %0, %1, off nt" : : "v"(dst), "v"(v) : "memory");
+    asm volatile("global_store_dwordx4 %0, %1, off nt\n\ts_nop 1" : : "v"(dst), "v"(v) : "memory");
 }
 
 template <int S, bool RELU>

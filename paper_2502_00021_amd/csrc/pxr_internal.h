@@ -71,7 +71,7 @@ struct SceneConsts {
     const float* cxcy;        // [W+H]   pixel-centre ray slopes
     // LDS carve-up (byte offsets into the dynamic segment)
     // the lds_keys region first holds the per-vertex cell codes (u32[V]) and the candidate list (u16[T])
-    uint32_t lds_keys, lds_vx, lds_vy, lds_vd, lds_body, lds_list, lds_large, lds_cxcy, lds_misc, lds_total;
+    uint32_t lds_keys, lds_vx, lds_vy, lds_vd, lds_body, lds_list, lds_large, lds_cxcy, lds_rows, lds_misc, lds_total;
 };
 
 // Distractor state bound by pxr_apply_distractor.
@@ -147,6 +147,10 @@ int launch_conv(const ConvConsts& cc, const uint8_t* d_frames, uint32_t B, uint1
 // read+write bandwidth of a plain 1 GiB copy and of 2 GiB read-only / write-only streams (GB/s) on the current device.
 int measure_peaks(double* fma_tlaneops, double* imad_tlaneops, double* copy_gbs, double* read_gbs, double* write_gbs,
                   std::string& err);
+
+// selftest.hip: the render kernel's arithmetic shortcuts against the plain forms over every float
+// (counts: reciprocal mismatches, floor-convert mismatches, patterns looked at by each check).
+int selftest_arithmetic(unsigned long long counts[4], std::string& err);
 
 // kinematics.hip: joint angles -> poses, one lane per frame.
 uint32_t fk_lds_bytes(const SkeletonConsts& sk);

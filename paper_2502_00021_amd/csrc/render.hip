@@ -31,6 +31,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include "arith.h"
 #include "pxr_internal.h"
 
 namespace pxr {
@@ -122,7 +123,7 @@ __device__ __forceinline__ void raster_rows(const TriSetup& s, uint32_t tri, uin
     const int dx_bc = s.cx - s.bx, dy_bc = s.cy - s.by;
     const int dx_ca = s.ax - s.cx, dy_ca = s.ay - s.cy;
     const I A2 = emul<I>(dx_ab, s.cy - s.ay) - emul<I>(dy_ab, s.cx - s.ax);
-    const float invA = 1.0f / (float)A2;
+    const float invA = recip_in_range((float)A2);  // a front face: 1 <= A2 < 2^47
     const I b_ab = edge_bias(dx_ab, dy_ab), b_bc = edge_bias(dx_bc, dy_bc), b_ca = edge_bias(dx_ca, dy_ca);
     const int px0 = (s.i0 << 8) + 128, py = (j << 8) + 128;
     I f_ab = emul<I>(dx_ab, py - s.ay) - emul<I>(dy_ab, px0 - s.ax) + b_ab;
@@ -275,8 +276,8 @@ __device__ __forceinline__ void raster_clipped(const SceneConsts& sc, uint32_t t
                 const float sy = __builtin_fmaf(-sc.f, iy * inv, sc.halfH);
                 const bool ok = (__builtin_fabsf(sx) <= 16384.0f) && (__builtin_fabsf(sy) <= 16384.0f);
                 usable = usable && ok;
-                cX[c] = ok ? (int)__builtin_floorf(__builtin_fmaf(sx, 256.0f, 0.5f)) : 0;
-                cY[c] = ok ? (int)__builtin_floorf(__builtin_fmaf(sy, 256.0f, 0.5f)) : 0;
+                cX[c] = ok ? floor_to_int(__builtin_fmaf(sx, 256.0f, 0.5f)) : 0;
+                cY[c] = ok ? floor_to_int(__builtin_fmaf(sy, 256.0f, 0.5f)) : 0;
                 cD[c] = sc.z_near * inv;
             }
         }
@@ -328,7 +329,7 @@ __device__ __forceinline__ uint32_t lanes_below(u64 m) {
 }
 
 __device__ __forceinline__ uint32_t quantise(float c) {
-    return (uint32_t)(int)__builtin_floorf(__builtin_fmaf(c, 255.0f, 0.5f)) & 0xFFu;
+    return (uint32_t)floor_to_int(__builtin_fmaf(c, 255.0f, 0.5f)) & 0xFFu;
 }
 
 // ---------------------------------------------------------------- the kernel
@@ -446,18 +447,18 @@ __device__ __forceinline__ uint32_t resolve_pixel(const SceneConsts& sc, const R
 // horizontal) so is the whole ground test, which then costs one division per lane, not four.
 template <int NT, bool UNIT_CELL, bool NO_ROLL>
 __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const ResolveCtx& rc, const float* body,
-                                              const float* cxcy, u64* keys, uint8_t* out, uint32_t* out_ids,
-                                              uint32_t tid, uint32_t p_begin, uint32_t p_end) {
+                                              const float* cxcy, const float4* rows, u64* keys, uint8_t* out,
+                                              uint32_t* out_ids, uint32_t tid, uint32_t p_begin, uint32_t p_end) {
     // pixels [p_begin, p_end) of the frame; keys[0] belongs to pixel p_begin
     const uint32_t lane = tid & 63u;
     for (uint32_t q = (p_begin >> 2) + tid; q * 4 < p_end; q += NT) {
         const uint32_t p0 = q * 4;
         const uint32_t j = __umulhi(p0, sc.magicW);
         const uint32_t i0 = p0 - j * sc.W;
-        const float cyj = cxcy[sc.W + j];
-        const float rx = __builtin_fmaf(sc.Up[0], cyj, sc.Fw[0]);
-        const float ry = __builtin_fmaf(sc.Up[1], cyj, sc.Fw[1]);
-        const float rz = __builtin_fmaf(sc.Up[2], cyj, sc.Fw[2]);
+        // what is shared by a row's pixels was worked out once per row in phase 0
+        const float4 row = rows[j];
+        const float rx = row.x, ry = row.y;
+        const float rz = NO_ROLL ? 0.0f : row.z;
         const float4 cx4 = *reinterpret_cast<const float4*>(cxcy + i0);
         const float cxs[4] = {cx4.x, cx4.y, cx4.z, cx4.w};
         uint32_t vid[3] = {0u, 0u, 0u};
@@ -469,9 +470,9 @@ __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const Resol
         }
         const uint32_t vb[4] = {vid[0] & 0xFFFFFFu, (vid[0] >> 24) | ((vid[1] & 0xFFFFu) << 8),
                                 (vid[1] >> 16) | ((vid[2] & 0xFFu) << 16), vid[2] >> 8};
-        float tg_row = 0.0f;
-        u64 gkey_row = 0ull;
-        if (NO_ROLL) gkey_row = ground_key(sc, rc, -rz, tg_row);  // fma(+-0, cx, rz) == rz
+        // without roll the ground test is the row's: ray parameter (0 = miss) and depth bits from the row table
+        const float tg_row = NO_ROLL ? row.z : 0.0f;
+        const u64 gkey_row = (NO_ROLL && tg_row != 0.0f) ? (((u64)__float_as_uint(row.w) << 32) | 1ull) : 0ull;
         uint32_t rgb[4], low[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -535,6 +536,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     float* vd = reinterpret_cast<float*>(lds + sc.lds_vd);
     float* body = reinterpret_cast<float*>(lds + sc.lds_body);
     float* cxcy = reinterpret_cast<float*>(lds + sc.lds_cxcy);
+    float4* rows = reinterpret_cast<float4*>(lds + sc.lds_rows);
     FrameUniforms* fu = reinterpret_cast<FrameUniforms*>(lds + sc.lds_misc);
     uint16_t* list = reinterpret_cast<uint16_t*>(lds + sc.lds_list);    // tiny bin grows up, small bin grows down
     uint16_t* list2 = reinterpret_cast<uint16_t*>(lds + sc.lds_large);  // mid bin grows up, large bin grows down
@@ -586,6 +588,34 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         for (int c = 0; c < 4; ++c) o[16 + c] = shp[c];
 #pragma unroll
         for (int c = 0; c < 3; ++c) o[20 + c] = sc.body_const[tid * 8 + 4 + c];
+    }
+    if (tid >= 64u) {
+        // The second wavefront on: one lane per image row prepares what all pixels of the row share: the row
+        // part of the ray, and - when the camera does not roll, so that the ray's z does not depend on the
+        // column (fma(+-0, cx, rz) == rz) - the whole ground test with its division.
+        //   rows[j] = (rx, ry, tg or 0 for a miss, depth bits)   without roll
+        //   rows[j] = (rx, ry, rz, -)                            with roll
+        const bool no_roll = sc.Rt[2] == 0.0f;
+        ResolveCtx g;
+        g.eye_z = eye_z;
+        g.inv_ez = 1.0f / eye_z;
+        g.ground_ok = sc.ground_on && eye_z > 0.0f;
+        for (uint32_t j = tid - 64u; j < sc.H; j += NT - 64u) {
+            const float cyj = sc.cxcy[sc.W + j];
+            const float rz = __builtin_fmaf(sc.Up[2], cyj, sc.Fw[2]);
+            float4 r;
+            r.x = __builtin_fmaf(sc.Up[0], cyj, sc.Fw[0]);
+            r.y = __builtin_fmaf(sc.Up[1], cyj, sc.Fw[1]);
+            r.z = rz;
+            r.w = 0.0f;
+            if (no_roll) {
+                float tg;
+                const u64 key = ground_key(sc, g, -rz, tg);
+                r.z = key ? tg : 0.0f;  // (a hit has tg >= z_near > 0)
+                r.w = __uint_as_float((uint32_t)(key >> 32));
+            }
+            rows[j] = r;
+        }
     }
     if (tid == NT - 1) {  // a lane of the last wave: the first wave is busy with the bodies
         fu->bins = 0ull;
@@ -648,18 +678,25 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     PXR_PHASE_MARK(0);
 
     // ---- phase 1: instancing + projection + snap + cell code (one lane per template vertex)
+    const bool recip_long_form = !(sc.z_near >= kRecipMin);
     for (uint32_t v = tid; v < sc.V; v += NT) {
         float pvx, pvy, pvz;
         view_position(sc, body, v, pvx, pvy, pvz);
-        const float inv = 1.0f / pvz;
+        // 1 / pvz is only used when pvz >= z_near (otherwise the vertex is behind the plane or unusable
+        // whatever it is), so the short form serves unless some lane's depth is beyond its range
+        float inv;
+        if (__builtin_expect(recip_long_form || __ballot(pvz > kRecipMax) != 0ull, 0))
+            inv = 1.0f / pvz;
+        else
+            inv = recip_in_range(pvz);
         const float sx = __builtin_fmaf(sc.f, pvx * inv, sc.halfW);
         const float sy = __builtin_fmaf(-sc.f, pvy * inv, sc.halfH);
         const bool ok = (pvz >= sc.z_near) && (__builtin_fabsf(sx) <= 16384.0f) && (__builtin_fabsf(sy) <= 16384.0f);
         int X = pvz < sc.z_near ? kBehindX : kRejectedX, Y = 0;
         uint32_t m = 0xFFFFFFFFu;  // an unusable or clipped vertex never lets a triangle be discarded early
         if (ok) {
-            X = (int)__builtin_floorf(__builtin_fmaf(sx, 256.0f, 0.5f));
-            Y = (int)__builtin_floorf(__builtin_fmaf(sy, 256.0f, 0.5f));
+            X = floor_to_int(__builtin_fmaf(sx, 256.0f, 0.5f));
+            Y = floor_to_int(__builtin_fmaf(sy, 256.0f, 0.5f));
             m = cell_code(X, (int)sc.W) | (cell_code(Y, (int)sc.H) << 16);
         }
         vx[v] = X;
@@ -754,7 +791,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         if (row_lo) __syncthreads();  // the previous band's keys have been resolved
 
         // codes and candidates are dead: clear the pixel keys they shared LDS with (0 = background at depth 0)
-        for (uint32_t p = tid; p < p_end - p_begin; p += NT) keys[p] = 0ull;
+        // (two keys per store; the region is padded to 16 bytes, so an odd count may clear one key more)
+        for (uint32_t p = tid; p < (p_end - p_begin + 1u) >> 1; p += NT)
+            reinterpret_cast<uint4*>(keys)[p] = make_uint4(0u, 0u, 0u, 0u);
         __syncthreads();
         PXR_PHASE_MARK(4);
 
@@ -782,7 +821,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         rc.eye_x = eye_x;
         rc.eye_y = eye_y;
         rc.eye_z = eye_z;
-        rc.inv_ez = 1.0f / eye_z;
+        const bool no_roll = sc.Rt[2] == 0.0f;
+        rc.inv_ez = (PX == 4 && no_roll) ? 0.0f : 1.0f / eye_z;  // (the row table already holds the ground test)
         rc.ground_ok = sc.ground_on && eye_z > 0.0f;
         rc.mode = dc.mode;
         rc.alpha = dc.alpha;
@@ -799,17 +839,16 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         uint32_t* out_ids = ids ? ids + (size_t)frame * sc.npix : nullptr;
         if (PX == 4) {
             // uniform scene properties select a specialised loop (kept out of the per-pixel code)
-            const bool no_roll = sc.Rt[2] == 0.0f;
             if (sc.cell_is_one) {
                 if (no_roll)
-                    resolve_rows4<NT, true, true>(sc, rc, body, cxcy, keys, out, out_ids, tid, p_begin, p_end);
+                    resolve_rows4<NT, true, true>(sc, rc, body, cxcy, rows, keys, out, out_ids, tid, p_begin, p_end);
                 else
-                    resolve_rows4<NT, true, false>(sc, rc, body, cxcy, keys, out, out_ids, tid, p_begin, p_end);
+                    resolve_rows4<NT, true, false>(sc, rc, body, cxcy, rows, keys, out, out_ids, tid, p_begin, p_end);
             } else {
                 if (no_roll)
-                    resolve_rows4<NT, false, true>(sc, rc, body, cxcy, keys, out, out_ids, tid, p_begin, p_end);
+                    resolve_rows4<NT, false, true>(sc, rc, body, cxcy, rows, keys, out, out_ids, tid, p_begin, p_end);
                 else
-                    resolve_rows4<NT, false, false>(sc, rc, body, cxcy, keys, out, out_ids, tid, p_begin, p_end);
+                    resolve_rows4<NT, false, false>(sc, rc, body, cxcy, rows, keys, out, out_ids, tid, p_begin, p_end);
             }
         } else {
             // any image shape: one pixel per lane, byte stores

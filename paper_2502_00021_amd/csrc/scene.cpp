@@ -450,6 +450,8 @@ int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
         o += align(std::max(c.band_rows * c.W * 8, c.V * 4 + c.T * 2), 16);
         c.lds_cxcy = o;
         o += align((c.W + c.H) * 4, 16);
+        c.lds_rows = o;  // float4 per image row
+        o += c.H * 16;
         c.lds_misc = o;
         o += 64 * 4;
         c.lds_body = o;

@@ -90,6 +90,8 @@ def lib():
         L.pxr_conv_set_tuning.argtypes = [vp, u32, u32]
         for name in ("pxr_conv_create", "pxr_conv_destroy", "pxr_conv_forward", "pxr_conv_info", "pxr_conv_set_tuning"):
             getattr(L, name).restype = C.c_int
+        L.pxr_selftest_arithmetic.argtypes = [vp]
+        L.pxr_selftest_arithmetic.restype = C.c_int
         L.pxr_measure_peaks.argtypes = [vp, vp, vp, vp, vp]
         L.pxr_measure_peaks.restype = C.c_int
         L.pxr_last_error.restype = C.c_char_p
@@ -401,6 +403,13 @@ def make_skeleton_desc(skel, n_free, n_angles):
     d.parent, d.slot = parent.ctypes.data, slot.ctypes.data
     d.anchor, d.axis, d.offset = (a.ctypes.data for a in arrs)
     return d, [parent, slot] + arrs
+
+
+def selftest_arithmetic():
+    """pxr_selftest_arithmetic: dict(recip_mismatches, floor_mismatches, recip_checked, floor_checked) on the current device."""
+    c = (C.c_uint64 * 4)()
+    _check(lib().pxr_selftest_arithmetic(c))
+    return dict(recip_mismatches=int(c[0]), floor_mismatches=int(c[1]), recip_checked=int(c[2]), floor_checked=int(c[3]))
 
 
 def measure_peaks():
