@@ -335,23 +335,33 @@ __device__ __forceinline__ uint32_t quantise(float c) {
 // ---------------------------------------------------------------- the kernel
 
 #ifdef PXR_PHASE_TIMING
-// Profiling build only: lane 0 of every workgroup adds the shader-clock span of each phase.
-__device__ unsigned long long g_phase_cycles[8];
-#define PXR_PHASE_BEGIN() unsigned long long phase_t0 = clock64()
-#define PXR_PHASE_MARK(i)                                         \
-    if (tid == 0) {                                               \
-        const unsigned long long now = clock64();                 \
-        atomicAdd(&g_phase_cycles[i], now - phase_t0);            \
-        phase_t0 = now;                                           \
+// Profiling build only: the first wavefront of every workgroup notes the clock at each phase boundary (in
+// registers) and lane 0 adds the spans to global counters when the kernel ends (1024 sets of counters: one
+// shared set would serialise the kernel's tail).
+__device__ unsigned long long g_phase_cycles[1024 * 8];
+#define PXR_PHASE_BEGIN()                      \
+    unsigned long long phase_span[8] = {0};    \
+    unsigned long long phase_t0 = __builtin_readcyclecounter()
+#define PXR_PHASE_MARK(i)                                                \
+    {                                                                    \
+        const unsigned long long now = __builtin_readcyclecounter();    \
+        phase_span[i] += now - phase_t0;                                 \
+        phase_t0 = now;                                                  \
+    }
+#define PXR_PHASE_END()                                                                                      \
+    if (tid == 0) {                                                                                          \
+        for (int i = 0; i < 7; ++i) atomicAdd(&g_phase_cycles[(blockIdx.x & 1023u) * 8u + i], phase_span[i]); \
     }
 #elif defined(PXR_STOP_AFTER)
 // Profiling build only: the kernel ends after phase PXR_STOP_AFTER (counter deltas give per-phase cost).
 #define PXR_PHASE_BEGIN()
 #define PXR_PHASE_MARK(i) \
     if ((i) == PXR_STOP_AFTER) return
+#define PXR_PHASE_END()
 #else
 #define PXR_PHASE_BEGIN()
 #define PXR_PHASE_MARK(i)
+#define PXR_PHASE_END()
 #endif
 
 struct FrameUniforms {  // written in phase 0 (one lane) or by LDS atomics, read by all after a barrier
@@ -877,6 +887,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         row_lo += sc.band_rows;
     } while (BANDED && row_lo < sc.H);
     PXR_PHASE_MARK(6);
+    PXR_PHASE_END();
 }
 
 template <int NT, int PX, bool BANDED>
@@ -916,10 +927,16 @@ int prepare_all(uint32_t cap, std::string& err) {
 
 #ifdef PXR_PHASE_TIMING
 extern "C" int pxr_debug_phase_cycles(unsigned long long* out, int reset) {
-    if (out && hipMemcpyFromSymbol(out, HIP_SYMBOL(g_phase_cycles), sizeof(g_phase_cycles)) != hipSuccess) return 1;
+    static unsigned long long host[1024 * 8];
+    if (out) {
+        if (hipMemcpyFromSymbol(host, HIP_SYMBOL(g_phase_cycles), sizeof(host)) != hipSuccess) return 1;
+        for (int i = 0; i < 8; ++i) out[i] = 0;
+        for (int k = 0; k < 1024; ++k)
+            for (int i = 0; i < 8; ++i) out[i] += host[k * 8 + i];
+    }
     if (reset) {
-        unsigned long long zero[8] = {0};
-        if (hipMemcpyToSymbol(HIP_SYMBOL(g_phase_cycles), zero, sizeof(zero)) != hipSuccess) return 1;
+        for (auto& h : host) h = 0;
+        if (hipMemcpyToSymbol(HIP_SYMBOL(g_phase_cycles), host, sizeof(host)) != hipSuccess) return 1;
     }
     return 0;
 }
