@@ -18,24 +18,24 @@ constexpr int32_t kRejectedX = INT32_MIN;
 // raster phase.  (Snapped coordinates stay within +-2^22, so both sentinels sort below every real one.)
 constexpr int32_t kBehindX = INT32_MIN + 1;
 
-// Raster bins by the number of pixel centres in a surviving triangle's clamped
-// bounding box (both fixed-point extents must also be below 2^15):
-//   tiny  <= kTinyMaxPixels   one lane, at most two loop trips
-//   small <= kSmallMaxPixels  one lane
-//   mid   <= kMidMaxPixels    eight lanes, rows dealt round-robin
-//   large otherwise           a whole wavefront, one row per lane
+// Raster bins by the number of pixel centres in a surviving triangle's clamped bounding box:
+//   tiny  <= kTinyMaxPixels   one lane
+//   small <= kSmallMaxPixels  a team of 2^kSmallLanesLog2 lanes, rows dealt round-robin
+//   large otherwise           a whole wavefront, one row per lane (also: triangles to be clipped)
+// What is balanced here is the longest chain in the raster phase, not the instruction count: one lane
+// walking a 12-pixel triangle holds up its whole workgroup at the next barrier.
 #ifndef PXR_TINY_MAX
-#define PXR_TINY_MAX 2
+#define PXR_TINY_MAX 3
 #endif
 #ifndef PXR_SMALL_MAX
-#define PXR_SMALL_MAX 12
+#define PXR_SMALL_MAX 128
 #endif
-#ifndef PXR_MID_MAX
-#define PXR_MID_MAX 96
+#ifndef PXR_SMALL_LANES_LOG2
+#define PXR_SMALL_LANES_LOG2 2
 #endif
 constexpr uint32_t kTinyMaxPixels = PXR_TINY_MAX;
 constexpr uint32_t kSmallMaxPixels = PXR_SMALL_MAX;
-constexpr uint32_t kMidMaxPixels = PXR_MID_MAX;
+constexpr uint32_t kSmallLanesLog2 = PXR_SMALL_LANES_LOG2;
 constexpr uint32_t kNoTriangle = 0xFFFFu;
 
 // Per-body record kept in LDS for the duration of one frame (floats).

@@ -17,8 +17,8 @@
 //      its bounding box can hold a pixel centre; candidates are compacted
 //      wave-wide (ballot + mbcnt) into a list in LDS
 //   2b binning, exact: one lane per candidate: exact area sign, pixel range,
-//      then compaction into four bins by candidate-pixel count
-//   3  raster: bins are walked by 1, 1, 8 or 64 lanes per triangle (rows are
+//      then compaction into three bins by candidate-pixel count
+//   3  raster: bins are walked by 1, 4 or 64 lanes per triangle (rows are
 //      dealt round-robin to a triangle's lanes); integer edge functions,
 //      top-left rule, float reversed depth, 64-bit LDS atomic max on
 //      (depth bits << 32 | ~triangle id)
@@ -365,7 +365,7 @@ __device__ unsigned long long g_phase_cycles[1024 * 8];
 #endif
 
 struct FrameUniforms {  // written in phase 0 (one lane) or by LDS atomics, read by all after a barrier
-    u64 bins;           // four 16-bit counters: tiny | small << 16 | mid << 32 | large << 48
+    u64 bins;           // three 16-bit counters: tiny | small << 16 | large << 32
     uint32_t n_cand;
     uint32_t video_frame;
     float scale[3], offs[3];
@@ -549,7 +549,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     float4* rows = reinterpret_cast<float4*>(lds + sc.lds_rows);
     FrameUniforms* fu = reinterpret_cast<FrameUniforms*>(lds + sc.lds_misc);
     uint16_t* list = reinterpret_cast<uint16_t*>(lds + sc.lds_list);    // tiny bin grows up, small bin grows down
-    uint16_t* list2 = reinterpret_cast<uint16_t*>(lds + sc.lds_large);  // mid bin grows up, large bin grows down
+    uint16_t* list2 = reinterpret_cast<uint16_t*>(lds + sc.lds_large);  // large bin
 
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & 63u;
@@ -749,11 +749,11 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     PXR_PHASE_MARK(2);
 
     // ---- phase 2b: exact binning, one lane per candidate triangle: reject, area sign, pixel range,
-    // then one of four bins by the number of candidate pixel centres (one packed LDS atomic per wave).
+    // then one of three bins by the number of candidate pixel centres (one packed LDS atomic per wave).
     const uint32_t n_cand = fu->n_cand;
     for (uint32_t k0 = 0; k0 < n_cand; k0 += NT) {
         const uint32_t k = k0 + tid;
-        int cls = 0;  // 0 none, 1 tiny, 2 small, 3 mid, 4 large
+        int cls = 0;  // 0 none, 1 tiny, 2 small, 3 large
         uint32_t t = 0;
         if (k < n_cand) {
             t = cand[k];
@@ -761,7 +761,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
             uint32_t v0, v1, v2;
             bool small_extent;
             const int kind = tri_gather(sc, t, vx, vy, s, v0, v1, v2, small_extent);
-            if (kind == kTriClip) cls = 4;  // clipped, then rastered, by a whole wavefront
+            if (kind == kTriClip) cls = 3;  // clipped, then rastered, by a whole wavefront
             if (kind == kTriPlain) {
                 bool front;
                 if (small_extent)
@@ -771,22 +771,20 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
                             (long long)(s.by - s.ay) * (long long)(s.cx - s.ax);
                 if (front) {
                     const uint32_t npx = (uint32_t)((s.i1 - s.i0 + 1) * (s.j1 - s.j0 + 1));
-                    cls = npx <= kTinyMaxPixels ? 1 : (npx <= kSmallMaxPixels ? 2 : (npx <= kMidMaxPixels ? 3 : 4));
+                    cls = npx <= kTinyMaxPixels ? 1 : (npx <= kSmallMaxPixels ? 2 : 3);
                 }
             }
         }
-        const u64 m1 = __ballot(cls == 1), m2 = __ballot(cls == 2), m3 = __ballot(cls == 3), m4 = __ballot(cls == 4);
-        if (m1 | m2 | m3 | m4) {
+        const u64 m1 = __ballot(cls == 1), m2 = __ballot(cls == 2), m3 = __ballot(cls == 3);
+        if (m1 | m2 | m3) {
             u64 old = 0;
             if (lane == 0)
-                old = atomicAdd(&fu->bins, (u64)__popcll(m1) | ((u64)__popcll(m2) << 16) | ((u64)__popcll(m3) << 32) |
-                                               ((u64)__popcll(m4) << 48));
+                old = atomicAdd(&fu->bins, (u64)__popcll(m1) | ((u64)__popcll(m2) << 16) | ((u64)__popcll(m3) << 32));
             const uint32_t old_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)old);
             const uint32_t old_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(old >> 32));
             if (cls == 1) list[(old_lo & 0xFFFFu) + lanes_below(m1)] = (uint16_t)t;
             if (cls == 2) list[sc.T - 1 - ((old_lo >> 16) + lanes_below(m2))] = (uint16_t)t;
-            if (cls == 3) list2[(old_hi & 0xFFFFu) + lanes_below(m3)] = (uint16_t)t;
-            if (cls == 4) list2[sc.T - 1 - ((old_hi >> 16) + lanes_below(m4))] = (uint16_t)t;
+            if (cls == 3) list2[old_hi + lanes_below(m3)] = (uint16_t)t;
         }
     }
     __syncthreads();
@@ -810,19 +808,19 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         // ---- phase 3: raster + z-test into the LDS key buffer.  The bins start at different
         // lanes of the workgroup so that all waves get a share.
         const u64 bins = fu->bins;
-        const uint32_t n_tiny = (uint32_t)bins & 0xFFFFu, n_small = ((uint32_t)bins >> 16);
-        const uint32_t n_mid = (uint32_t)(bins >> 32) & 0xFFFFu, n_large = (uint32_t)(bins >> 48);
+        const uint32_t n_tiny = (uint32_t)bins & 0xFFFFu, n_small = (uint32_t)bins >> 16, n_large = (uint32_t)(bins >> 32);
 
+        // tiny: one lane per triangle, from the first lane up
         for (uint32_t k = tid; k < n_tiny; k += NT)
             raster_binned<false>(sc, list[k], body, vx, vy, vd, keys, 0, 0, (int)row_lo, (int)row_hi);
-        for (uint32_t k = NT - 1 - tid; k < n_small; k += NT)
-            raster_binned<false>(sc, list[sc.T - 1 - k], body, vx, vy, vd, keys, 0, 0, (int)row_lo, (int)row_hi);
-        // mid: 8 lanes per triangle, starting in the middle waves
-        for (uint32_t k = ((tid >> 3) + NT / 16) % (NT / 8); k < n_mid; k += NT / 8)
-            raster_binned<false>(sc, list2[k], body, vx, vy, vd, keys, (int)(tid & 7u), 3, (int)row_lo, (int)row_hi);
-        // large: a whole wave per triangle
+        // small: a team of lanes per triangle, from the last lane down
+        constexpr uint32_t kTeam = 1u << kSmallLanesLog2;
+        for (uint32_t k = (NT - 1 - tid) >> kSmallLanesLog2; k < n_small; k += NT >> kSmallLanesLog2)
+            raster_binned<false>(sc, list[sc.T - 1 - k], body, vx, vy, vd, keys, (int)(tid & (kTeam - 1u)), (int)kSmallLanesLog2,
+                                 (int)row_lo, (int)row_hi);
+        // large: a whole wave per triangle, starting in the middle waves
         for (uint32_t k = ((tid >> 6) + NT / 128) % (NT / 64); k < n_large; k += NT / 64)
-            raster_binned<true>(sc, list2[sc.T - 1 - k], body, vx, vy, vd, keys, (int)lane, 6, (int)row_lo, (int)row_hi);
+            raster_binned<true>(sc, list2[k], body, vx, vy, vd, keys, (int)lane, 6, (int)row_lo, (int)row_hi);
         __syncthreads();
         PXR_PHASE_MARK(5);
 
