@@ -71,7 +71,7 @@ struct SceneConsts {
     const float* cxcy;        // [W+H]   pixel-centre ray slopes
     // LDS carve-up (byte offsets into the dynamic segment)
     // the lds_keys region first holds the per-vertex cell codes (u32[V]) and the candidate list (u16[T])
-    uint32_t lds_keys, lds_vx, lds_vy, lds_vd, lds_body, lds_list, lds_large, lds_cxcy, lds_rows, lds_misc, lds_total;
+    uint32_t lds_keys, lds_vxy, lds_vd, lds_body, lds_list, lds_large, lds_cxcy, lds_rows, lds_misc, lds_total;
 };
 
 // Distractor state bound by pxr_apply_distractor.

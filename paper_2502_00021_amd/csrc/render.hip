@@ -156,23 +156,24 @@ __device__ __forceinline__ void raster_rows(const TriSetup& s, uint32_t tri, uin
 // inside the bounding box; kTriClip if the triangle straddles the near plane (nothing else is valid
 // then); kTriPlain otherwise.  `small_extent` = both fixed-point extents below 2^15.
 enum { kTriNone = 0, kTriPlain = 1, kTriClip = 2 };
-__device__ __forceinline__ int tri_gather(const SceneConsts& sc, uint32_t t, const int* vx, const int* vy, TriSetup& s,
+__device__ __forceinline__ int tri_gather(const SceneConsts& sc, uint32_t t, const int2* vxy, TriSetup& s,
                                           uint32_t& v0, uint32_t& v1, uint32_t& v2, bool& small_extent) {
     const uint2 ti = reinterpret_cast<const uint2*>(sc.tri_idx)[t];
     v0 = ti.x & 0xFFFFu;
     v1 = ti.x >> 16;
     v2 = ti.y & 0xFFFFu;
-    s.ax = vx[v0];
-    s.bx = vx[v2];
-    s.cx = vx[v1];
+    const int2 a = vxy[v0], b = vxy[v2], c = vxy[v1];  // (x, y) pairs: one LDS read per vertex
+    s.ax = a.x;
+    s.bx = b.x;
+    s.cx = c.x;
     const int minx = imin3(s.ax, s.bx, s.cx), maxx = imax3(s.ax, s.bx, s.cx);
     if (minx <= kBehindX) {  // a sentinel among the three (rare)
         if (minx == kRejectedX) return kTriNone;
         return maxx == kBehindX ? kTriNone : kTriClip;
     }
-    s.ay = vy[v0];
-    s.by = vy[v2];
-    s.cy = vy[v1];
+    s.ay = a.y;
+    s.by = b.y;
+    s.cy = c.y;
     const int miny = imin3(s.ay, s.by, s.cy), maxy = imax3(s.ay, s.by, s.cy);
     // pixel centres sit at 256 i + 128: first centre >= min, last centre <= max
     s.i0 = max(0, (minx + 127) >> 8);
@@ -234,14 +235,14 @@ __device__ __forceinline__ void raster_piece(const SceneConsts& sc, uint32_t t, 
 // code per corner (P << 2 | Q, P == Q for a kept vertex), four corners per pattern, patterns indexed by
 // the in-front mask (bit e = vertex e in front).  Corners are recomputed per piece rather than kept, so
 // that this rarely taken path does not raise the kernel's register count.
-__device__ __forceinline__ void raster_clipped(const SceneConsts& sc, uint32_t t, const float* body, const int* vx, const int* vy,
+__device__ __forceinline__ void raster_clipped(const SceneConsts& sc, uint32_t t, const float* body, const int2* vxy,
                                                const float* vd, u64* keys, int lane, int row_lo, int row_hi) {
 #pragma unroll 1
     for (uint32_t piece = 0; piece < 2u; ++piece) {
         // everything is re-derived per piece so that nothing but `t` stays live across the raster loops
         const uint2 ti = reinterpret_cast<const uint2*>(sc.tri_idx)[t];
         const uint32_t v0 = ti.x & 0xFFFFu, v1 = ti.x >> 16, v2 = ti.y & 0xFFFFu;
-        const uint32_t mask = (vx[v0] != kBehindX ? 1u : 0u) | (vx[v1] != kBehindX ? 2u : 0u) | (vx[v2] != kBehindX ? 4u : 0u);
+        const uint32_t mask = (vxy[v0].x != kBehindX ? 1u : 0u) | (vxy[v1].x != kBehindX ? 2u : 0u) | (vxy[v2].x != kBehindX ? 4u : 0u);
         // corners k = 0..3 in bits 4k..4k+3; V_e = e<<2|e, I_pq = p<<2|q
         //   001: V0 I01 I02      010: I10 V1 I12      100: I21 V2 I20
         //   011: V0 V1 I12 I02   110: I10 V1 V2 I20   101: V0 I01 I21 V2
@@ -260,8 +261,8 @@ __device__ __forceinline__ void raster_clipped(const SceneConsts& sc, uint32_t t
             const uint32_t p = code >> 2, q = code & 3u;
             const uint32_t vp = p == 0 ? v0 : (p == 1 ? v1 : v2), vq = q == 0 ? v0 : (q == 1 ? v1 : v2);
             if (p == q) {
-                cX[c] = vx[vp];
-                cY[c] = vy[vp];
+                cX[c] = vxy[vp].x;
+                cY[c] = vxy[vp].y;
                 cD[c] = vd[vp];
             } else {
                 float px, py, pz, qx, qy, qz;
@@ -289,15 +290,15 @@ __device__ __forceinline__ void raster_clipped(const SceneConsts& sc, uint32_t t
 // the rows [row_lo, row_hi) that the key buffer currently holds.
 // MAY_CLIP: the bin (the wave-per-triangle one) also holds the triangles that straddle the near plane.
 template <bool MAY_CLIP>
-__device__ __forceinline__ void raster_binned(const SceneConsts& sc, uint32_t t, const float* body, const int* vx,
-                                              const int* vy, const float* vd, u64* keys, int r, int shift, int row_lo,
+__device__ __forceinline__ void raster_binned(const SceneConsts& sc, uint32_t t, const float* body, const int2* vxy,
+                                              const float* vd, u64* keys, int r, int shift, int row_lo,
                                               int row_hi) {
     TriSetup s;
     uint32_t v0, v1, v2;
     bool small_extent;
-    const int kind = tri_gather(sc, t, vx, vy, s, v0, v1, v2, small_extent);
+    const int kind = tri_gather(sc, t, vxy, s, v0, v1, v2, small_extent);
     if (MAY_CLIP && kind == kTriClip) {
-        raster_clipped(sc, t, body, vx, vy, vd, keys, r, row_lo, row_hi);
+        raster_clipped(sc, t, body, vxy, vd, keys, r, row_lo, row_hi);
         return;
     }
     s.j0 = max(s.j0, row_lo);
@@ -541,8 +542,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     // the key buffer's LDS holds the cell codes and the candidate list until the keys are cleared
     uint32_t* vm = reinterpret_cast<uint32_t*>(lds + sc.lds_keys);
     uint16_t* cand = reinterpret_cast<uint16_t*>(lds + sc.lds_keys + sc.V * 4);
-    int* vx = reinterpret_cast<int*>(lds + sc.lds_vx);
-    int* vy = reinterpret_cast<int*>(lds + sc.lds_vy);
+    int2* vxy = reinterpret_cast<int2*>(lds + sc.lds_vxy);
     float* vd = reinterpret_cast<float*>(lds + sc.lds_vd);
     float* body = reinterpret_cast<float*>(lds + sc.lds_body);
     float* cxcy = reinterpret_cast<float*>(lds + sc.lds_cxcy);
@@ -627,18 +627,30 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
             rows[j] = r;
         }
     }
+    if (tid >= NT - 2 && dc.mode == PXR_DISTRACT_COLOR) {
+        // The colour draws are two generator streams, the longest serial chain of this phase: the last two
+        // lanes walk one stream each, side by side; the offsets go through LDS to the last lane.
+        const uint32_t stream = (NT - 1) - tid;
+        uint32_t r[4];
+        counter_rng(dc.seed_lo, dc.seed_hi, env, step, stream, 0u, r);
+        const float span = stream == 0u ? dc.scale_span : dc.offset_span, lo = stream == 0u ? dc.scale_lo : dc.offset_lo;
+        float* dst = stream == 0u ? fu->scale : fu->offs;
+#pragma unroll
+        for (int c = 0; c < 3; ++c) dst[c] = __builtin_fmaf(unit_float(r[c]), span, lo);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
     if (tid == NT - 1) {  // a lane of the last wave: the first wave is busy with the bodies
         fu->bins = 0ull;
         fu->n_cand = 0;
         float scale[3] = {1.0f, 1.0f, 1.0f}, offs[3] = {0.0f, 0.0f, 0.0f};
         if (dc.mode == PXR_DISTRACT_COLOR) {
-            uint32_t r[4];
-            counter_rng(dc.seed_lo, dc.seed_hi, env, step, 0u, 0u, r);
 #pragma unroll
-            for (int c = 0; c < 3; ++c) scale[c] = __builtin_fmaf(unit_float(r[c]), dc.scale_span, dc.scale_lo);
-            counter_rng(dc.seed_lo, dc.seed_hi, env, step, 1u, 0u, r);
-#pragma unroll
-            for (int c = 0; c < 3; ++c) offs[c] = __builtin_fmaf(unit_float(r[c]), dc.offset_span, dc.offset_lo);
+            for (int c = 0; c < 3; ++c) {
+                scale[c] = fu->scale[c];
+                offs[c] = fu->offs[c];
+            }
         } else if (dc.mode == PXR_DISTRACT_VIDEO) {
             uint32_t first;
             if (dc.env_offset) {
@@ -709,8 +721,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
             Y = floor_to_int(__builtin_fmaf(sy, 256.0f, 0.5f));
             m = cell_code(X, (int)sc.W) | (cell_code(Y, (int)sc.H) << 16);
         }
-        vx[v] = X;
-        vy[v] = Y;
+        vxy[v] = make_int2(X, Y);
         vd[v] = sc.z_near * inv;
         vm[v] = m;
     }
@@ -760,7 +771,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
             TriSetup s;
             uint32_t v0, v1, v2;
             bool small_extent;
-            const int kind = tri_gather(sc, t, vx, vy, s, v0, v1, v2, small_extent);
+            const int kind = tri_gather(sc, t, vxy, s, v0, v1, v2, small_extent);
             if (kind == kTriClip) cls = 3;  // clipped, then rastered, by a whole wavefront
             if (kind == kTriPlain) {
                 bool front;
@@ -812,15 +823,15 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
 
         // tiny: one lane per triangle, from the first lane up
         for (uint32_t k = tid; k < n_tiny; k += NT)
-            raster_binned<false>(sc, list[k], body, vx, vy, vd, keys, 0, 0, (int)row_lo, (int)row_hi);
+            raster_binned<false>(sc, list[k], body, vxy, vd, keys, 0, 0, (int)row_lo, (int)row_hi);
         // small: a team of lanes per triangle, from the last lane down
         constexpr uint32_t kTeam = 1u << kSmallLanesLog2;
         for (uint32_t k = (NT - 1 - tid) >> kSmallLanesLog2; k < n_small; k += NT >> kSmallLanesLog2)
-            raster_binned<false>(sc, list[sc.T - 1 - k], body, vx, vy, vd, keys, (int)(tid & (kTeam - 1u)), (int)kSmallLanesLog2,
+            raster_binned<false>(sc, list[sc.T - 1 - k], body, vxy, vd, keys, (int)(tid & (kTeam - 1u)), (int)kSmallLanesLog2,
                                  (int)row_lo, (int)row_hi);
         // large: a whole wave per triangle, starting in the middle waves
         for (uint32_t k = ((tid >> 6) + NT / 128) % (NT / 64); k < n_large; k += NT / 64)
-            raster_binned<true>(sc, list2[k], body, vx, vy, vd, keys, (int)lane, 6, (int)row_lo, (int)row_hi);
+            raster_binned<true>(sc, list2[k], body, vxy, vd, keys, (int)lane, 6, (int)row_lo, (int)row_hi);
         __syncthreads();
         PXR_PHASE_MARK(5);
 

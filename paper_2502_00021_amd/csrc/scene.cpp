@@ -456,10 +456,8 @@ int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
         o += 64 * 4;
         c.lds_body = o;
         o += c.K * kBodyStride * 4;
-        c.lds_vx = o;
-        o += c.V * 4;
-        c.lds_vy = o;
-        o += c.V * 4;
+        c.lds_vxy = o;  // (x, y) pairs: 8-byte aligned, as everything before it is a multiple of 16
+        o += c.V * 8;
         c.lds_vd = o;
         o += c.V * 4;
         c.lds_list = o;
