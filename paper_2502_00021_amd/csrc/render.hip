@@ -644,14 +644,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     if (tid == NT - 1) {  // a lane of the last wave: the first wave is busy with the bodies
         fu->bins = 0ull;
         fu->n_cand = 0;
-        float scale[3] = {1.0f, 1.0f, 1.0f}, offs[3] = {0.0f, 0.0f, 0.0f};
-        if (dc.mode == PXR_DISTRACT_COLOR) {
-#pragma unroll
-            for (int c = 0; c < 3; ++c) {
-                scale[c] = fu->scale[c];
-                offs[c] = fu->offs[c];
-            }
-        } else if (dc.mode == PXR_DISTRACT_VIDEO) {
+        if (dc.mode == PXR_DISTRACT_VIDEO) {
             uint32_t first;
             if (dc.env_offset) {
                 first = dc.env_offset[e];
@@ -672,28 +665,38 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
             }
             fu->video_frame = clip * dc.n_frames + (uint32_t)(((u64)first + (u64)step) % dc.n_frames);
         }
-        // Background and the two ground greys are the same for every pixel that shows them:
-        // run them through the colour distractor and the quantiser once per frame.
-#pragma unroll
-        for (int k = 0; k < 3; ++k) {
-            uint32_t packed = 0;
+    }
+    if (tid >= NT - 3) {
+        // Background and the two ground greys are the same for every pixel that shows them: they go through
+        // the colour distractor and the quantiser once per frame, one lane per colour.
+        const uint32_t k = (NT - 1) - tid;
+        float scale[3] = {1.0f, 1.0f, 1.0f}, offs[3] = {0.0f, 0.0f, 0.0f};
+        if (dc.mode == PXR_DISTRACT_COLOR) {
 #pragma unroll
             for (int c = 0; c < 3; ++c) {
-                float v = k == 0 ? sc.bg[c] : sc.gs[k - 1];
-                if (dc.mode == PXR_DISTRACT_COLOR) {
-                    v = __builtin_fmaf(v, scale[c], offs[c]);
-                    v = v > 0.0f ? v : 0.0f;
-                    v = v < 1.0f ? v : 1.0f;
-                }
-                fu->base_col[k][c] = v;
-                packed |= quantise(v) << (8 * c);
+                scale[c] = fu->scale[c];
+                offs[c] = fu->offs[c];
             }
-            fu->base_packed[k] = packed;
         }
+        uint32_t packed = 0;
 #pragma unroll
         for (int c = 0; c < 3; ++c) {
-            fu->scale[c] = scale[c];
-            fu->offs[c] = offs[c];
+            float v = k == 0u ? sc.bg[c] : (k == 1u ? sc.gs[0] : sc.gs[1]);
+            if (dc.mode == PXR_DISTRACT_COLOR) {
+                v = __builtin_fmaf(v, scale[c], offs[c]);
+                v = v > 0.0f ? v : 0.0f;
+                v = v < 1.0f ? v : 1.0f;
+            }
+            fu->base_col[k][c] = v;
+            packed |= quantise(v) << (8 * c);
+        }
+        fu->base_packed[k] = packed;
+        if (k == 0u && dc.mode != PXR_DISTRACT_COLOR) {
+#pragma unroll
+            for (int c = 0; c < 3; ++c) {
+                fu->scale[c] = 1.0f;
+                fu->offs[c] = 0.0f;
+            }
         }
     }
     __syncthreads();
