@@ -332,6 +332,15 @@ inline bool top_left(int64_t px, int64_t py, int64_t qx, int64_t qy) {
     int64_t dx = qx - px, dy = qy - py;
     return dy < 0 || (dy == 0 && dx > 0);
 }
+// float -> int32 for a value that may lie outside the int32 range.  C++ leaves that conversion undefined and the
+// paper says nothing of such inputs (a camera 3e9 m from the origin); defined here as saturating, NaN -> 0.
+inline int32_t to_int_saturating(float x) {
+    if (x != x) return 0;
+    if (x >= 2147483648.0f) return INT32_MAX;
+    if (x <= -2147483648.0f) return INT32_MIN;
+    return (int32_t)x;
+}
+
 inline int64_t floor_div(int64_t a, int64_t b) {  // b > 0
     int64_t q = a / b, r = a % b;
     return (r < 0) ? q - 1 : q;
@@ -720,7 +729,9 @@ int orc_render(const orc_scene* s, const float* poses, const float* shapes, uint
                     } else if (g == ORC_ID_GROUND) {
                         float wx = std::fmaf(tg, dwx, fx.eye[0]);
                         float wy = std::fmaf(tg, dwy, fx.eye[1]);
-                        int par = ((int)std::floor(wx / s->cell) + (int)std::floor(wy / s->cell)) & 1;
+                        // (the sum wraps: only its parity is used)
+                        int par = (int)(((uint32_t)to_int_saturating(std::floor(wx / s->cell)) +
+                                         (uint32_t)to_int_saturating(std::floor(wy / s->cell))) & 1u);
                         for (int ch = 0; ch < 3; ++ch) c[ch] = s->gs[par];
                     } else {
                         const uint32_t b = s->tbody[g];
@@ -747,7 +758,7 @@ int orc_render(const orc_scene* s, const float* poses, const float* shapes, uint
                         }
                     }
                     for (int ch = 0; ch < 3; ++ch)
-                        out[pix * 3 + ch] = (uint8_t)(int)std::floor(std::fmaf(c[ch], 255.0f, 0.5f));
+                        out[pix * 3 + ch] = (uint8_t)(uint32_t)to_int_saturating(std::floor(std::fmaf(c[ch], 255.0f, 0.5f)));
                 }
             if (ids) std::memcpy(ids + frame * npix, zb.id.data(), npix * 4);
             if (depth_bits) for (size_t p = 0; p < npix; ++p) depth_bits[frame * npix + p] = fbits(zb.depth[p]);

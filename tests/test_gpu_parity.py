@@ -379,9 +379,12 @@ def test_huge_offscreen_extents_use_64bit_edges(torch, pxr, orc):
 
 
 def test_rejected_and_degenerate_inputs(torch, pxr, orc):
-    w = wl.make(2, B=9)
+    w = wl.make(2, B=12)
     p = w["poses"].copy()
     p[8, 0, 0, 0] = np.nan         # non-finite root x: no usable vertex, ground cells decided by y alone
+    p[9, 0, 0, 0] = 3.0e9          # ground cell index beyond int32: the conversion saturates on both sides
+    p[10, 0, 0, 1] = -np.inf
+    p[11, 0, 0, :2] = (-7.0e9, 5.0e9)
     p[0, 0, :, 0] -= 10.0          # whole chain far behind the camera (root too: camera follows it) -> visible
     p[1, 0, 1:, 0] = -5.0          # links behind the camera: rejected
     p[2, 0, 3, :3] = np.nan        # non-finite position

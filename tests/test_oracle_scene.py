@@ -386,3 +386,27 @@ def test_ground_grey_levels(orc):
     lz = 0.85 / np.linalg.norm(desc["light_dir"])
     levels = {int(np.floor(255 * g * (0.3 + 0.7 * lz) + 0.5)) for g in desc["ground_grey"]}
     assert set(np.unique(fr[ids == GROUND])) == levels
+
+
+def test_ground_cell_index_beyond_int32_saturates(orc):
+    """A camera billions of metres from the origin puts the checker's cell index outside int32.  The
+    conversion is defined as saturating (NaN -> 0), so the x index is the same odd number for every such camera
+    and the pattern is decided by y alone; it must not depend on how far beyond the range the camera is."""
+    desc = one_body_scene(wl.sphere(0.1, RGB, 6, 3), 32, 24)
+    s = orc.Scene(desc)
+
+    def ground_rgb(x, y=0.3):
+        o = s.render(pose_row((x, y, 1.0))[None, None, None])
+        assert (o["ids"][0, 0] == GROUND).sum() > 100
+        return np.where((o["ids"][0, 0] == GROUND)[..., None], o["frames"][0, 0], 0)
+
+    far, farther, neg = ground_rgb(3.0e9), ground_rgb(7.5e9), ground_rgb(-6.0e9)
+    assert np.array_equal(far, farther)
+    # INT32_MAX is odd and INT32_MIN even: the two ends show complementary checkers
+    greys = np.unique(far[far > 0])
+    assert len(greys) == 2
+    swapped = np.where(far == greys[0], greys[1], np.where(far == greys[1], greys[0], 0))
+    assert np.array_equal(neg, swapped)
+    # infinities and NaN are defined too (NaN counts as cell 0: the same parity as INT32_MIN)
+    assert np.array_equal(ground_rgb(np.inf), far)
+    assert np.array_equal(ground_rgb(np.nan), neg)
