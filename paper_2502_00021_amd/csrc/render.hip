@@ -567,8 +567,11 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     PXR_PHASE_BEGIN();
     // ---- phase 0: per-body transforms, per-frame draws, the three non-triangle colours
     for (uint32_t i = tid; i < sc.W + sc.H; i += NT) cxcy[i] = sc.cxcy[i];
-    if (tid < sc.K) {
-        const float* p = pose + tid * 7;
+    if (tid < 4u * sc.K) {
+        // Four lanes per body: each rebuilds the body's rotation and takes one row of the work (the view matrix
+        // has three rows, the light direction is the fourth): a quarter of the dot products on the chain.
+        const uint32_t b = tid >> 2, part = tid & 3u;
+        const float* p = pose + b * 7;
         const float w = p[3], x = p[4], y = p[5], z = p[6];
         float R[3][3];
         R[0][0] = 1.0f - 2.0f * (y * y + z * z);
@@ -581,23 +584,21 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         R[2][1] = 2.0f * (y * z + w * x);
         R[2][2] = 1.0f - 2.0f * (x * x + y * y);
         const float dx = p[0] - eye_x, dy = p[1] - eye_y, dz = p[2] - eye_z;
-        float* o = body + tid * kBodyStride;
+        const float r0 = part == 0u ? sc.Rt[0] : (part == 1u ? sc.Up[0] : (part == 2u ? sc.Fw[0] : sc.l[0]));
+        const float r1 = part == 0u ? sc.Rt[1] : (part == 1u ? sc.Up[1] : (part == 2u ? sc.Fw[1] : sc.l[1]));
+        const float r2 = part == 0u ? sc.Rt[2] : (part == 1u ? sc.Up[2] : (part == 2u ? sc.Fw[2] : sc.l[2]));
+        float* o = body + b * kBodyStride;
 #pragma unroll
-        for (int c = 0; c < 3; ++c) {
-            o[0 + c] = dot3(sc.Rt[0], sc.Rt[1], sc.Rt[2], R[0][c], R[1][c], R[2][c]);
-            o[3 + c] = dot3(sc.Up[0], sc.Up[1], sc.Up[2], R[0][c], R[1][c], R[2][c]);
-            o[6 + c] = dot3(sc.Fw[0], sc.Fw[1], sc.Fw[2], R[0][c], R[1][c], R[2][c]);
+        for (int c = 0; c < 3; ++c) o[3u * part + (part == 3u ? 3u : 0u) + c] = dot3(r0, r1, r2, R[0][c], R[1][c], R[2][c]);
+        if (part < 3u) {
+            o[9u + part] = dot3(r0, r1, r2, dx, dy, dz);
+        } else {
+            const float* shp = shapes ? shapes + ((size_t)e * sc.K + b) * 4 : sc.body_const + b * 8;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) o[16 + c] = shp[c];
+#pragma unroll
+            for (int c = 0; c < 3; ++c) o[20 + c] = sc.body_const[b * 8 + 4 + c];
         }
-        o[9] = dot3(sc.Rt[0], sc.Rt[1], sc.Rt[2], dx, dy, dz);
-        o[10] = dot3(sc.Up[0], sc.Up[1], sc.Up[2], dx, dy, dz);
-        o[11] = dot3(sc.Fw[0], sc.Fw[1], sc.Fw[2], dx, dy, dz);
-#pragma unroll
-        for (int c = 0; c < 3; ++c) o[12 + c] = dot3(sc.l[0], sc.l[1], sc.l[2], R[0][c], R[1][c], R[2][c]);
-        const float* shp = shapes ? shapes + ((size_t)e * sc.K + tid) * 4 : sc.body_const + tid * 8;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) o[16 + c] = shp[c];
-#pragma unroll
-        for (int c = 0; c < 3; ++c) o[20 + c] = sc.body_const[tid * 8 + 4 + c];
     }
     if (tid >= 64u) {
         // The second wavefront on: one lane per image row prepares what all pixels of the row share: the row
