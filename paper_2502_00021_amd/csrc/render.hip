@@ -340,6 +340,7 @@ __device__ __forceinline__ uint32_t quantise(float c) {
 // registers) and lane 0 adds the spans to global counters when the kernel ends (1024 sets of counters: one
 // shared set would serialise the kernel's tail).
 __device__ unsigned long long g_phase_cycles[1024 * 8];
+__device__ unsigned long long g_wave_arrival[1024 * 16];  // per wavefront: clock at the first barrier minus workgroup start
 #define PXR_PHASE_BEGIN()                      \
     unsigned long long phase_span[8] = {0};    \
     unsigned long long phase_t0 = __builtin_readcyclecounter()
@@ -566,7 +567,11 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
 
     PXR_PHASE_BEGIN();
     // ---- phase 0: per-body transforms, per-frame draws, the three non-triangle colours
-    for (uint32_t i = tid; i < sc.W + sc.H; i += NT) cxcy[i] = sc.cxcy[i];
+    // (16-wavefront groups: copied by the fourth wavefront on, the first three have chains of their own in this
+    // phase; measured the other way round for the smaller groups)
+    constexpr uint32_t kCopyFrom = NT >= 1024 ? 192u : 0u;
+    if (tid >= kCopyFrom)
+        for (uint32_t i = tid - kCopyFrom; i < sc.W + sc.H; i += NT - kCopyFrom) cxcy[i] = sc.cxcy[i];
     if (tid < 4u * sc.K) {
         // Four lanes per body: each rebuilds the body's rotation and takes one row of the work (the view matrix
         // has three rows, the light direction is the fourth): a quarter of the dot products on the chain.
@@ -628,10 +633,14 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
             rows[j] = r;
         }
     }
-    if (tid >= NT - 2 && dc.mode == PXR_DISTRACT_COLOR) {
-        // The colour draws are two generator streams, the longest serial chain of this phase: the last two
+    // (The wavefronts of a workgroup start a few hundred clocks apart, four at a time; the last ones start more than
+    // a thousand clocks after the first.  The draws are this phase's longest chain beside the bodies': they belong on
+    // an early wavefront that has nothing else to do - the third - and the late ones get no work here at all.)
+    constexpr uint32_t kDrawLane = NT >= 1024 ? 191u : NT - 1u;  // last lane of the third wavefront (of the last: smaller groups)
+    if (tid <= kDrawLane && tid >= kDrawLane - 1u && dc.mode == PXR_DISTRACT_COLOR) {
+        // The colour draws are two generator streams, the longest serial chain of this phase: the two
         // lanes walk one stream each, side by side; the offsets go through LDS to the last lane.
-        const uint32_t stream = (NT - 1) - tid;
+        const uint32_t stream = kDrawLane - tid;
         uint32_t r[4];
         counter_rng(dc.seed_lo, dc.seed_hi, env, step, stream, 0u, r);
         const float span = stream == 0u ? dc.scale_span : dc.offset_span, lo = stream == 0u ? dc.scale_lo : dc.offset_lo;
@@ -642,7 +651,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
-    if (tid == NT - 1) {  // a lane of the last wave: the first wave is busy with the bodies
+    if (tid == kDrawLane) {
         fu->bins = 0ull;
         fu->n_cand = 0;
         if (dc.mode == PXR_DISTRACT_VIDEO) {
@@ -667,10 +676,10 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
             fu->video_frame = clip * dc.n_frames + (uint32_t)(((u64)first + (u64)step) % dc.n_frames);
         }
     }
-    if (tid >= NT - 3) {
+    if (tid <= kDrawLane && tid >= kDrawLane - 2u) {
         // Background and the two ground greys are the same for every pixel that shows them: they go through
         // the colour distractor and the quantiser once per frame, one lane per colour.
-        const uint32_t k = (NT - 1) - tid;
+        const uint32_t k = kDrawLane - tid;
         float scale[3] = {1.0f, 1.0f, 1.0f}, offs[3] = {0.0f, 0.0f, 0.0f};
         if (dc.mode == PXR_DISTRACT_COLOR) {
 #pragma unroll
@@ -700,7 +709,22 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
             }
         }
     }
+#ifdef PXR_PHASE_TIMING
+    {
+        unsigned long long* arr = reinterpret_cast<unsigned long long*>(lds + sc.lds_list);  // (free until phase 2b)
+        if (lane == 0) arr[tid >> 6] = __builtin_readcyclecounter();
+    }
+#endif
     __syncthreads();
+#ifdef PXR_PHASE_TIMING
+    if (tid < NT / 64) {
+        unsigned long long* arr = reinterpret_cast<unsigned long long*>(lds + sc.lds_list);
+        unsigned long long first = arr[0];
+        for (uint32_t k = 1; k < NT / 64; ++k) first = arr[k] < first ? arr[k] : first;
+        atomicAdd(&g_wave_arrival[(blockIdx.x & 1023u) * 16u + tid], arr[tid] - first);
+    }
+    __syncthreads();
+#endif
     PXR_PHASE_MARK(0);
 
     // ---- phase 1: instancing + projection + snap + cell code (one lane per template vertex)
@@ -939,6 +963,16 @@ int prepare_all(uint32_t cap, std::string& err) {
 }
 
 #ifdef PXR_PHASE_TIMING
+extern "C" int pxr_debug_wave_arrival(unsigned long long* out) {
+    static unsigned long long host[1024 * 16];
+    if (hipMemcpyFromSymbol(host, HIP_SYMBOL(g_wave_arrival), sizeof(host)) != hipSuccess) return 1;
+    for (int i = 0; i < 16; ++i) out[i] = 0;
+    for (int k = 0; k < 1024; ++k)
+        for (int i = 0; i < 16; ++i) out[i] += host[k * 16 + i];
+    for (auto& h : host) h = 0;
+    return hipMemcpyToSymbol(HIP_SYMBOL(g_wave_arrival), host, sizeof(host)) != hipSuccess;
+}
+
 extern "C" int pxr_debug_phase_cycles(unsigned long long* out, int reset) {
     static unsigned long long host[1024 * 8];
     if (out) {
