@@ -849,14 +849,16 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         const u64 bins = fu->bins;
         const uint32_t n_tiny = (uint32_t)bins & 0xFFFFu, n_small = (uint32_t)bins >> 16, n_large = (uint32_t)(bins >> 32);
 
-        // tiny: one lane per triangle, from the first lane up
-        for (uint32_t k = tid; k < n_tiny; k += NT)
-            raster_binned<false>(sc, list[k], body, vxy, vd, keys, 0, 0, (int)row_lo, (int)row_hi);
-        // small: a team of lanes per triangle, from the last lane down
+        // The hardware favours a workgroup's older wavefronts when several want to issue, so the youngest finish a
+        // phase last: the heavier bin goes to the oldest.
+        // small: a team of lanes per triangle, from the first lane up
         constexpr uint32_t kTeam = 1u << kSmallLanesLog2;
-        for (uint32_t k = (NT - 1 - tid) >> kSmallLanesLog2; k < n_small; k += NT >> kSmallLanesLog2)
+        for (uint32_t k = tid >> kSmallLanesLog2; k < n_small; k += NT >> kSmallLanesLog2)
             raster_binned<false>(sc, list[sc.T - 1 - k], body, vxy, vd, keys, (int)(tid & (kTeam - 1u)), (int)kSmallLanesLog2,
                                  (int)row_lo, (int)row_hi);
+        // tiny: one lane per triangle, from the last lane down
+        for (uint32_t k = NT - 1 - tid; k < n_tiny; k += NT)
+            raster_binned<false>(sc, list[k], body, vxy, vd, keys, 0, 0, (int)row_lo, (int)row_hi);
         // large: a whole wave per triangle, starting in the middle waves
         for (uint32_t k = ((tid >> 6) + NT / 128) % (NT / 64); k < n_large; k += NT / 64)
             raster_binned<true>(sc, list2[k], body, vxy, vd, keys, (int)lane, 6, (int)row_lo, (int)row_hi);
