@@ -340,7 +340,7 @@ __device__ __forceinline__ uint32_t quantise(float c) {
 // registers) and lane 0 adds the spans to global counters when the kernel ends (1024 sets of counters: one
 // shared set would serialise the kernel's tail).
 __device__ unsigned long long g_phase_cycles[1024 * 8];
-__device__ unsigned long long g_wave_arrival[1024 * 16];  // per wavefront: clock at the first barrier minus workgroup start
+__device__ unsigned long long g_wave_arrival[1024 * 8 * 16];  // per barrier and wavefront: arrival after the barrier's first wavefront
 #define PXR_PHASE_BEGIN()                      \
     unsigned long long phase_span[8] = {0};    \
     unsigned long long phase_t0 = __builtin_readcyclecounter()
@@ -349,6 +349,19 @@ __device__ unsigned long long g_wave_arrival[1024 * 16];  // per wavefront: cloc
         const unsigned long long now = __builtin_readcyclecounter();    \
         phase_span[i] += now - phase_t0;                                 \
         phase_t0 = now;                                                  \
+    }
+// (a barrier that also notes, per wavefront, how long after the first one it arrived)
+#define PXR_TIMED_BARRIER(i)                                                                              \
+    {                                                                                                         \
+        unsigned long long* arr = reinterpret_cast<unsigned long long*>(lds + sc.lds_misc + 128);             \
+        if (lane == 0) arr[tid >> 6] = __builtin_readcyclecounter();                                          \
+        __syncthreads();                                                                                      \
+        if (tid < NT / 64) {                                                                                  \
+            unsigned long long first = arr[0];                                                                \
+            for (uint32_t k = 1; k < NT / 64; ++k) first = arr[k] < first ? arr[k] : first;                   \
+            atomicAdd(&g_wave_arrival[((blockIdx.x & 1023u) * 8u + (i)) * 16u + tid], arr[tid] - first);      \
+        }                                                                                                     \
+        __syncthreads();                                                                                      \
     }
 #define PXR_PHASE_END()                                                                                      \
     if (tid == 0) {                                                                                          \
@@ -359,10 +372,12 @@ __device__ unsigned long long g_wave_arrival[1024 * 16];  // per wavefront: cloc
 #define PXR_PHASE_BEGIN()
 #define PXR_PHASE_MARK(i) \
     if ((i) == PXR_STOP_AFTER) return
+#define PXR_TIMED_BARRIER(i) __syncthreads()
 #define PXR_PHASE_END()
 #else
 #define PXR_PHASE_BEGIN()
 #define PXR_PHASE_MARK(i)
+#define PXR_TIMED_BARRIER(i) __syncthreads()
 #define PXR_PHASE_END()
 #endif
 
@@ -709,22 +724,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
             }
         }
     }
-#ifdef PXR_PHASE_TIMING
-    {
-        unsigned long long* arr = reinterpret_cast<unsigned long long*>(lds + sc.lds_list);  // (free until phase 2b)
-        if (lane == 0) arr[tid >> 6] = __builtin_readcyclecounter();
-    }
-#endif
-    __syncthreads();
-#ifdef PXR_PHASE_TIMING
-    if (tid < NT / 64) {
-        unsigned long long* arr = reinterpret_cast<unsigned long long*>(lds + sc.lds_list);
-        unsigned long long first = arr[0];
-        for (uint32_t k = 1; k < NT / 64; ++k) first = arr[k] < first ? arr[k] : first;
-        atomicAdd(&g_wave_arrival[(blockIdx.x & 1023u) * 16u + tid], arr[tid] - first);
-    }
-    __syncthreads();
-#endif
+    PXR_TIMED_BARRIER(0);
     PXR_PHASE_MARK(0);
 
     // ---- phase 1: instancing + projection + snap + cell code (one lane per template vertex)
@@ -753,7 +753,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         vd[v] = sc.z_near * inv;
         vm[v] = m;
     }
-    __syncthreads();
+    PXR_TIMED_BARRIER(1);
     PXR_PHASE_MARK(1);
 
     // ---- phase 2a: coarse binning, one lane per pair of edge-sharing triangles (q0,q1,q2), (q0,q2,q3).
@@ -784,7 +784,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
             if (keep_b) cand[slot + (keep_a ? 1u : 0u)] = (uint16_t)tb;
         }
     }
-    __syncthreads();
+    PXR_TIMED_BARRIER(2);
     PXR_PHASE_MARK(2);
 
     // ---- phase 2b: exact binning, one lane per candidate triangle: reject, area sign, pixel range,
@@ -826,7 +826,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
             if (cls == 3) list2[old_hi + lanes_below(m3)] = (uint16_t)t;
         }
     }
-    __syncthreads();
+    PXR_TIMED_BARRIER(3);
     PXR_PHASE_MARK(3);
 
     // Tall frames are rendered in horizontal bands so that the key buffer stays small enough for two
@@ -841,7 +841,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         // (two keys per store; the region is padded to 16 bytes, so an odd count may clear one key more)
         for (uint32_t p = tid; p < (p_end - p_begin + 1u) >> 1; p += NT)
             reinterpret_cast<uint4*>(keys)[p] = make_uint4(0u, 0u, 0u, 0u);
-        __syncthreads();
+        PXR_TIMED_BARRIER(4);
         PXR_PHASE_MARK(4);
 
         // ---- phase 3: raster + z-test into the LDS key buffer.  The bins start at different
@@ -862,7 +862,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         // large: a whole wave per triangle, starting in the middle waves
         for (uint32_t k = ((tid >> 6) + NT / 128) % (NT / 64); k < n_large; k += NT / 64)
             raster_binned<true>(sc, list2[k], body, vxy, vd, keys, (int)lane, 6, (int)row_lo, (int)row_hi);
-        __syncthreads();
+        PXR_TIMED_BARRIER(5);
         PXR_PHASE_MARK(5);
 
         // ---- phase 4: resolve + shade + distractor + pack + store
@@ -965,12 +965,12 @@ int prepare_all(uint32_t cap, std::string& err) {
 }
 
 #ifdef PXR_PHASE_TIMING
-extern "C" int pxr_debug_wave_arrival(unsigned long long* out) {
-    static unsigned long long host[1024 * 16];
+extern "C" int pxr_debug_wave_arrival(unsigned long long* out) {  // out[8][16]
+    static unsigned long long host[1024 * 8 * 16];
     if (hipMemcpyFromSymbol(host, HIP_SYMBOL(g_wave_arrival), sizeof(host)) != hipSuccess) return 1;
-    for (int i = 0; i < 16; ++i) out[i] = 0;
+    for (int i = 0; i < 128; ++i) out[i] = 0;
     for (int k = 0; k < 1024; ++k)
-        for (int i = 0; i < 16; ++i) out[i] += host[k * 16 + i];
+        for (int i = 0; i < 128; ++i) out[i] += host[k * 128 + i];
     for (auto& h : host) h = 0;
     return hipMemcpyToSymbol(HIP_SYMBOL(g_wave_arrival), host, sizeof(host)) != hipSuccess;
 }
