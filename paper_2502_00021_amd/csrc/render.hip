@@ -350,7 +350,11 @@ __device__ unsigned long long g_wave_arrival[1024 * 8 * 16];  // per barrier and
         phase_span[i] += now - phase_t0;                                 \
         phase_t0 = now;                                                  \
     }
-// (a barrier that also notes, per wavefront, how long after the first one it arrived)
+// (with -DPXR_WAVE_ARRIVAL: a barrier that also notes, per wavefront, how long after the first one it arrived;
+// the second barrier it needs slows the kernel, so the phase clocks are best read without it)
+#ifndef PXR_WAVE_ARRIVAL
+#define PXR_TIMED_BARRIER(i) __syncthreads()
+#else
 #define PXR_TIMED_BARRIER(i)                                                                              \
     {                                                                                                         \
         unsigned long long* arr = reinterpret_cast<unsigned long long*>(lds + sc.lds_misc + 128);             \
@@ -363,6 +367,7 @@ __device__ unsigned long long g_wave_arrival[1024 * 8 * 16];  // per barrier and
         }                                                                                                     \
         __syncthreads();                                                                                      \
     }
+#endif
 #define PXR_PHASE_END()                                                                                      \
     if (tid == 0) {                                                                                          \
         for (int i = 0; i < 7; ++i) atomicAdd(&g_phase_cycles[(blockIdx.x & 1023u) * 8u + i], phase_span[i]); \
