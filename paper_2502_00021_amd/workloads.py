@@ -477,3 +477,52 @@ def make(cfg, B=None):
     """Workload `cfg` in 1..5, optionally at a reduced (or enlarged) environment count."""
     fn = CONFIGS[int(cfg)]
     return fn() if B is None else fn(B)
+
+
+def random_scene(seed, B=4):
+    """A seeded random scene for parity fuzzing: image shape (packed and unpacked store paths, banded or not),
+    camera (offset, field of view, with or without roll), ground, a mix of capsules / spheres / boxes of random
+    size and tessellation at random distances (so that triangles of every raster bin occur), free random poses,
+    optional per-environment shapes and any of the three distractor modes."""
+    rng = np.random.default_rng(SEED_BASE + 1000 + int(seed))
+    W = int(rng.choice([24, 33, 40, 64, 84, 96, 110]))
+    H = int(rng.choice([16, 31, 48, 64, 84, 100]))
+    K = int(rng.integers(1, 9))
+    bodies = []
+    for _ in range(K):
+        rgb = rng.uniform(0.1, 1.0, 3)
+        kind = int(rng.integers(0, 3))
+        if kind == 0:
+            bodies.append(capsule(rng.uniform(0.03, 0.3), rng.uniform(0.0, 0.5), rgb, int(rng.integers(3, 14)), int(rng.integers(1, 7))))
+        elif kind == 1:
+            bodies.append(sphere(rng.uniform(0.05, 0.6), rgb, int(rng.integers(3, 18)), int(rng.integers(1, 9))))
+        else:
+            e = rng.uniform(0.05, 0.6, 3)
+            bodies.append(box(e[0], e[1], e[2], rgb, int(rng.integers(1, 6))))
+    desc = default_scene(W, H, bodies, root_body=int(rng.integers(0, K)))
+    off = rng.uniform(-1.0, 1.0, 3)
+    off = off / np.linalg.norm(off) * rng.uniform(0.8, 4.0)
+    off[2] = abs(off[2]) * 0.7 + 0.1
+    desc.update(fov_y_deg=float(rng.uniform(25.0, 95.0)), cam_offset=tuple(float(x) for x in off),
+                ground_enabled=bool(rng.random() < 0.8), ground_cell=float(rng.choice([1.0, 1.0, 0.37, 2.5])),
+                z_far=float(rng.choice([50.0, 6.0])), light_dir=tuple(float(x) for x in rng.uniform(-1.0, 1.0, 3) + np.array([0, 0, 0.2])))
+    if rng.random() < 0.4:  # camera roll
+        desc["cam_up"] = (float(rng.uniform(-0.4, 0.4)), float(rng.uniform(-0.4, 0.4)), 1.0)
+    S = int(rng.integers(1, 4))
+    poses = np.zeros((B, S, K, 7), np.float32)
+    poses[..., :3] = rng.uniform([-0.8, -0.8, 0.1], [0.8, 0.8, 1.6], (B, S, K, 3))
+    q = rng.standard_normal((B, S, K, 4))
+    poses[..., 3:] = q / np.linalg.norm(q, axis=-1, keepdims=True)
+    shapes = None
+    if rng.random() < 0.5:
+        base = np.array([b["shape"] for b in bodies], np.float32)
+        shapes = (base[None] * rng.uniform(0.6, 1.5, (B, K, 1))).astype(np.float32)
+    mode = int(rng.integers(0, 3))
+    dis = None
+    if mode == 1:
+        dis = dict(mode="color", seed=int(rng.integers(0, 2**62)), scale_lo=0.5, scale_hi=1.5, offset_lo=-0.2, offset_hi=0.2)
+    elif mode == 2:
+        n = int(rng.integers(1, 6))
+        dis = dict(mode="video", seed=int(rng.integers(0, 2**62)), alpha=float(rng.choice([0.5, 0.25, 1.0])),
+                   video=rng.integers(0, 256, (n, H, W, 3), dtype=np.uint8))
+    return dict(name=f"random-{seed}", desc=desc, poses=poses, shapes=shapes, distractor=dis)

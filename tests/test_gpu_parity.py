@@ -408,6 +408,16 @@ def test_ground_variants(torch, pxr, orc):
         assert_parity(gpu_render(torch, pxr, w2), oracle_render(orc, w2))
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_scenes_match_oracle(torch, pxr, orc, seed):
+    """Seeded random scenes: image shapes, cameras (with and without roll), body mixes and sizes (triangles of
+    every raster bin, bodies crossing the near plane), shapes per environment, all distractor modes."""
+    w = wl.random_scene(seed)
+    ref = oracle_render(orc, w, step0=3, env0=5)
+    assert_parity(gpu_render(torch, pxr, w, step0=3, env0=5), ref)
+    assert_parity(gpu_render(torch, pxr, w, step0=3, env0=5, threads=(256, 512, 768, 1024)[seed % 4]), ref)
+
+
 # ---------------------------------------------------------------- distractors
 
 def test_colour_distractor_per_step_and_identity(torch, pxr, orc):
