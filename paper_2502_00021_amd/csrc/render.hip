@@ -190,14 +190,16 @@ __device__ __forceinline__ void view_position(const SceneConsts& sc, const float
                                               float& pvz) {
     const float4 tv = reinterpret_cast<const float4*>(sc.vtmpl)[v];
     const uint32_t code = __float_as_uint(tv.w);
-    const float* o = body + __umul24(code >> 2, kBodyStride);
+    // (body records are 96 bytes at a 16-byte aligned base: four 16-byte LDS reads)
+    const float4* o4 = reinterpret_cast<const float4*>(body + __umul24(code >> 2, kBodyStride));
+    const float4 m0 = o4[0], m1 = o4[1], m2 = o4[2], sh = o4[4];  // M and t as floats 0..11, the shape as 16..19
     const float sel = (float)((int)(code & 3u) - 1);
-    const float lx = o[16] * tv.x;
-    const float ly = o[17] * tv.y;
-    const float lz = __builtin_fmaf(o[18], tv.z, sel * o[19]);
-    pvx = __builtin_fmaf(o[0], lx, __builtin_fmaf(o[1], ly, __builtin_fmaf(o[2], lz, o[9])));
-    pvy = __builtin_fmaf(o[3], lx, __builtin_fmaf(o[4], ly, __builtin_fmaf(o[5], lz, o[10])));
-    pvz = __builtin_fmaf(o[6], lx, __builtin_fmaf(o[7], ly, __builtin_fmaf(o[8], lz, o[11])));
+    const float lx = sh.x * tv.x;
+    const float ly = sh.y * tv.y;
+    const float lz = __builtin_fmaf(sh.z, tv.z, sel * sh.w);
+    pvx = __builtin_fmaf(m0.x, lx, __builtin_fmaf(m0.y, ly, __builtin_fmaf(m0.z, lz, m2.y)));
+    pvy = __builtin_fmaf(m0.w, lx, __builtin_fmaf(m1.x, ly, __builtin_fmaf(m1.y, lz, m2.z)));
+    pvz = __builtin_fmaf(m1.z, lx, __builtin_fmaf(m1.w, ly, __builtin_fmaf(m2.x, lz, m2.w)));
 }
 
 // One piece (a, b, c in screen order) of a clipped triangle, rastered by a whole wavefront.
@@ -428,14 +430,16 @@ __device__ __forceinline__ u64 ground_key(const SceneConsts& sc, const ResolveCt
 // Triangle g as a 24-bit colour: flat Lambert + ambient in the body frame, then the colour distractor.
 __device__ __forceinline__ uint32_t shade_triangle(const SceneConsts& sc, const ResolveCtx& rc, const float* body, uint32_t g) {
     const float4 ns = reinterpret_cast<const float4*>(sc.tri_shade)[g];
-    const float* o = body + (sc.tri_idx[g * 2 + 1] >> 16) * kBodyStride;
-    float I = __builtin_fmaf(ns.x, o[12], __builtin_fmaf(ns.y, o[13], ns.z * o[14]));
+    const float4* o4 = reinterpret_cast<const float4*>(body + (sc.tri_idx[g * 2 + 1] >> 16) * kBodyStride);
+    const float4 lb = o4[3], col = o4[5];  // floats 12..14: light in the body frame, 20..22: colour
+    const float o_rgb[3] = {col.x, col.y, col.z};
+    float I = __builtin_fmaf(ns.x, lb.x, __builtin_fmaf(ns.y, lb.y, ns.z * lb.z));
     I = I > 0.0f ? I : 0.0f;
     const float sh = __builtin_fmaf(sc.diffuse, I, sc.ambient);
     uint32_t rgb = 0;
 #pragma unroll
     for (int ch = 0; ch < 3; ++ch) {
-        float v = (o[20 + ch] * ns.w) * sh;
+        float v = (o_rgb[ch] * ns.w) * sh;
         v = v < 1.0f ? v : 1.0f;
         if (rc.mode == PXR_DISTRACT_COLOR) {
             v = __builtin_fmaf(v, rc.scale[ch], rc.offs[ch]);
@@ -505,6 +509,9 @@ __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const Resol
         // without roll the ground test is the row's: ray parameter (0 = miss) and depth bits from the row table
         const float tg_row = NO_ROLL ? row.z : 0.0f;
         const u64 gkey_row = (NO_ROLL && tg_row != 0.0f) ? (((u64)__float_as_uint(row.w) << 32) | 1ull) : 0ull;
+        // the lane's four keys are 32 contiguous, aligned bytes: two 16-byte LDS reads
+        const uint4 k01 = reinterpret_cast<const uint4*>(keys + (p0 - p_begin))[0], k23 = reinterpret_cast<const uint4*>(keys + (p0 - p_begin))[1];
+        const u64 key4[4] = {((u64)k01.y << 32) | k01.x, ((u64)k01.w << 32) | k01.z, ((u64)k23.y << 32) | k23.x, ((u64)k23.w << 32) | k23.z};
         uint32_t rgb[4], low[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -513,7 +520,7 @@ __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const Resol
             if (!NO_ROLL) gkey = ground_key(sc, rc, -__builtin_fmaf(sc.Rt[2], cxs[k], rz), tg);
             const float dwx = __builtin_fmaf(sc.Rt[0], cxs[k], rx);
             const float dwy = __builtin_fmaf(sc.Rt[1], cxs[k], ry);
-            rgb[k] = resolve_pixel<UNIT_CELL, true>(sc, rc, body, keys[p0 - p_begin + k], gkey, tg, dwx, dwy, vb[k], low[k]);
+            rgb[k] = resolve_pixel<UNIT_CELL, true>(sc, rc, body, key4[k], gkey, tg, dwx, dwy, vb[k], low[k]);
         }
         // Triangle pixels are few and clustered: instead of every lane walking the shading code four
         // times, the wavefront compacts its triangle pixels into a list (in the LDS of its own, already
