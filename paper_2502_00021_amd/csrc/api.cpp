@@ -74,12 +74,24 @@ int pxr_create_scene(const pxr_scene_desc* desc, pxr_scene** out) {
         size_t bytes;
         size_t off;
     };
+    // The device copy of the pair table holds, in place of the four vertex indices, the LDS byte addresses of
+    // the vertices' cell codes (the kernel reads them without any address arithmetic): code v sits at
+    // lds_keys + 4 v of the dynamic LDS segment, which starts at address 0 (prepare_kernels checks that the
+    // kernels have no static LDS in front of it).
+    if ((uint64_t)hs.c.lds_keys + 4ull * hs.c.V > 0x10000ull)
+        return fail(PXR_ERR_UNSUPPORTED, "pxr_create_scene: too many vertices for 16-bit LDS addresses in the pair table");
+    std::vector<uint32_t> pair_dev(hs.pair_tbl);
+    for (size_t p = 0; p < pair_dev.size() / 4; ++p)
+        for (int w = 0; w < 2; ++w) {
+            const uint32_t q = hs.pair_tbl[p * 4 + w];
+            pair_dev[p * 4 + w] = (hs.c.lds_keys + 4u * (q & 0xFFFFu)) | ((hs.c.lds_keys + 4u * (q >> 16)) << 16);
+        }
     Part parts[6] = {{hs.vtmpl.data(), hs.vtmpl.size() * 4, 0},
                      {hs.tri_idx.data(), hs.tri_idx.size() * 4, 0},
                      {hs.tri_shade.data(), hs.tri_shade.size() * 4, 0},
                      {hs.body_const.data(), hs.body_const.size() * 4, 0},
                      {hs.cxcy.data(), hs.cxcy.size() * 4, 0},
-                     {hs.pair_tbl.data(), hs.pair_tbl.size() * 4, 0}};
+                     {pair_dev.data(), pair_dev.size() * 4, 0}};
     size_t total = 0;
     for (Part& p : parts) {
         p.off = total;

@@ -65,7 +65,8 @@ struct SceneConsts {
     const float* vtmpl;       // [V][4]  ux,uy,uz, bits = body<<2 | (s+1)
     const uint32_t* tri_idx;  // [T][2]  v0 | v1<<16 ,  v2 | body<<16
     const float* tri_shade;   // [T][4]  unit normal (body frame), colour multiplier
-    const uint32_t* pair_tbl; // [P][4]  q0 | q1<<16 , q2 | q3<<16 , triA | triB<<16 , 0: two triangles sharing the
+    const uint32_t* pair_tbl; // [P][4]  a0 | a1<<16 , a2 | a3<<16 , triA | triB<<16 , 0 (a_i = LDS byte address of the cell
+                              //         code of vertex q_i; the host-side table holds q_i itself): two triangles sharing the
                               //         edge q0-q2, or one triangle (q3 = q2, triB = kNoTriangle)
     const float* body_const;  // [K][8]  shape a,b,c,h ; rgb r,g,b,0
     const float* cxcy;        // [W+H]   pixel-centre ray slopes

@@ -327,6 +327,12 @@ __device__ __forceinline__ uint32_t cell_code(int x, int n) {
     return (uint32_t)r;
 }
 
+// A 32-bit word of LDS by its byte address.  (The dynamic LDS segment starts at address 0: the kernels here have
+// no static LDS, which prepare_kernels verifies; tables built on the host can therefore hold LDS addresses.)
+__device__ __forceinline__ uint32_t lds_u32_at(uint32_t byte_address) {
+    return *reinterpret_cast<const __attribute__((address_space(3))) uint32_t*>(static_cast<uintptr_t>(byte_address));
+}
+
 __device__ __forceinline__ uint32_t lanes_below(u64 m) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
 }
@@ -778,7 +784,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         if (p < sc.P) {
             const uint4 rec = reinterpret_cast<const uint4*>(sc.pair_tbl)[p];
             const uint32_t w0 = rec.x, w1 = rec.y, w2 = rec.z;
-            const uint32_t m0 = vm[w0 & 0xFFFFu], m1 = vm[w0 >> 16], m2 = vm[w1 & 0xFFFFu], m3 = vm[w1 >> 16];
+            const uint32_t m0 = lds_u32_at(w0 & 0xFFFFu), m1 = lds_u32_at(w0 >> 16), m2 = lds_u32_at(w1 & 0xFFFFu), m3 = lds_u32_at(w1 >> 16);
             const uint32_t odd = m0 & 0x00010001u, x02 = m0 ^ m2;
             const uint32_t da = (m0 ^ m1) | x02 | odd, db = x02 | (m0 ^ m3) | odd;
             ta = w2 & 0xFFFFu;
@@ -957,6 +963,12 @@ int launch_one(const SceneConsts& sc, const DistractConsts& dc, const float* d_p
 
 template <int NT, int PX, bool BANDED>
 int prepare_one(uint32_t lds_bytes, std::string& err) {
+    hipFuncAttributes attr;
+    if (hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(&render_kernel<NT, PX, BANDED>)) != hipSuccess ||
+        attr.sharedSizeBytes != 0) {
+        err = "the render kernel has static LDS in front of its dynamic segment (LDS addresses in the tables assume none)";
+        return PXR_ERR_DEVICE;
+    }
     const hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&render_kernel<NT, PX, BANDED>),
                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (rc != hipSuccess) {
