@@ -86,7 +86,18 @@ int pxr_create_scene(const pxr_scene_desc* desc, pxr_scene** out) {
             const uint32_t q = hs.pair_tbl[p * 4 + w];
             pair_dev[p * 4 + w] = (hs.c.lds_keys + 4u * (q & 0xFFFFu)) | ((hs.c.lds_keys + 4u * (q >> 16)) << 16);
         }
-    Part parts[6] = {{hs.vtmpl.data(), hs.vtmpl.size() * 4, 0},
+    // Likewise the device copy of the vertex templates: its fourth word holds the LDS byte address of the body's
+    // record, shifted left by 2, and the cap selector as a 2-bit two's-complement number (-1, 0, +1) below it, in
+    // place of body << 2 | (selector + 1).
+    std::vector<float> vtmpl_dev(hs.vtmpl);
+    for (size_t v = 0; v < vtmpl_dev.size() / 4; ++v) {
+        uint32_t code;
+        std::memcpy(&code, &hs.vtmpl[v * 4 + 3], 4);
+        const uint32_t body_at = hs.c.lds_body + (code >> 2) * pxr::kBodyStride * 4u, sel = ((code & 3u) - 1u) & 3u;
+        const uint32_t dev = (body_at << 2) | sel;
+        std::memcpy(&vtmpl_dev[v * 4 + 3], &dev, 4);
+    }
+    Part parts[6] = {{vtmpl_dev.data(), vtmpl_dev.size() * 4, 0},
                      {hs.tri_idx.data(), hs.tri_idx.size() * 4, 0},
                      {hs.tri_shade.data(), hs.tri_shade.size() * 4, 0},
                      {hs.body_const.data(), hs.body_const.size() * 4, 0},

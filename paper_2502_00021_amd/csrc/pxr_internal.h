@@ -62,7 +62,8 @@ struct SceneConsts {
     uint32_t band_rows;                     // rows of the frame held by the LDS key buffer at a time
     uint32_t magicW;  // ceil(2^32 / W): p / W == mulhi(p, magicW) for every pixel index p < 512 * W
     // device tables
-    const float* vtmpl;       // [V][4]  ux,uy,uz, bits = body<<2 | (s+1)
+    const float* vtmpl;       // [V][4]  ux,uy,uz, bits = (LDS byte address of the body's record)<<2 | s as a 2-bit signed number
+                              //         (the host-side table holds body<<2 | (s+1))
     const uint32_t* tri_idx;  // [T][2]  v0 | v1<<16 ,  v2 | body<<16
     const float* tri_shade;   // [T][4]  unit normal (body frame), colour multiplier
     const uint32_t* pair_tbl; // [P][4]  a0 | a1<<16 , a2 | a3<<16 , triA | triB<<16 , 0 (a_i = LDS byte address of the cell

@@ -191,9 +191,11 @@ __device__ __forceinline__ void view_position(const SceneConsts& sc, const float
     const float4 tv = reinterpret_cast<const float4*>(sc.vtmpl)[v];
     const uint32_t code = __float_as_uint(tv.w);
     // (body records are 96 bytes at a 16-byte aligned base: four 16-byte LDS reads)
-    const float4* o4 = reinterpret_cast<const float4*>(body + __umul24(code >> 2, kBodyStride));
-    const float4 m0 = o4[0], m1 = o4[1], m2 = o4[2], sh = o4[4];  // M and t as floats 0..11, the shape as 16..19
-    const float sel = (float)((int)(code & 3u) - 1);
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    const __attribute__((address_space(3))) f32x4* o4 =
+        reinterpret_cast<const __attribute__((address_space(3))) f32x4*>(static_cast<uintptr_t>(code >> 2));
+    const f32x4 m0 = o4[0], m1 = o4[1], m2 = o4[2], sh = o4[4];  // M and t as floats 0..11, the shape as 16..19
+    const float sel = (float)(int)__builtin_amdgcn_sbfe((int)code, 0, 2);  // -1, 0 or +1
     const float lx = sh.x * tv.x;
     const float ly = sh.y * tv.y;
     const float lz = __builtin_fmaf(sh.z, tv.z, sel * sh.w);
