@@ -540,3 +540,26 @@ def test_full_size_batches_sampled_against_oracle(torch, pxr, orc, cfg):
         got = dict(frames=frames[e:e + 1].cpu().numpy(), ids=pxr.ids_to_numpy(ids[e:e + 1]))
         assert_parity(got, ref)
     scene.close()
+
+
+def test_outputs_beyond_four_gibibytes(torch, pxr, orc):
+    """A batch whose frames (4.5 GB) and id maps (6 GB) pass 2^32 bytes: offsets are 64-bit all the way.
+    Sampled environments from both ends and around the 4 GiB mark against the oracle."""
+    w = wl.make(4, B=16)
+    B = 212992
+    rng = np.random.default_rng(44)
+    poses = np.ascontiguousarray(w["poses"][rng.integers(0, 16, B)])
+    poses[..., 0, :2] += rng.uniform(-0.3, 0.3, (B, 1, 2)).astype(np.float32)  # (the root moves: every frame differs)
+    scene = pxr.Scene(w["desc"])
+    _bind(torch, scene, w["distractor"])
+    frames, ids = scene.render_batch(torch.from_numpy(poses).cuda(), None, step0=2, want_ids=True)
+    torch.cuda.synchronize()
+    frame_bytes = frames[0].numel()
+    assert frames.numel() > 2 ** 32 and ids.numel() * 4 > 2 ** 32
+    mark = 2 ** 32 // frame_bytes
+    o = orc.Scene(w["desc"])
+    for e in (0, 1, mark - 1, mark, mark + 1, 2 ** 32 // (4 * 84 * 84), B - 2, B - 1):
+        ref = o.render(poses[e:e + 1], None, step0=2, env0=e, distractor=w["distractor"])
+        got = dict(frames=frames[e:e + 1].cpu().numpy(), ids=pxr.ids_to_numpy(ids[e:e + 1]))
+        assert_parity(got, ref)
+    scene.close()
