@@ -56,7 +56,8 @@ struct SceneConsts {
     // light, ground, background
     float l[3], ambient, diffuse;
     float cell, gs[2], bg[3];
-    uint32_t ground_on, cell_is_one;
+    uint32_t ground_on;
+    uint32_t checker_short_form;  // cell == 1 and z_far <= 2^64: no division, and ground points of a frame whose eye is no NaN are no NaNs
     // sizes
     uint32_t W, H, npix, K, root, V, T, P;  // P = entries of the pair table
     uint32_t band_rows;                     // rows of the frame held by the LDS key buffer at a time

@@ -434,7 +434,8 @@ __device__ __forceinline__ u64 ground_key(const SceneConsts& sc, const ResolveCt
 // One pixel: winner of (triangles, ground, background) -> colour -> distractor
 // -> 24-bit RGB.  `low` returns ~id.  `vbytes` = the pixel's three video bytes
 // (R | G<<8 | B<<16), only read in video mode.
-// UNIT_CELL: the checkerboard cell is 1 m, so the division by the cell size is the identity.
+// UNIT_CELL: the checkerboard cell is 1 m, so the division by the cell size is the identity, and the ground point
+// cannot be a NaN (a finite or infinite eye, a far plane within 2^64), so the one-instruction floor-and-convert serves.
 // Triangle g as a 24-bit colour: flat Lambert + ambient in the body frame, then the colour distractor.
 __device__ __forceinline__ uint32_t shade_triangle(const SceneConsts& sc, const ResolveCtx& rc, const float* body, uint32_t g) {
     const float4 ns = reinterpret_cast<const float4*>(sc.tri_shade)[g];
@@ -462,18 +463,21 @@ __device__ __forceinline__ uint32_t shade_triangle(const SceneConsts& sc, const 
 // DEFER_TRIANGLES: a triangle pixel returns 0 here; the caller shades it (compacted over the wavefront).
 template <bool UNIT_CELL, bool DEFER_TRIANGLES = false>
 __device__ __forceinline__ uint32_t resolve_pixel(const SceneConsts& sc, const ResolveCtx& rc, const float* body, u64 key,
-                                                  u64 gkey, float tg, float dwx, float dwy, uint32_t vbytes, uint32_t& low) {
+                                                  u64 gkey, float tg, float dwx, float dwy, uint32_t vbytes, uint32_t& low,
+                                                  u64& tri_lanes) {
     key = key > gkey ? key : gkey;
     low = (uint32_t)key;
+    tri_lanes = __ballot(low > 1u);  // (taken here, beside the branch on the same comparison, it costs nothing)
     if (low > 1u) return DEFER_TRIANGLES ? 0u : shade_triangle(sc, rc, body, 0xFFFFFFFFu - low);
     // background or ground: one of three colours per frame
     int cls = 0;
     if (low == 1u) {
         const float wx = __builtin_fmaf(tg, dwx, rc.eye_x);
         const float wy = __builtin_fmaf(tg, dwy, rc.eye_y);
-        const float ux = UNIT_CELL ? wx : wx / sc.cell;
-        const float uy = UNIT_CELL ? wy : wy / sc.cell;
-        cls = 1 + (((int)__builtin_floorf(ux) + (int)__builtin_floorf(uy)) & 1);
+        if (UNIT_CELL)  // (wx and wy are no NaNs here: the caller has looked at the eye and at z_far)
+            cls = 1 + (int)(((uint32_t)floor_to_int(wx) + (uint32_t)floor_to_int(wy)) & 1u);
+        else
+            cls = 1 + (int)(((uint32_t)(int)__builtin_floorf(wx / sc.cell) + (uint32_t)(int)__builtin_floorf(wy / sc.cell)) & 1u);
     }
     if (rc.mode != PXR_DISTRACT_VIDEO) return rc.base_packed[cls];
     uint32_t rgb = 0;
@@ -516,11 +520,13 @@ __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const Resol
                                 (vid[1] >> 16) | ((vid[2] & 0xFFu) << 16), vid[2] >> 8};
         // without roll the ground test is the row's: ray parameter (0 = miss) and depth bits from the row table
         const float tg_row = NO_ROLL ? row.z : 0.0f;
-        const u64 gkey_row = (NO_ROLL && tg_row != 0.0f) ? (((u64)__float_as_uint(row.w) << 32) | 1ull) : 0ull;
+        // (a miss has depth bits 0 in the table: the key is 0 then)
+        const u64 gkey_row = NO_ROLL ? (((u64)__float_as_uint(row.w) << 32) | (tg_row != 0.0f ? 1ull : 0ull)) : 0ull;
         // the lane's four keys are 32 contiguous, aligned bytes: two 16-byte LDS reads
         const uint4 k01 = reinterpret_cast<const uint4*>(keys + (p0 - p_begin))[0], k23 = reinterpret_cast<const uint4*>(keys + (p0 - p_begin))[1];
         const u64 key4[4] = {((u64)k01.y << 32) | k01.x, ((u64)k01.w << 32) | k01.z, ((u64)k23.y << 32) | k23.x, ((u64)k23.w << 32) | k23.z};
         uint32_t rgb[4], low[4];
+        u64 tri_lanes[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             float tg = tg_row;
@@ -528,12 +534,12 @@ __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const Resol
             if (!NO_ROLL) gkey = ground_key(sc, rc, -__builtin_fmaf(sc.Rt[2], cxs[k], rz), tg);
             const float dwx = __builtin_fmaf(sc.Rt[0], cxs[k], rx);
             const float dwy = __builtin_fmaf(sc.Rt[1], cxs[k], ry);
-            rgb[k] = resolve_pixel<UNIT_CELL, true>(sc, rc, body, key4[k], gkey, tg, dwx, dwy, vb[k], low[k]);
+            rgb[k] = resolve_pixel<UNIT_CELL, true>(sc, rc, body, key4[k], gkey, tg, dwx, dwy, vb[k], low[k], tri_lanes[k]);
         }
         // Triangle pixels are few and clustered: instead of every lane walking the shading code four
         // times, the wavefront compacts its triangle pixels into a list (in the LDS of its own, already
         // consumed, pixel keys), shades the list densely, and the owners pick their colours up.
-        const u64 m0 = __ballot(low[0] > 1u), m1 = __ballot(low[1] > 1u), m2 = __ballot(low[2] > 1u), m3 = __ballot(low[3] > 1u);
+        const u64 m0 = tri_lanes[0], m1 = tri_lanes[1], m2 = tri_lanes[2], m3 = tri_lanes[3];
         if (m0 | m1 | m2 | m3) {
             uint32_t* list = reinterpret_cast<uint32_t*>(keys + ((q - lane) * 4 - p_begin));  // 256 keys = 512 words
             const uint32_t n0 = (uint32_t)__popcll(m0), n1 = n0 + (uint32_t)__popcll(m1), n2 = n1 + (uint32_t)__popcll(m2);
@@ -908,7 +914,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         uint32_t* out_ids = ids ? ids + (size_t)frame * sc.npix : nullptr;
         if (PX == 4) {
             // uniform scene properties select a specialised loop (kept out of the per-pixel code)
-            if (sc.cell_is_one) {
+            // (an eye that is a NaN makes ground points NaNs: such a frame takes the general loop, which is exact
+            // for a unit cell as well)
+            if (sc.checker_short_form && eye_x == eye_x && eye_y == eye_y) {
                 if (no_roll)
                     resolve_rows4<NT, true, true>(sc, rc, body, cxcy, rows, keys, out, out_ids, tid, p_begin, p_end);
                 else
@@ -936,7 +944,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
                     vbytes = (uint32_t)v[0] | ((uint32_t)v[1] << 8) | ((uint32_t)v[2] << 16);
                 }
                 uint32_t low;
-                const uint32_t rgb = resolve_pixel<false>(sc, rc, body, keys[p - p_begin], gkey, tg, dwx, dwy, vbytes, low);
+                u64 unused;
+                const uint32_t rgb = resolve_pixel<false>(sc, rc, body, keys[p - p_begin], gkey, tg, dwx, dwy, vbytes, low, unused);
                 out[(size_t)p * 3 + 0] = (uint8_t)(rgb & 0xFFu);
                 out[(size_t)p * 3 + 1] = (uint8_t)((rgb >> 8) & 0xFFu);
                 out[(size_t)p * 3 + 2] = (uint8_t)(rgb >> 16);

@@ -432,7 +432,9 @@ int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
     c.diffuse = d.diffuse;
     c.ground_on = d.ground_enabled ? 1u : 0u;
     c.cell = d.ground_cell;
-    c.cell_is_one = d.ground_cell == 1.0f ? 1u : 0u;
+    // A ground point is eye + t * direction with t <= z_far and |direction| < 2^30 (fov < 180 degrees as a float,
+    // images up to 512 pixels): with z_far <= 2^64 the product is finite, and the sum is a NaN only if the eye is.
+    c.checker_short_form = (d.ground_cell == 1.0f && d.z_far <= 0x1p64f) ? 1u : 0u;
     const double lz = ld.z / ld_len;
     const double lit = (double)d.ambient + (double)d.diffuse * (lz > 0.0 ? lz : 0.0);
     c.gs[0] = (float)((double)d.ground_grey[0] * lit);

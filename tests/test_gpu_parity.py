@@ -400,6 +400,29 @@ def test_rejected_and_degenerate_inputs(torch, pxr, orc):
     assert not np.any(ref["ids"][4] == GROUND)  # camera below the plane: no ground
 
 
+@pytest.mark.parametrize("over", [dict(), dict(cam_up=(0.2, 0.1, 1.0)), dict(z_far=1.0e30),
+                                  dict(z_far=3.0e38, cam_up=(0.2, 0.1, 1.0)), dict(ground_cell=0.37)])
+def test_checker_cells_of_non_finite_and_huge_ground_points(torch, pxr, orc, over):
+    """The unit-cell checker takes a shorter floor-and-convert that is only right when the ground point is no NaN:
+    frames whose eye is a NaN, and scenes whose far plane lets the ray parameter overflow, must take the long form."""
+    w = wl.make(1, B=12)
+    p = w["poses"].copy()
+    r = w["desc"]["root_body"]
+    p[0, 0, r, 0] = np.nan
+    p[1, 0, r, 1] = np.nan
+    p[2, 0, r, 0] = np.inf
+    p[3, 0, r, 1] = -np.inf
+    p[4, 0, r, :2] = (np.inf, np.nan)
+    p[5, 0, r, :2] = (-3.0e38, 3.0e38)
+    p[6, 0, r, :2] = (2147483647.0, -2147483648.0)   # cell indices at the ends of int32
+    p[7, 0, r, :2] = (2147483520.0, -2147483904.0)   # the floats next to them
+    p[8, 0, r, :2] = (-0.0, 1.0e-30)
+    p[9, 0, r, 2] = 3.0e38                           # eye so high that the ground is beyond any far plane
+    p[10, 0, r, 2] = np.inf
+    w = dict(w, poses=p, desc=dict(w["desc"], **over))
+    assert_parity(gpu_render(torch, pxr, w), oracle_render(orc, w))
+
+
 def test_ground_variants(torch, pxr, orc):
     w = wl.make(1, B=8)
     for over in (dict(ground_enabled=False), dict(ground_cell=0.37), dict(z_far=4.0), dict(cam_up=(0.2, 0.1, 1.0)),
