@@ -406,14 +406,16 @@ struct FrameUniforms {  // written in phase 0 (one lane) or by LDS atomics, read
 };
 
 // Everything phase 4 needs that is uniform over the frame.
+static_assert((offsetof(FrameUniforms, base_packed) + 4) % 8 == 0, "the first grey's word must be 8-byte aligned");
+
 struct ResolveCtx {
     float eye_x, eye_y, eye_z, inv_ez;
     bool ground_ok;
     uint32_t mode;
     float alpha;
     float scale[3], offs[3];
-    const float* base_col;        // LDS [3][3]
-    const uint32_t* base_packed;  // LDS [3]
+    uint32_t col_addr;     // LDS byte address of the three colours as floats [3][3]
+    uint32_t packed_addr;  // and as packed bytes [3]
     const uint8_t* vframe;
 };
 
@@ -460,6 +462,17 @@ __device__ __forceinline__ uint32_t shade_triangle(const SceneConsts& sc, const 
     return rgb;
 }
 
+// Sum of the two checker cell indices where the pixel's ray (parameter tg, direction dwx, dwy) meets the ground:
+// its lowest bit says which of the two greys shows.
+template <bool UNIT_CELL>
+__device__ __forceinline__ uint32_t checker_cells(const SceneConsts& sc, const ResolveCtx& rc, float tg, float dwx, float dwy) {
+    const float wx = __builtin_fmaf(tg, dwx, rc.eye_x);
+    const float wy = __builtin_fmaf(tg, dwy, rc.eye_y);
+    if (UNIT_CELL)  // (wx and wy are no NaNs here: the caller has looked at the eye and at z_far)
+        return (uint32_t)floor_to_int(wx) + (uint32_t)floor_to_int(wy);
+    return (uint32_t)(int)__builtin_floorf(wx / sc.cell) + (uint32_t)(int)__builtin_floorf(wy / sc.cell);
+}
+
 // DEFER_TRIANGLES: a triangle pixel returns 0 here; the caller shades it (compacted over the wavefront).
 template <bool UNIT_CELL, bool DEFER_TRIANGLES = false>
 __device__ __forceinline__ uint32_t resolve_pixel(const SceneConsts& sc, const ResolveCtx& rc, const float* body, u64 key,
@@ -469,21 +482,24 @@ __device__ __forceinline__ uint32_t resolve_pixel(const SceneConsts& sc, const R
     low = (uint32_t)key;
     tri_lanes = __ballot(low > 1u);  // (taken here, beside the branch on the same comparison, it costs nothing)
     if (low > 1u) return DEFER_TRIANGLES ? 0u : shade_triangle(sc, rc, body, 0xFFFFFFFFu - low);
-    // background or ground: one of three colours per frame
-    int cls = 0;
-    if (low == 1u) {
-        const float wx = __builtin_fmaf(tg, dwx, rc.eye_x);
-        const float wy = __builtin_fmaf(tg, dwy, rc.eye_y);
-        if (UNIT_CELL)  // (wx and wy are no NaNs here: the caller has looked at the eye and at z_far)
-            cls = 1 + (int)(((uint32_t)floor_to_int(wx) + (uint32_t)floor_to_int(wy)) & 1u);
-        else
-            cls = 1 + (int)(((uint32_t)(int)__builtin_floorf(wx / sc.cell) + (uint32_t)(int)__builtin_floorf(wy / sc.cell)) & 1u);
+    // background or ground: one of three colours per frame (consecutive in LDS: background, grey 0, grey 1)
+    if (rc.mode != PXR_DISTRACT_VIDEO) {
+        uint32_t word = rc.packed_addr;
+        if (low == 1u) word = rc.packed_addr + 4u + ((checker_cells<UNIT_CELL>(sc, rc, tg, dwx, dwy) & 1u) << 2);
+        return lds_u32_at(word);
     }
-    if (rc.mode != PXR_DISTRACT_VIDEO) return rc.base_packed[cls];
+    uint32_t col = rc.col_addr;
+    if (low == 1u) {
+        uint32_t grey = checker_cells<UNIT_CELL>(sc, rc, tg, dwx, dwy) & 1u;
+        asm("" : "+v"(grey));  // (kept from the compiler, which would turn the multiply-add into compare, select, add)
+        col = __umul24(grey, 12u) + (rc.col_addr + 12u);
+    }
+    const __attribute__((address_space(3))) float* c3 =
+        reinterpret_cast<const __attribute__((address_space(3))) float*>(static_cast<uintptr_t>(col));
     uint32_t rgb = 0;
 #pragma unroll
     for (int ch = 0; ch < 3; ++ch) {
-        const float c = rc.base_col[cls * 3 + ch];
+        const float c = c3[ch];
         const float vf = (float)((vbytes >> (8 * ch)) & 0xFFu) * (1.0f / 255.0f);
         rgb |= quantise(__builtin_fmaf(rc.alpha, vf - c, c)) << (8 * ch);
     }
@@ -527,14 +543,46 @@ __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const Resol
         const u64 key4[4] = {((u64)k01.y << 32) | k01.x, ((u64)k01.w << 32) | k01.z, ((u64)k23.y << 32) | k23.x, ((u64)k23.w << 32) | k23.z};
         uint32_t rgb[4], low[4];
         u64 tri_lanes[4];
+        if (rc.mode != PXR_DISTRACT_VIDEO) {
+            // One of the frame's three colours (background, two greys: consecutive words in LDS), without a branch
+            // per pixel.  A triangle pixel picks up one of them as well, to be overwritten below.  Without roll a
+            // row is ground or sky as a whole, so the choice between "background" and "a grey by the checker" is the
+            // lane's, not the pixel's.
+            const bool ground_row = tg_row != 0.0f;
+            // (the first grey sits at a multiple of 8 bytes: "+ 4 for the second" is an "or")
+            const uint32_t lane_word = rc.packed_addr + ((NO_ROLL && ground_row) ? 4u : 0u);
+            const uint32_t lane_mask = (NO_ROLL && ground_row) ? 4u : 0u;
+            const bool ground_in_sight = !NO_ROLL || __ballot(ground_row) != 0ull;  // (a wavefront above the horizon)
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            float tg = tg_row;
-            u64 gkey = gkey_row;
-            if (!NO_ROLL) gkey = ground_key(sc, rc, -__builtin_fmaf(sc.Rt[2], cxs[k], rz), tg);
-            const float dwx = __builtin_fmaf(sc.Rt[0], cxs[k], rx);
-            const float dwy = __builtin_fmaf(sc.Rt[1], cxs[k], ry);
-            rgb[k] = resolve_pixel<UNIT_CELL, true>(sc, rc, body, key4[k], gkey, tg, dwx, dwy, vb[k], low[k], tri_lanes[k]);
+            for (int k = 0; k < 4; ++k) {
+                float tg = tg_row;
+                u64 gkey = gkey_row;
+                if (!NO_ROLL) gkey = ground_key(sc, rc, -__builtin_fmaf(sc.Rt[2], cxs[k], rz), tg);
+                const u64 key = key4[k] > gkey ? key4[k] : gkey;
+                low[k] = (uint32_t)key;
+                tri_lanes[k] = __ballot(low[k] > 1u);
+                uint32_t word = lane_word;
+                if (ground_in_sight) {
+                    const float dwx = __builtin_fmaf(sc.Rt[0], cxs[k], rx);
+                    const float dwy = __builtin_fmaf(sc.Rt[1], cxs[k], ry);
+                    const uint32_t cells = checker_cells<UNIT_CELL>(sc, rc, tg, dwx, dwy);
+                    if (NO_ROLL)
+                        word = lane_word | ((cells << 2) & lane_mask);
+                    else
+                        word = low[k] == 1u ? rc.packed_addr + 4u + ((cells & 1u) << 2) : rc.packed_addr;
+                }
+                rgb[k] = lds_u32_at(word);
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                float tg = tg_row;
+                u64 gkey = gkey_row;
+                if (!NO_ROLL) gkey = ground_key(sc, rc, -__builtin_fmaf(sc.Rt[2], cxs[k], rz), tg);
+                const float dwx = __builtin_fmaf(sc.Rt[0], cxs[k], rx);
+                const float dwy = __builtin_fmaf(sc.Rt[1], cxs[k], ry);
+                rgb[k] = resolve_pixel<UNIT_CELL, true>(sc, rc, body, key4[k], gkey, tg, dwx, dwy, vb[k], low[k], tri_lanes[k]);
+            }
         }
         // Triangle pixels are few and clustered: instead of every lane walking the shading code four
         // times, the wavefront compacts its triangle pixels into a list (in the LDS of its own, already
@@ -907,8 +955,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
             rc.scale[c] = fu->scale[c];
             rc.offs[c] = fu->offs[c];
         }
-        rc.base_col = &fu->base_col[0][0];
-        rc.base_packed = fu->base_packed;
+        rc.col_addr = sc.lds_misc + (uint32_t)offsetof(FrameUniforms, base_col);
+        rc.packed_addr = sc.lds_misc + (uint32_t)offsetof(FrameUniforms, base_packed);
         if (rc.mode == PXR_DISTRACT_VIDEO) rc.vframe = dc.video + (size_t)fu->video_frame * sc.npix * 3;
         uint8_t* out = frames + (size_t)frame * sc.npix * 3;
         uint32_t* out_ids = ids ? ids + (size_t)frame * sc.npix : nullptr;
