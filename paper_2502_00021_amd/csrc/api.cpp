@@ -78,7 +78,9 @@ int pxr_create_scene(const pxr_scene_desc* desc, pxr_scene** out) {
     // the vertices' cell codes (the kernel reads them without any address arithmetic): code v sits at
     // lds_keys + 4 v of the dynamic LDS segment, which starts at address 0 (prepare_kernels checks that the
     // kernels have no static LDS in front of it).
-    if ((uint64_t)hs.c.lds_keys + 4ull * hs.c.V > 0x10000ull)
+    // It is padded to a multiple of 64 entries (a wavefront reads 64 without a bounds test) with entries that
+    // hold no triangle and point four times at the word after the last code, which the kernel sets to code 0.
+    if ((uint64_t)hs.c.lds_keys + 4ull * (hs.c.V + 1ull) > 0x10000ull)
         return fail(PXR_ERR_UNSUPPORTED, "pxr_create_scene: too many vertices for 16-bit LDS addresses in the pair table");
     std::vector<uint32_t> pair_dev(hs.pair_tbl);
     for (size_t p = 0; p < pair_dev.size() / 4; ++p)
@@ -86,6 +88,13 @@ int pxr_create_scene(const pxr_scene_desc* desc, pxr_scene** out) {
             const uint32_t q = hs.pair_tbl[p * 4 + w];
             pair_dev[p * 4 + w] = (hs.c.lds_keys + 4u * (q & 0xFFFFu)) | ((hs.c.lds_keys + 4u * (q >> 16)) << 16);
         }
+    const uint32_t zero_code_at = hs.c.lds_keys + 4u * hs.c.V;
+    while ((pair_dev.size() / 4) % 64 != 0) {
+        pair_dev.push_back(zero_code_at | (zero_code_at << 16));
+        pair_dev.push_back(zero_code_at | (zero_code_at << 16));
+        pair_dev.push_back(pxr::kNoTriangle | (pxr::kNoTriangle << 16));
+        pair_dev.push_back(0u);
+    }
     // Likewise the device copy of the vertex templates: its fourth word holds the LDS byte address of the body's
     // record, shifted left by 2, and the cap selector as a 2-bit two's-complement number (-1, 0, +1) below it, in
     // place of body << 2 | (selector + 1).
@@ -97,10 +106,14 @@ int pxr_create_scene(const pxr_scene_desc* desc, pxr_scene** out) {
         const uint32_t dev = (body_at << 2) | sel;
         std::memcpy(&vtmpl_dev[v * 4 + 3], &dev, 4);
     }
+    // Behind the bodies' constants: the rows (right, up, forward) of the view rotation and the light direction, for
+    // the lanes of the kernel's set-up phase that take one row each.
+    std::vector<float> body_dev(hs.body_const);
+    for (const float* row : {hs.c.Rt, hs.c.Up, hs.c.Fw, hs.c.l}) body_dev.insert(body_dev.end(), row, row + 3);
     Part parts[6] = {{vtmpl_dev.data(), vtmpl_dev.size() * 4, 0},
                      {hs.tri_idx.data(), hs.tri_idx.size() * 4, 0},
                      {hs.tri_shade.data(), hs.tri_shade.size() * 4, 0},
-                     {hs.body_const.data(), hs.body_const.size() * 4, 0},
+                     {body_dev.data(), body_dev.size() * 4, 0},
                      {hs.cxcy.data(), hs.cxcy.size() * 4, 0},
                      {pair_dev.data(), pair_dev.size() * 4, 0}};
     size_t total = 0;
@@ -129,6 +142,7 @@ int pxr_create_scene(const pxr_scene_desc* desc, pxr_scene** out) {
     s->sc.body_const = reinterpret_cast<const float*>(base + parts[3].off);
     s->sc.cxcy = reinterpret_cast<const float*>(base + parts[4].off);
     s->sc.pair_tbl = reinterpret_cast<const uint32_t*>(base + parts[5].off);
+    s->sc.P = (uint32_t)(pair_dev.size() / 4);  // (with the padding)
 
     rc = pxr::prepare_kernels(s->sc.lds_total, err);
     if (rc != PXR_OK) {

@@ -59,7 +59,7 @@ struct SceneConsts {
     uint32_t ground_on;
     uint32_t checker_short_form;  // cell == 1 and z_far <= 2^64: no division, and ground points of a frame whose eye is no NaN are no NaNs
     // sizes
-    uint32_t W, H, npix, K, root, V, T, P;  // P = entries of the pair table
+    uint32_t W, H, npix, K, root, V, T, P;  // P = entries of the pair table (on the device: padded to a multiple of 64)
     uint32_t band_rows;                     // rows of the frame held by the LDS key buffer at a time
     uint32_t magicW;  // ceil(2^32 / W): p / W == mulhi(p, magicW) for every pixel index p < 512 * W
     // device tables
@@ -69,8 +69,9 @@ struct SceneConsts {
     const float* tri_shade;   // [T][4]  unit normal (body frame), colour multiplier
     const uint32_t* pair_tbl; // [P][4]  a0 | a1<<16 , a2 | a3<<16 , triA | triB<<16 , 0 (a_i = LDS byte address of the cell
                               //         code of vertex q_i; the host-side table holds q_i itself): two triangles sharing the
-                              //         edge q0-q2, or one triangle (q3 = q2, triB = kNoTriangle)
-    const float* body_const;  // [K][8]  shape a,b,c,h ; rgb r,g,b,0
+                              //         edge q0-q2, or one triangle (q3 = q2, triB = kNoTriangle); the device copy ends with padding entries
+    //         (no triangles; the four addresses are that of the word after the last vertex's code, which holds code 0)
+    const float* body_const;  // [K][8]  shape a,b,c,h ; rgb r,g,b,0   then, on the device, [4][3]: Rt, Up, Fw, l
     const float* cxcy;        // [W+H]   pixel-centre ray slopes
     // LDS carve-up (byte offsets into the dynamic segment)
     // the lds_keys region first holds the per-vertex cell codes (u32[V]) and the candidate list (u16[T])

@@ -335,6 +335,13 @@ __device__ __forceinline__ uint32_t lds_u32_at(uint32_t byte_address) {
     return *reinterpret_cast<const __attribute__((address_space(3))) uint32_t*>(static_cast<uintptr_t>(byte_address));
 }
 
+// Low half times high half of a word (non-zero iff both are), in one instruction.
+__device__ __forceinline__ uint32_t halves_product(uint32_t x) {
+    uint32_t r;
+    asm("v_mul_u32_u24_sdwa %0, %1, %1 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:WORD_1 src1_sel:WORD_0" : "=v"(r) : "v"(x));
+    return r;
+}
+
 __device__ __forceinline__ uint32_t lanes_below(u64 m) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
 }
@@ -631,7 +638,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     u64* keys = reinterpret_cast<u64*>(lds + sc.lds_keys);
     // the key buffer's LDS holds the cell codes and the candidate list until the keys are cleared
     uint32_t* vm = reinterpret_cast<uint32_t*>(lds + sc.lds_keys);
-    uint16_t* cand = reinterpret_cast<uint16_t*>(lds + sc.lds_keys + sc.V * 4);
+    uint16_t* cand = reinterpret_cast<uint16_t*>(lds + sc.lds_keys + sc.V * 4 + 4);  // (after the word of code 0)
     int2* vxy = reinterpret_cast<int2*>(lds + sc.lds_vxy);
     float* vd = reinterpret_cast<float*>(lds + sc.lds_vd);
     float* body = reinterpret_cast<float*>(lds + sc.lds_body);
@@ -666,6 +673,13 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         // has three rows, the light direction is the fourth): a quarter of the dot products on the chain.
         const uint32_t b = tid >> 2, part = tid & 3u;
         const float* p = pose + b * 7;
+        // Everything the lane will need from memory is requested here, in one go: the pose, the lane's row of
+        // (right, up, forward, light) from the table behind the bodies' constants, the body's shape and colour
+        // (all four lanes of a body ask for the same: one request).
+        const float* vr = sc.body_const + sc.K * 8u + 3u * part;
+        const float r0 = vr[0], r1 = vr[1], r2 = vr[2];
+        const float4 shp = *reinterpret_cast<const float4*>(shapes ? shapes + ((size_t)e * sc.K + b) * 4 : sc.body_const + b * 8);
+        const float4 col = *reinterpret_cast<const float4*>(sc.body_const + b * 8 + 4);
         const float w = p[3], x = p[4], y = p[5], z = p[6];
         float R[3][3];
         R[0][0] = 1.0f - 2.0f * (y * y + z * z);
@@ -678,21 +692,14 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         R[2][1] = 2.0f * (y * z + w * x);
         R[2][2] = 1.0f - 2.0f * (x * x + y * y);
         const float dx = p[0] - eye_x, dy = p[1] - eye_y, dz = p[2] - eye_z;
-        const float r0 = part == 0u ? sc.Rt[0] : (part == 1u ? sc.Up[0] : (part == 2u ? sc.Fw[0] : sc.l[0]));
-        const float r1 = part == 0u ? sc.Rt[1] : (part == 1u ? sc.Up[1] : (part == 2u ? sc.Fw[1] : sc.l[1]));
-        const float r2 = part == 0u ? sc.Rt[2] : (part == 1u ? sc.Up[2] : (part == 2u ? sc.Fw[2] : sc.l[2]));
         float* o = body + b * kBodyStride;
 #pragma unroll
         for (int c = 0; c < 3; ++c) o[3u * part + (part == 3u ? 3u : 0u) + c] = dot3(r0, r1, r2, R[0][c], R[1][c], R[2][c]);
-        if (part < 3u) {
-            o[9u + part] = dot3(r0, r1, r2, dx, dy, dz);
-        } else {
-            const float* shp = shapes ? shapes + ((size_t)e * sc.K + b) * 4 : sc.body_const + b * 8;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) o[16 + c] = shp[c];
-#pragma unroll
-            for (int c = 0; c < 3; ++c) o[20 + c] = sc.body_const[b * 8 + 4 + c];
-        }
+        if (part < 3u) o[9u + part] = dot3(r0, r1, r2, dx, dy, dz);
+        // (written by all four lanes, the same values: in a branch of its own the compiler would request them
+        // only there, after the arithmetic, and the first wavefront would wait for memory twice)
+        *reinterpret_cast<float4*>(o + 16) = shp;
+        *reinterpret_cast<float4*>(o + 20) = col;  // (the fourth float is padding)
     }
     if (tid >= 64u) {
         // The second wavefront on: one lane per image row prepares what all pixels of the row share: the row
@@ -803,6 +810,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
 
     // ---- phase 1: instancing + projection + snap + cell code (one lane per template vertex)
     const bool recip_long_form = !(sc.z_near >= kRecipMin);
+    if (tid == NT - 1) vm[sc.V] = 0u;  // the code that the padding of the pair table points at: no pixel centre on either axis
     for (uint32_t v = tid; v < sc.V; v += NT) {
         float pvx, pvy, pvz;
         view_position(sc, body, v, pvx, pvy, pvz);
@@ -833,29 +841,29 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     // ---- phase 2a: coarse binning, one lane per pair of edge-sharing triangles (q0,q1,q2), (q0,q2,q3).
     // A triangle can hold a pixel centre only if, on both axes, its vertices' cell codes are not all
     // equal-and-even; the xor of the codes tells (low half = x, high half = y).
-    for (uint32_t p0 = 0; p0 < sc.P; p0 += NT) {
-        const uint32_t p = p0 + tid;
-        bool keep_a = false, keep_b = false;
-        uint32_t ta = 0, tb = 0;
-        if (p < sc.P) {
-            const uint4 rec = reinterpret_cast<const uint4*>(sc.pair_tbl)[p];
-            const uint32_t w0 = rec.x, w1 = rec.y, w2 = rec.z;
-            const uint32_t m0 = lds_u32_at(w0 & 0xFFFFu), m1 = lds_u32_at(w0 >> 16), m2 = lds_u32_at(w1 & 0xFFFFu), m3 = lds_u32_at(w1 >> 16);
-            const uint32_t odd = m0 & 0x00010001u, x02 = m0 ^ m2;
-            const uint32_t da = (m0 ^ m1) | x02 | odd, db = x02 | (m0 ^ m3) | odd;
-            ta = w2 & 0xFFFFu;
-            tb = w2 >> 16;
-            keep_a = (da & 0xFFFFu) != 0u && da > 0xFFFFu;
-            keep_b = (db & 0xFFFFu) != 0u && db > 0xFFFFu && tb != kNoTriangle;
-        }
-        const u64 ma = __ballot(keep_a), mb = __ballot(keep_b);
+    // The device table is padded to whole wavefronts with entries whose four addresses are those of a word that holds
+    // code 0 (never a candidate), so no lane needs a bounds test, and a wavefront past the end leaves.  "Both halves
+    // non-zero" is one 16 x 16-bit product; the ballots are taken from single comparisons (their masks as they
+    // are) and combined as scalars.
+    const uint32_t wave_first = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid & ~63u));
+    for (uint32_t p0 = wave_first; p0 < sc.P; p0 += NT) {
+        const uint4 rec = reinterpret_cast<const uint4*>(sc.pair_tbl)[p0 + lane];
+        const uint32_t w0 = rec.x, w1 = rec.y, w2 = rec.z;
+        const uint32_t m0 = lds_u32_at(w0 & 0xFFFFu), m1 = lds_u32_at(w0 >> 16), m2 = lds_u32_at(w1 & 0xFFFFu), m3 = lds_u32_at(w1 >> 16);
+        const uint32_t odd = m0 & 0x00010001u, x02 = m0 ^ m2;
+        const uint32_t da = (m0 ^ m1) | x02 | odd, db = x02 | (m0 ^ m3) | odd;
+        const uint32_t ta = w2 & 0xFFFFu, tb = w2 >> 16;
+        const bool keep_a = halves_product(da) != 0u;
+        const bool both_b = halves_product(db) != 0u, has_b = tb != kNoTriangle;
+        const bool keep_b = both_b && has_b;
+        const u64 ma = __ballot(keep_a), mb = __ballot(both_b) & __ballot(has_b);
         if (ma | mb) {
             uint32_t base = 0;
             if (lane == 0) base = atomicAdd(&fu->n_cand, (uint32_t)(__popcll(ma) + __popcll(mb)));
             base = (uint32_t)__builtin_amdgcn_readfirstlane((int)base);
-            const uint32_t slot = base + lanes_below(ma) + lanes_below(mb);
-            if (keep_a) cand[slot] = (uint16_t)ta;
-            if (keep_b) cand[slot + (keep_a ? 1u : 0u)] = (uint16_t)tb;
+            // (the first triangles of the wavefront's entries, then the second ones: the order is free)
+            if (keep_a) cand[base + lanes_below(ma)] = (uint16_t)ta;
+            if (keep_b) cand[base + (uint32_t)__popcll(ma) + lanes_below(mb)] = (uint16_t)tb;
         }
     }
     PXR_TIMED_BARRIER(2);

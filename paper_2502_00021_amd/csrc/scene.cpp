@@ -449,7 +449,7 @@ int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
         c.band_rows = (c.H + n_bands - 1) / n_bands;
         uint32_t o = 0;
         c.lds_keys = o;  // 16-byte aligned regions first
-        o += align(std::max(c.band_rows * c.W * 8, c.V * 4 + c.T * 2), 16);
+        o += align(std::max(c.band_rows * c.W * 8, c.V * 4 + 4 + c.T * 2), 16);  // (V codes, one word of code 0, T candidates)
         c.lds_cxcy = o;
         o += align((c.W + c.H) * 4, 16);
         c.lds_rows = o;  // float4 per image row
