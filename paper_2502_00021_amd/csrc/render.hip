@@ -410,6 +410,7 @@ struct FrameUniforms {  // written in phase 0 (one lane) or by LDS atomics, read
     float scale[3], offs[3];
     float base_col[3][3];     // background, ground grey 0, ground grey 1 after the colour distractor
     uint32_t base_packed[3];  // the same three, quantised: R | G<<8 | B<<16
+    float eye[3];             // camera position (written by the first lane in phase 0 for phase 4)
 };
 
 // Everything phase 4 needs that is uniform over the frame.
@@ -656,10 +657,18 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     const uint32_t env = env0 + e;
     const float* pose = poses + (size_t)frame * sc.K * 7;
 
-    // camera position: fixed world-space offset from the root body
-    const float eye_x = pose[sc.root * 7 + 0] + sc.off[0];
-    const float eye_y = pose[sc.root * 7 + 1] + sc.off[1];
-    const float eye_z = pose[sc.root * 7 + 2] + sc.off[2];
+    // camera position: fixed world-space offset from the root body.
+    // The root's position is fetched with vector loads (through an offset of 0 that the compiler cannot see
+    // through), although it is the same for every lane: as scalar loads they share their counter with the loads
+    // of the kernel's arguments, every wait for one of those would wait for memory as well, and the first
+    // wavefront would request its bodies' poses only after the root's position had arrived.
+    uint32_t opaque_zero = 0u;
+    asm volatile("" : "+v"(opaque_zero));
+    const float* root_pos = pose + sc.root * 7 + opaque_zero;
+    // (Only requested here.  The additions, and with them the wait, are made where phase 0 uses the eye: after the
+    // bodies' lanes have requested their poses, in particular.  Phase 4 gets the eye through LDS, so that these
+    // registers are free in between.)
+    const float root_x = root_pos[0], root_y = root_pos[1], root_z = root_pos[2];
 
     PXR_PHASE_BEGIN();
     // ---- phase 0: per-body transforms, per-frame draws, the three non-triangle colours
@@ -691,7 +700,13 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         R[2][0] = 2.0f * (x * z - w * y);
         R[2][1] = 2.0f * (y * z + w * x);
         R[2][2] = 1.0f - 2.0f * (x * x + y * y);
+        const float eye_x = root_x + sc.off[0], eye_y = root_y + sc.off[1], eye_z = root_z + sc.off[2];
         const float dx = p[0] - eye_x, dy = p[1] - eye_y, dz = p[2] - eye_z;
+        if (tid == 0u) {
+            fu->eye[0] = eye_x;
+            fu->eye[1] = eye_y;
+            fu->eye[2] = eye_z;
+        }
         float* o = body + b * kBodyStride;
 #pragma unroll
         for (int c = 0; c < 3; ++c) o[3u * part + (part == 3u ? 3u : 0u) + c] = dot3(r0, r1, r2, R[0][c], R[1][c], R[2][c]);
@@ -709,6 +724,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         //   rows[j] = (rx, ry, rz, -)                            with roll
         const bool no_roll = sc.Rt[2] == 0.0f;
         ResolveCtx g;
+        const float eye_z = root_z + sc.off[2];
         g.eye_z = eye_z;
         g.inv_ez = 1.0f / eye_z;
         g.ground_ok = sc.ground_on && eye_z > 0.0f;
@@ -949,6 +965,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
 
         // ---- phase 4: resolve + shade + distractor + pack + store
         ResolveCtx rc;
+        const float eye_x = fu->eye[0], eye_y = fu->eye[1], eye_z = fu->eye[2];
         rc.eye_x = eye_x;
         rc.eye_y = eye_y;
         rc.eye_z = eye_z;
