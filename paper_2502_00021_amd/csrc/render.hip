@@ -851,6 +851,11 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         vd[v] = sc.z_near * inv;
         vm[v] = m;
     }
+    // (phase 2a's first table entry depends on nothing in LDS: requested before the barrier, it arrives while the
+    // wavefront waits there; later ones are requested a trip ahead)
+    const uint32_t wave_first = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid & ~63u));
+    uint4 rec_next = make_uint4(0u, 0u, 0u, 0u);
+    if (wave_first < sc.P) rec_next = reinterpret_cast<const uint4*>(sc.pair_tbl)[wave_first + lane];
     PXR_TIMED_BARRIER(1);
     PXR_PHASE_MARK(1);
 
@@ -861,9 +866,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     // code 0 (never a candidate), so no lane needs a bounds test, and a wavefront past the end leaves.  "Both halves
     // non-zero" is one 16 x 16-bit product; the ballots are taken from single comparisons (their masks as they
     // are) and combined as scalars.
-    const uint32_t wave_first = (uint32_t)__builtin_amdgcn_readfirstlane((int)(tid & ~63u));
     for (uint32_t p0 = wave_first; p0 < sc.P; p0 += NT) {
-        const uint4 rec = reinterpret_cast<const uint4*>(sc.pair_tbl)[p0 + lane];
+        const uint4 rec = rec_next;
+        if (p0 + NT < sc.P) rec_next = reinterpret_cast<const uint4*>(sc.pair_tbl)[p0 + NT + lane];
         const uint32_t w0 = rec.x, w1 = rec.y, w2 = rec.z;
         const uint32_t m0 = lds_u32_at(w0 & 0xFFFFu), m1 = lds_u32_at(w0 >> 16), m2 = lds_u32_at(w1 & 0xFFFFu), m3 = lds_u32_at(w1 >> 16);
         const uint32_t odd = m0 & 0x00010001u, x02 = m0 ^ m2;
