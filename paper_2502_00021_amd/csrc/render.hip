@@ -162,18 +162,20 @@ __device__ __forceinline__ int tri_gather(const SceneConsts& sc, uint32_t t, con
     v0 = ti.x & 0xFFFFu;
     v1 = ti.x >> 16;
     v2 = ti.y & 0xFFFFu;
-    const int2 a = vxy[v0], b = vxy[v2], c = vxy[v1];  // (x, y) pairs: one LDS read per vertex
-    s.ax = a.x;
-    s.bx = b.x;
-    s.cx = c.x;
+    // (x, y) pairs: one 8-byte LDS read per vertex (as one integer each: read as pairs, the compiler would fetch
+    // the y's separately, after the test of the x's, in a second round trip)
+    const u64 a = reinterpret_cast<const u64*>(vxy)[v0], b = reinterpret_cast<const u64*>(vxy)[v2], c = reinterpret_cast<const u64*>(vxy)[v1];
+    s.ax = (int)(uint32_t)a;
+    s.bx = (int)(uint32_t)b;
+    s.cx = (int)(uint32_t)c;
     const int minx = imin3(s.ax, s.bx, s.cx), maxx = imax3(s.ax, s.bx, s.cx);
     if (minx <= kBehindX) {  // a sentinel among the three (rare)
         if (minx == kRejectedX) return kTriNone;
         return maxx == kBehindX ? kTriNone : kTriClip;
     }
-    s.ay = a.y;
-    s.by = b.y;
-    s.cy = c.y;
+    s.ay = (int)(uint32_t)(a >> 32);
+    s.by = (int)(uint32_t)(b >> 32);
+    s.cy = (int)(uint32_t)(c >> 32);
     const int miny = imin3(s.ay, s.by, s.cy), maxy = imax3(s.ay, s.by, s.cy);
     // pixel centres sit at 256 i + 128: first centre >= min, last centre <= max
     s.i0 = max(0, (minx + 127) >> 8);
@@ -912,7 +914,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
                     front = (long long)(s.bx - s.ax) * (long long)(s.cy - s.ay) >
                             (long long)(s.by - s.ay) * (long long)(s.cx - s.ax);
                 if (front) {
-                    const uint32_t npx = (uint32_t)((s.i1 - s.i0 + 1) * (s.j1 - s.j0 + 1));
+                    const uint32_t npx = __umul24((uint32_t)(s.i1 - s.i0 + 1), (uint32_t)(s.j1 - s.j0 + 1));  // (each at most 512)
                     cls = npx <= kTinyMaxPixels ? 1 : (npx <= kSmallMaxPixels ? 2 : 3);
                 }
             }
