@@ -151,14 +151,13 @@ __device__ __forceinline__ void raster_rows(const TriSetup& s, uint32_t tri, uin
     }
 }
 
-// Gather a triangle's snapped vertices and its clamped pixel-centre range.
+// Gather the snapped vertices of a triangle (ti = its entry of the index table) and its clamped pixel-centre range.
 // Returns kTriNone if a vertex is unusable, all of them lie behind the near plane or no pixel centre is
 // inside the bounding box; kTriClip if the triangle straddles the near plane (nothing else is valid
 // then); kTriPlain otherwise.  `small_extent` = both fixed-point extents below 2^15.
 enum { kTriNone = 0, kTriPlain = 1, kTriClip = 2 };
-__device__ __forceinline__ int tri_gather(const SceneConsts& sc, uint32_t t, const int2* vxy, TriSetup& s,
+__device__ __forceinline__ int tri_gather(const SceneConsts& sc, const uint2 ti, const int2* vxy, TriSetup& s,
                                           uint32_t& v0, uint32_t& v1, uint32_t& v2, bool& small_extent) {
-    const uint2 ti = reinterpret_cast<const uint2*>(sc.tri_idx)[t];
     v0 = ti.x & 0xFFFFu;
     v1 = ti.x >> 16;
     v2 = ti.y & 0xFFFFu;
@@ -296,13 +295,13 @@ __device__ __forceinline__ void raster_clipped(const SceneConsts& sc, uint32_t t
 // the rows [row_lo, row_hi) that the key buffer currently holds.
 // MAY_CLIP: the bin (the wave-per-triangle one) also holds the triangles that straddle the near plane.
 template <bool MAY_CLIP>
-__device__ __forceinline__ void raster_binned(const SceneConsts& sc, uint32_t t, const float* body, const int2* vxy,
-                                              const float* vd, u64* keys, int r, int shift, int row_lo,
+__device__ __forceinline__ void raster_binned(const SceneConsts& sc, uint32_t t, const uint2 ti, const float* body,
+                                              const int2* vxy, const float* vd, u64* keys, int r, int shift, int row_lo,
                                               int row_hi) {
     TriSetup s;
     uint32_t v0, v1, v2;
     bool small_extent;
-    const int kind = tri_gather(sc, t, vxy, s, v0, v1, v2, small_extent);
+    const int kind = tri_gather(sc, ti, vxy, s, v0, v1, v2, small_extent);
     if (MAY_CLIP && kind == kTriClip) {
         raster_clipped(sc, t, body, vxy, vd, keys, r, row_lo, row_hi);
         return;
@@ -904,7 +903,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
             TriSetup s;
             uint32_t v0, v1, v2;
             bool small_extent;
-            const int kind = tri_gather(sc, t, vxy, s, v0, v1, v2, small_extent);
+            const int kind = tri_gather(sc, reinterpret_cast<const uint2*>(sc.tri_idx)[t], vxy, s, v0, v1, v2, small_extent);
             if (kind == kTriClip) cls = 3;  // clipped, then rastered, by a whole wavefront
             if (kind == kTriPlain) {
                 bool front;
@@ -942,6 +941,19 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         const uint32_t p_begin = row_lo * sc.W, p_end = row_hi * sc.W;
         if (row_lo) __syncthreads();  // the previous band's keys have been resolved
 
+        // The bins are complete: each lane asks now for the first triangle it will raster from the small and from the
+        // tiny bin (its list entry, then its entry of the index table), so that they come in from memory while the keys
+        // are cleared and the barrier is waited at.
+        const u64 bins = fu->bins;
+        const uint32_t n_tiny = (uint32_t)bins & 0xFFFFu, n_small = (uint32_t)bins >> 16, n_large = (uint32_t)(bins >> 32);
+        constexpr uint32_t kTeam = 1u << kSmallLanesLog2;
+        const uint2* tri_table = reinterpret_cast<const uint2*>(sc.tri_idx);
+        // (Asked for without a branch, so that nothing has to wait for the answers here: a lane with no triangle in a
+        // bin reads a list entry that may never have been written and clamps it into the table.)
+        uint32_t t_small = list[sc.T - 1 - min(tid >> kSmallLanesLog2, sc.T - 1u)];
+        uint32_t t_tiny = list[min(NT - 1 - tid, sc.T - 1u)];
+        uint2 ti_small = tri_table[min(t_small, sc.T - 1u)], ti_tiny = tri_table[min(t_tiny, sc.T - 1u)];
+
         // codes and candidates are dead: clear the pixel keys they shared LDS with (0 = background at depth 0)
         // (two keys per store; the region is padded to 16 bytes, so an odd count may clear one key more)
         for (uint32_t p = tid; p < (p_end - p_begin + 1u) >> 1; p += NT)
@@ -951,22 +963,31 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
 
         // ---- phase 3: raster + z-test into the LDS key buffer.  The bins start at different
         // lanes of the workgroup so that all waves get a share.
-        const u64 bins = fu->bins;
-        const uint32_t n_tiny = (uint32_t)bins & 0xFFFFu, n_small = (uint32_t)bins >> 16, n_large = (uint32_t)(bins >> 32);
-
         // The hardware favours a workgroup's older wavefronts when several want to issue, so the youngest finish a
         // phase last: the heavier bin goes to the oldest.
         // small: a team of lanes per triangle, from the first lane up
-        constexpr uint32_t kTeam = 1u << kSmallLanesLog2;
-        for (uint32_t k = tid >> kSmallLanesLog2; k < n_small; k += NT >> kSmallLanesLog2)
-            raster_binned<false>(sc, list[sc.T - 1 - k], body, vxy, vd, keys, (int)(tid & (kTeam - 1u)), (int)kSmallLanesLog2,
+        // (a lane's first triangle of each was requested before the barrier; the next one is at the loop's end)
+        for (uint32_t k = tid >> kSmallLanesLog2; k < n_small;) {
+            raster_binned<false>(sc, t_small, ti_small, body, vxy, vd, keys, (int)(tid & (kTeam - 1u)), (int)kSmallLanesLog2,
                                  (int)row_lo, (int)row_hi);
+            k += NT >> kSmallLanesLog2;
+            if (k < n_small) {
+                t_small = list[sc.T - 1 - k];
+                ti_small = tri_table[t_small];
+            }
+        }
         // tiny: one lane per triangle, from the last lane down
-        for (uint32_t k = NT - 1 - tid; k < n_tiny; k += NT)
-            raster_binned<false>(sc, list[k], body, vxy, vd, keys, 0, 0, (int)row_lo, (int)row_hi);
+        for (uint32_t k = NT - 1 - tid; k < n_tiny;) {
+            raster_binned<false>(sc, t_tiny, ti_tiny, body, vxy, vd, keys, 0, 0, (int)row_lo, (int)row_hi);
+            k += NT;
+            if (k < n_tiny) {
+                t_tiny = list[k];
+                ti_tiny = tri_table[t_tiny];
+            }
+        }
         // large: a whole wave per triangle, starting in the middle waves
         for (uint32_t k = ((tid >> 6) + NT / 128) % (NT / 64); k < n_large; k += NT / 64)
-            raster_binned<true>(sc, list2[k], body, vxy, vd, keys, (int)lane, 6, (int)row_lo, (int)row_hi);
+            raster_binned<true>(sc, list2[k], tri_table[list2[k]], body, vxy, vd, keys, (int)lane, 6, (int)row_lo, (int)row_hi);
         PXR_TIMED_BARRIER(5);
         PXR_PHASE_MARK(5);
 
