@@ -141,7 +141,7 @@ int pxr_apply_distractor(pxr_scene* s, const pxr_distractor_desc* d);
  * Only enqueues and returns: no synchronisation, no host<->device copy, no
  * allocation.  Pose VALUES are not validated: a vertex behind the near plane,
  * far outside the image or non-finite removes its triangles from the frame.
- * Alignment: d_poses, d_shapes, d_frames 4 bytes, d_ids 16 bytes.
+ * Alignment: d_poses, d_frames 4 bytes; d_shapes (16-byte records), d_ids 16 bytes.
  * Errors: INVALID_ARG (null scene/poses/frames, B*S == 0, B*S > 2^31-1,
  * step0 + S or env0 + B overflow, misaligned buffer); DEVICE (launch failure). */
 int pxr_render_batch(pxr_scene* s, const float* d_poses, const float* d_shapes, uint32_t B, uint32_t S,

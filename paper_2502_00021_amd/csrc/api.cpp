@@ -217,9 +217,9 @@ int pxr_render_batch(pxr_scene* s, const float* d_poses, const float* d_shapes, 
     if (n_frames > 0x7FFFFFFFull) return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch: B*S exceeds 2^31-1 frames");
     if ((uint64_t)step0 + S > 0x100000000ull) return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch: step0 + S overflows 32 bits");
     if ((uint64_t)env0 + B > 0x100000000ull) return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch: env0 + B overflows 32 bits");
-    if ((reinterpret_cast<uintptr_t>(d_poses) & 3u) || (reinterpret_cast<uintptr_t>(d_shapes) & 3u) ||
+    if ((reinterpret_cast<uintptr_t>(d_poses) & 3u) || (reinterpret_cast<uintptr_t>(d_shapes) & 15u) ||
         (reinterpret_cast<uintptr_t>(d_frames) & 3u) || (reinterpret_cast<uintptr_t>(d_ids) & 15u))
-        return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch: poses/shapes/frames must be 4-byte and ids 16-byte aligned");
+        return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch: poses/frames must be 4-byte and shapes/ids 16-byte aligned");
     std::string err;
     const int rc = pxr::launch_render(s->sc, s->dc, d_poses, d_shapes, (uint32_t)n_frames, S, step0, env0, d_frames, d_ids,
                                       s->block_threads, hip_stream, err);

@@ -186,9 +186,8 @@ __device__ __forceinline__ int tri_gather(const SceneConsts& sc, const uint2 ti,
 }
 
 // View-space position of template vertex v (the instancing arithmetic of phase 1; also used when a
-// triangle has to be clipped).  Returns the body record the vertex belongs to.
-__device__ __forceinline__ void view_position(const SceneConsts& sc, const float* body, uint32_t v, float& pvx, float& pvy,
-                                              float& pvz) {
+// triangle has to be clipped).  The template's fourth word says where in LDS its body's record is.
+__device__ __forceinline__ void view_position(const SceneConsts& sc, uint32_t v, float& pvx, float& pvy, float& pvz) {
     const float4 tv = reinterpret_cast<const float4*>(sc.vtmpl)[v];
     const uint32_t code = __float_as_uint(tv.w);
     // (body records are 96 bytes at a 16-byte aligned base: four 16-byte LDS reads)
@@ -240,7 +239,7 @@ __device__ __forceinline__ void raster_piece(const SceneConsts& sc, uint32_t t, 
 // code per corner (P << 2 | Q, P == Q for a kept vertex), four corners per pattern, patterns indexed by
 // the in-front mask (bit e = vertex e in front).  Corners are recomputed per piece rather than kept, so
 // that this rarely taken path does not raise the kernel's register count.
-__device__ __forceinline__ void raster_clipped(const SceneConsts& sc, uint32_t t, const float* body, const int2* vxy,
+__device__ __forceinline__ void raster_clipped(const SceneConsts& sc, uint32_t t, const int2* vxy,
                                                const float* vd, u64* keys, int lane, int row_lo, int row_hi) {
 #pragma unroll 1
     for (uint32_t piece = 0; piece < 2u; ++piece) {
@@ -271,9 +270,9 @@ __device__ __forceinline__ void raster_clipped(const SceneConsts& sc, uint32_t t
                 cD[c] = vd[vp];
             } else {
                 float px, py, pz, qx, qy, qz;
-                view_position(sc, body, vp, px, py, pz);
+                view_position(sc, vp, px, py, pz);
                 __builtin_amdgcn_sched_barrier(0);  // one vertex at a time: keeps this path within the register budget
-                view_position(sc, body, vq, qx, qy, qz);
+                view_position(sc, vq, qx, qy, qz);
                 __builtin_amdgcn_sched_barrier(0);
                 const float tt = (sc.z_near - pz) / (qz - pz);
                 const float ix = __builtin_fmaf(tt, qx - px, px);
@@ -295,7 +294,7 @@ __device__ __forceinline__ void raster_clipped(const SceneConsts& sc, uint32_t t
 // the rows [row_lo, row_hi) that the key buffer currently holds.
 // MAY_CLIP: the bin (the wave-per-triangle one) also holds the triangles that straddle the near plane.
 template <bool MAY_CLIP>
-__device__ __forceinline__ void raster_binned(const SceneConsts& sc, uint32_t t, const uint2 ti, const float* body,
+__device__ __forceinline__ void raster_binned(const SceneConsts& sc, uint32_t t, const uint2 ti,
                                               const int2* vxy, const float* vd, u64* keys, int r, int shift, int row_lo,
                                               int row_hi) {
     TriSetup s;
@@ -303,7 +302,7 @@ __device__ __forceinline__ void raster_binned(const SceneConsts& sc, uint32_t t,
     bool small_extent;
     const int kind = tri_gather(sc, ti, vxy, s, v0, v1, v2, small_extent);
     if (MAY_CLIP && kind == kTriClip) {
-        raster_clipped(sc, t, body, vxy, vd, keys, r, row_lo, row_hi);
+        raster_clipped(sc, t, vxy, vd, keys, r, row_lo, row_hi);
         return;
     }
     s.j0 = max(s.j0, row_lo);
@@ -830,7 +829,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     if (tid == NT - 1) vm[sc.V] = 0u;  // the code that the padding of the pair table points at: no pixel centre on either axis
     for (uint32_t v = tid; v < sc.V; v += NT) {
         float pvx, pvy, pvz;
-        view_position(sc, body, v, pvx, pvy, pvz);
+        view_position(sc, v, pvx, pvy, pvz);
         // 1 / pvz is only used when pvz >= z_near (otherwise the vertex is behind the plane or unusable
         // whatever it is), so the short form serves unless some lane's depth is beyond its range
         float inv;
@@ -968,7 +967,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         // small: a team of lanes per triangle, from the first lane up
         // (a lane's first triangle of each was requested before the barrier; the next one is at the loop's end)
         for (uint32_t k = tid >> kSmallLanesLog2; k < n_small;) {
-            raster_binned<false>(sc, t_small, ti_small, body, vxy, vd, keys, (int)(tid & (kTeam - 1u)), (int)kSmallLanesLog2,
+            raster_binned<false>(sc, t_small, ti_small, vxy, vd, keys, (int)(tid & (kTeam - 1u)), (int)kSmallLanesLog2,
                                  (int)row_lo, (int)row_hi);
             k += NT >> kSmallLanesLog2;
             if (k < n_small) {
@@ -978,7 +977,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         }
         // tiny: one lane per triangle, from the last lane down
         for (uint32_t k = NT - 1 - tid; k < n_tiny;) {
-            raster_binned<false>(sc, t_tiny, ti_tiny, body, vxy, vd, keys, 0, 0, (int)row_lo, (int)row_hi);
+            raster_binned<false>(sc, t_tiny, ti_tiny, vxy, vd, keys, 0, 0, (int)row_lo, (int)row_hi);
             k += NT;
             if (k < n_tiny) {
                 t_tiny = list[k];
@@ -987,7 +986,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         }
         // large: a whole wave per triangle, starting in the middle waves
         for (uint32_t k = ((tid >> 6) + NT / 128) % (NT / 64); k < n_large; k += NT / 64)
-            raster_binned<true>(sc, list2[k], tri_table[list2[k]], body, vxy, vd, keys, (int)lane, 6, (int)row_lo, (int)row_hi);
+            raster_binned<true>(sc, list2[k], tri_table[list2[k]], vxy, vd, keys, (int)lane, 6, (int)row_lo, (int)row_hi);
         PXR_TIMED_BARRIER(5);
         PXR_PHASE_MARK(5);
 

@@ -518,6 +518,9 @@ def test_render_argument_errors(torch, pxr):
     assert L.pxr_render_batch(h, poses2.data_ptr(), None, 4, 2, 0xFFFFFFFF, 0, frames2.data_ptr(), None, None) == pxr.ERR_INVALID_ARG
     assert L.pxr_render_batch(h, poses2.data_ptr(), None, 4, 2, 0, 0xFFFFFFFD, frames2.data_ptr(), None, None) == pxr.ERR_INVALID_ARG
     assert L.pxr_render_batch(h, poses.data_ptr(), None, 4, 1, 0, 0, frames.data_ptr() + 1, None, None) == pxr.ERR_INVALID_ARG
+    shapes = torch.ones((5, w["poses"].shape[2], 4), dtype=torch.float32, device="cuda")
+    assert L.pxr_render_batch(h, poses.data_ptr(), shapes.data_ptr() + 4, 4, 1, 0, 0, frames.data_ptr(), None, None) == pxr.ERR_INVALID_ARG
+    assert L.pxr_render_batch(h, poses.data_ptr(), shapes.data_ptr() + 16, 4, 1, 0, 0, frames.data_ptr(), None, None) == pxr.OK
     assert L.pxr_render_batch(h, poses.data_ptr(), None, 1 << 31, 1, 0, 0, frames.data_ptr(), None, None) == pxr.ERR_INVALID_ARG
     assert b"pxr_render_batch" in L.pxr_last_error()
     with pytest.raises(pxr.PxrError):
