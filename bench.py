@@ -274,6 +274,9 @@ def main():
     ap.add_argument("--next-stages-only", action="store_true",
                     help="time only the kinematics and conv-consumer stages of the chosen workload (for profiler runs)")
     ap.add_argument("--extras", action="store_true", help="also time the other configurations (reported under 'others')")
+    ap.add_argument("--phase-clocks", action="store_true",
+                    help="with PXR_LIB set to a build made with --define PXR_PHASE_TIMING (see paper_2502_00021_amd/build.py): "
+                         "report the shader-clock ticks per frame a workgroup spends in each phase of the render kernel")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build renders on ONE GPU (environments are independent, so B shards trivially "
@@ -315,6 +318,16 @@ def main():
         for i in range(warmup):
             scene.render_batch(poses, shapes, step0=i, frames=frames)
         torch.cuda.synchronize()
+        if args.phase_clocks:
+            import ctypes
+            L = pxr.lib()
+            if not hasattr(L, "pxr_debug_phase_cycles"):
+                sys.exit("bench.py --phase-clocks: the loaded library is not a PXR_PHASE_TIMING build (set PXR_LIB)")
+            L.pxr_debug_phase_cycles.argtypes = [ctypes.c_void_p, ctypes.c_int]
+            L.pxr_debug_wave_arrival.argtypes = [ctypes.c_void_p]
+            scratch = (ctypes.c_ulonglong * 128)()
+            L.pxr_debug_phase_cycles(None, 1)
+            L.pxr_debug_wave_arrival(scratch)  # (reading resets)
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
         t0 = time.perf_counter()
         ev[0].record()
@@ -327,6 +340,16 @@ def main():
         info = scene.info()
         res = dict(w=w, B=B, S=S, K=K, H=scene.H, W=scene.W, mode=mode, wall=wall, kernel_ms=kernel_ms, info=info,
                    checksum=int(frames[:: max(1, B // 64)].to(torch.int64).sum().item()))
+        if args.phase_clocks:
+            names = ["0 setup", "1 vertices", "2a coarse", "2b exact", "key clear", "3 raster", "4 resolve"]
+            out = (ctypes.c_ulonglong * 16)()
+            L.pxr_debug_phase_cycles(out, 0)
+            n = float(steps * B * S)
+            res["phase_clocks"] = {"ticks_per_frame": {nm: out[i] / n for i, nm in enumerate(names)}}
+            L.pxr_debug_wave_arrival(scratch)
+            if any(scratch):  # only a PXR_WAVE_ARRIVAL build fills these
+                res["phase_clocks"]["wave_arrival_after_first"] = {
+                    nm: [scratch[i * 16 + k] / n for k in range(16)] for i, nm in enumerate(names[:6])}
         scene.close()
         del frames, poses, shapes
         return res
@@ -363,6 +386,8 @@ def main():
         "kernel_frames_per_s": n_frames / avg_kernel_s,
         "checksum": r["checksum"],
     }
+    if "phase_clocks" in r:
+        out["phase_clocks"] = r["phase_clocks"]  # (a profiling build: `value` is not the product's rate)
     if args.extras:
         # the same fractions against what this GPU sustains right now (microbenchmarks in the library)
         pk = pxr.measure_peaks()

@@ -28,17 +28,32 @@ def stale():
     return any(os.path.getmtime(d) > t for d in deps)
 
 
-def build(force=True, verbose=False, extra=()):
-    if not force and not stale():
+def build(force=True, verbose=False, extra=(), out=None):
+    """Compile the library.  `out`: another file than the in-tree libpxr.so (profiling builds, see __main__)."""
+    if out is None and not force and not stale():
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, *HIPFLAGS, *extra, "-I", os.path.join(ROOT, "include"), "-I", CSRC,
-           *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+           *[os.path.join(CSRC, s) for s in SOURCES], "-o", out or LIB]
     if verbose:
         print(" ".join(cmd))
     subprocess.check_call(cmd)
-    return LIB
+    return out or LIB
 
 
 if __name__ == "__main__":
-    build(verbose=True)
+    # Profiling builds of the render kernel, loaded by setting PXR_LIB to the file:
+    #   --define PXR_STOP_AFTER=k   the kernel returns after phase k = 0..5 (hardware counters of k minus those of
+    #                               k - 1 are phase k's); the frames are NOT rendered
+    #   --define PXR_PHASE_TIMING   the first wavefront of every workgroup notes the shader clock at each barrier
+    #                               (read with `bench.py --phase-clocks`); add --define PXR_WAVE_ARRIVAL for the
+    #                               arrival of every wavefront at every barrier (slower: two barriers per phase)
+    import argparse
+
+    ap = argparse.ArgumentParser(description=__doc__)
+    ap.add_argument("--define", action="append", default=[], metavar="NAME[=VALUE]")
+    ap.add_argument("--out", default=None, help="write the library here instead of in-tree")
+    a = ap.parse_args()
+    if a.define and not a.out:
+        ap.error("a build with --define is a profiling build: give it a file of its own with --out")
+    build(verbose=True, extra=["-D" + d for d in a.define], out=a.out)

@@ -69,9 +69,10 @@ def lib():
     """Load libpxr.so (built in-tree by __graft_entry__.build / paper_2502_00021_amd.build)."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
-            raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` first")
-        L = C.CDLL(LIB_PATH)
+        path = os.environ.get("PXR_LIB") or LIB_PATH  # (PXR_LIB: a profiling build of the same sources)
+        if not os.path.exists(path):
+            raise ImportError(f"{path} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` first")
+        L = C.CDLL(path)
         vp, u32 = C.c_void_p, C.c_uint32
         L.pxr_create_scene.argtypes = [C.POINTER(SceneDesc), C.POINTER(vp)]
         L.pxr_destroy_scene.argtypes = [vp]
