@@ -840,12 +840,17 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         const float sx = __builtin_fmaf(sc.f, pvx * inv, sc.halfW);
         const float sy = __builtin_fmaf(-sc.f, pvy * inv, sc.halfH);
         const bool ok = (pvz >= sc.z_near) && (__builtin_fabsf(sx) <= 16384.0f) && (__builtin_fabsf(sy) <= 16384.0f);
-        int X = pvz < sc.z_near ? kBehindX : kRejectedX, Y = 0;
-        uint32_t m = 0xFFFFFFFFu;  // an unusable or clipped vertex never lets a triangle be discarded early
-        if (ok) {
-            X = floor_to_int(__builtin_fmaf(sx, 256.0f, 0.5f));
-            Y = floor_to_int(__builtin_fmaf(sy, 256.0f, 0.5f));
-            m = cell_code(X, (int)sc.W) | (cell_code(Y, (int)sc.H) << 16);
+        // (worked out for every lane, whatever sx and sy are, and replaced where the vertex is not usable: such
+        // vertices are rare, and a wavefront without one skips the replacement altogether)
+        int X = floor_to_int(__builtin_fmaf(sx, 256.0f, 0.5f));
+        int Y = floor_to_int(__builtin_fmaf(sy, 256.0f, 0.5f));
+        uint32_t m = cell_code(X, (int)sc.W) | (cell_code(Y, (int)sc.H) << 16);
+        if (__builtin_expect(__ballot(!ok) != 0ull, 0)) {
+            if (!ok) {
+                X = pvz < sc.z_near ? kBehindX : kRejectedX;
+                Y = 0;
+                m = 0xFFFFFFFFu;  // an unusable or clipped vertex never lets a triangle be discarded early
+            }
         }
         vxy[v] = make_int2(X, Y);
         vd[v] = sc.z_near * inv;
