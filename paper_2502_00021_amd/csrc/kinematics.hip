@@ -71,16 +71,19 @@ __global__ __launch_bounds__(kFkLanes) void fk_kernel(const SkeletonConsts sk, c
     const uint32_t nf = min(kFkLanes, n_frames - f0);         // frames it holds (ragged tail)
 
     // coalesced loads of the workgroup's contiguous input chunks, transposed into LDS
+    // (index / row length by multiplication: indices stay below 64 * row length, far inside the exact range)
     {
         const float* src = angles + (size_t)f0 * sk.J;
+        const uint32_t magic_j = sk.J > 1u ? 0xFFFFFFFFu / sk.J + 1u : 0u;  // (ceil(2^32 / J); J == 1 needs none)
         for (uint32_t i = lane; i < nf * sk.J; i += kFkLanes) {
-            const uint32_t n = i / sk.J, j = i - n * sk.J;
+            const uint32_t n = sk.J > 1u ? __umulhi(i, magic_j) : i, j = i - n * sk.J;
             ang[j * kFkStride + n] = src[i];
         }
         const uint32_t row = sk.F * 7;
+        const uint32_t magic_f = row ? 0xFFFFFFFFu / row + 1u : 0u;  // (rows are multiples of 7)
         src = free_poses + (size_t)f0 * row;
         for (uint32_t i = lane; i < nf * row; i += kFkLanes) {
-            const uint32_t n = i / row, j = i - n * row;
+            const uint32_t n = __umulhi(i, magic_f), j = i - n * row;
             fre[j * kFkStride + n] = src[i];
         }
     }
@@ -126,9 +129,10 @@ __global__ __launch_bounds__(kFkLanes) void fk_kernel(const SkeletonConsts sk, c
     // coalesced store of the workgroup's contiguous output chunk
     {
         const uint32_t row = sk.K * 7;
+        const uint32_t magic = 0xFFFFFFFFu / row + 1u;
         float* dst = poses + (size_t)f0 * row;
         for (uint32_t i = lane; i < nf * row; i += kFkLanes) {
-            const uint32_t n = i / row, j = i - n * row;
+            const uint32_t n = __umulhi(i, magic), j = i - n * row;
             dst[i] = pose[j * kFkStride + n];
         }
     }
