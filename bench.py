@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch, measured with two rocprofv3 --pmc passes (FETCH_SIZE x 2.000 + WRITE_SIZE x
 # 1.000, the factors a plain 1 GiB copy gives for the same counters); see profiles/.  Others: null.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("cfg5", 65536): 2516.8e6, ("cfg4", 16384): 403.9e6}
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("cfg5", 65536): 2516.8e6, ("cfg4", 16384): 403.5e6}
 
 
 def algorithmic_ops_per_frame(V, T, npix, mode):
