@@ -161,3 +161,22 @@ def test_row_division_constant():
         magic = ((1 << 32) + W - 1) // W
         p = np.arange(512 * W, dtype=np.uint64)
         assert np.array_equal((p * np.uint64(magic)) >> np.uint64(32), p // np.uint64(W))
+
+
+def test_copy_index_constant_of_the_kinematics_stage():
+    """i // n == (i * (0xFFFFFFFF // n + 1)) >> 32 for every index of a 64-frame block of rows of n floats
+    (n >= 2; the kernel leaves n == 1 alone)."""
+    for n in range(2, 641):
+        magic = 0xFFFFFFFF // n + 1
+        assert magic < (1 << 32)
+        i = np.arange(64 * n, dtype=np.uint64)
+        assert np.array_equal((i * np.uint64(magic)) >> np.uint64(32), i // np.uint64(n))
+
+
+def test_profiling_builds_do_not_replace_the_library():
+    """A build with extra definitions is a profiling build and must be given a file of its own."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, "-m", "paper_2502_00021_amd.build", "--define", "PXR_STOP_AFTER=1"],
+                       cwd=ROOT, capture_output=True, text=True)
+    assert r.returncode != 0 and "--out" in r.stderr
