@@ -156,8 +156,9 @@ int pxr_render_batch(pxr_scene* s, const float* d_poses, const float* d_shapes, 
  *   anchor[k]  hinge position in the parent's frame; axis[k] unit hinge axis (same in both frames);
  *   offset[k]  body centre relative to the hinge, in the body's own frame   (each [n_bodies*3])
  * Pose of a hinged body: q = q_parent (x) (cos(a/2), sin(a/2) axis);
- *   p = (p_parent + R(q_parent) anchor) + R(q) offset,  fp32, R as in the vertex stage, sin/cos of a/2 by a
- *   two-term pi/2 reduction and degree-9 / degree-10 Taylor polynomials (device-independent). */
+ *   p = (p_parent + R(q_parent) anchor) + R(q) offset,  fp32, R as in the vertex stage.  sin and cos of a/2 are
+ *   within 1.25 * 2^-24 of the true values for |a| <= 65536 rad; an angle beyond that or a non-finite one makes
+ *   the body's pose, and those of its descendants, NaN (their triangles are not drawn). */
 typedef struct {
     uint32_t n_bodies, n_free, n_angles;
     const int32_t* parent;

@@ -24,6 +24,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstring>
+#include <limits>
 #include <vector>
 
 namespace {
@@ -769,28 +770,21 @@ int orc_render(const orc_scene* s, const float* poses, const float* shapes, uint
 
 // ---------------------------------------------------------------- F: forward kinematics
 //
-// sin(theta/2), cos(theta/2): h = theta/2; k = nearest integer to h*(2/pi) (ties to even);
-// r = h - k*pi/2 with pi/2 split in two fp32 parts; odd / even Taylor polynomials in r
-// (|r| <= pi/4: truncation error below 2e-9); quadrant from k mod 4.
-void orc_sincos_half(float theta, float* s_out, float* c_out) {
-    const float h = 0.5f * theta;
-    const float kf = std::nearbyint(h * 0.636619772f);
-    float r = std::fmaf(kf, -1.57079625f, h);
-    r = std::fmaf(kf, -7.54978942e-08f, r);
-    const float r2 = r * r;
-    float ps = std::fmaf(r2, 2.75573192e-06f, -1.98412698e-04f);
-    ps = std::fmaf(ps, r2, 8.33333333e-03f);
-    ps = std::fmaf(ps, r2, -1.66666667e-01f);
-    const float sp = std::fmaf(r * r2, ps, r);
-    float pc = std::fmaf(r2, -2.75573192e-07f, 2.48015873e-05f);
-    pc = std::fmaf(pc, r2, -1.38888889e-03f);
-    pc = std::fmaf(pc, r2, 4.16666667e-02f);
-    pc = std::fmaf(pc, r2, -0.5f);
-    const float cp = std::fmaf(pc, r2, 1.0f);
-    const int q = (int)kf & 3;
-    *s_out = q == 0 ? sp : (q == 1 ? cp : (q == 2 ? -sp : -cp));
-    *c_out = q == 0 ? cp : (q == 1 ? -sp : (q == 2 ? -cp : sp));
+// sin(theta/2), cos(theta/2) by their definition: the C library's double-precision routines on the exact
+// half angle, each result rounded once to fp32.  Hinge angles beyond +-65536 rad (and non-finite ones) are
+// outside the stage's domain: both come out as NaN, so the body and everything hanging on it vanish from
+// the frame (a NaN vertex drops its triangles).
+namespace {
+void sincos_half(float theta, float* s_out, float* c_out) {
+    if (!(std::fabs(theta) <= 65536.0f)) {
+        *s_out = *c_out = std::numeric_limits<float>::quiet_NaN();
+        return;
+    }
+    const double h = 0.5 * (double)theta;
+    *s_out = (float)std::sin(h);
+    *c_out = (float)std::cos(h);
 }
+}  // namespace
 
 namespace {
 void quat_matrix(const float* q, float R[3][3]) {  // same formulas as the vertex stage (V)
@@ -821,7 +815,7 @@ int orc_fk(uint32_t n_bodies, const int32_t* parent, const int32_t* slot, const 
         const float* pq = pp + 3;
         const float theta = slot[k] >= 0 ? angles[slot[k]] : 0.0f;
         float sn, cs;
-        orc_sincos_half(theta, &sn, &cs);
+        sincos_half(theta, &sn, &cs);
         const float* u = axis + (size_t)k * 3;
         const float jw = cs, jx = sn * u[0], jy = sn * u[1], jz = sn * u[2];
         const float pw = pq[0], px = pq[1], py = pq[2], pz = pq[3];

@@ -22,7 +22,7 @@
  * exact rational point-in-triangle; permutation invariance; analytic and
  * Moller-Trumbore ray casts; horizon row; shade extremes; RNG bijectivity and
  * statistics; distractor identities; kinematics against float64 quaternion algebra (an independent
- * numpy implementation) and libm sin/cos.
+ * numpy implementation) and closed-form hinge geometry.
  * The generator reproduces the published Philox-4x32-10 known-answer vectors
  * (tests/golden/philox4x32_10_kat.txt).
  */
@@ -140,12 +140,12 @@ int orc_render(const orc_scene* s, const float* poses, const float* shapes, uint
  * Body k is either free (parent[k] < 0: its pose is free_poses[slot[k]], copied verbatim) or hangs on
  * body parent[k] < k by a hinge: anchor[k] = hinge position in the parent's frame, axis[k] = unit hinge
  * axis, offset[k] = body centre relative to the hinge in the body's own frame, angle = angles[slot[k]]
- * (slot[k] < 0: rigidly attached, angle 0).  All arithmetic fp32 in a fixed order (orc.cpp, section F).
+ * (slot[k] < 0: rigidly attached, angle 0).  sin and cos of the half angle are the C library's in double,
+ * rounded once to fp32 (NaN for an angle beyond +-65536 rad or non-finite); the quaternion and position
+ * algebra is fp32 in a fixed order (orc.cpp, section F).
  * out_poses[K*7] = px,py,pz,qw,qx,qy,qz.  Returns non-zero on a malformed skeleton. */
 int orc_fk(uint32_t n_bodies, const int32_t* parent, const int32_t* slot, const float* anchor, const float* axis,
            const float* offset, const float* free_poses, const float* angles, float* out_poses);
-/* sin and cos of theta/2 as the kinematics stage computes them (range reduction + polynomials). */
-void orc_sincos_half(float theta, float* s, float* c);
 
 /* Counter-based generator: 10 rounds of the 4x32 multiply/xor network on
  * counter (c0..c3) under the 64-bit key `seed`; out[4]. */

@@ -71,8 +71,6 @@ def lib():
         _lib.orc_u01.restype = f32
         _lib.orc_fk.argtypes = [u32] + [vp] * 8
         _lib.orc_fk.restype = C.c_int
-        _lib.orc_sincos_half.argtypes = [f32, vp, vp]
-        _lib.orc_sincos_half.restype = None
     return _lib
 
 
@@ -243,12 +241,6 @@ def philox(seed, c0, c1, c2, c3):
 
 def u01(x):
     return float(lib().orc_u01(int(x)))
-
-
-def sincos_half(theta):
-    s, c = C.c_float(), C.c_float()
-    lib().orc_sincos_half(float(theta), C.byref(s), C.byref(c))
-    return s.value, c.value
 
 
 def fk(skel, free_poses, angles):

@@ -11,10 +11,11 @@
 // (row stride 65 floats: conflict-free both for the per-lane walk and for the
 // transposed, fully coalesced copy to HBM at the end).
 //
-// Arithmetic contract (shared with whoever checks this stage): fp32, explicit
-// fmaf, no contraction.  sin and cos of half the hinge angle come from a
-// two-constant Cody-Waite reduction by pi/2 and two Taylor polynomials, not
-// from a library routine, so the result is the same on every device.
+// Arithmetic: fp32, explicit fmaf, no contraction.  sin and cos of half the
+// hinge angle come from a two-constant Cody-Waite reduction by pi/2 and two
+// Taylor polynomials (within 1.25 * 2^-24 of the true values for hinge angles
+// up to +-65536 rad); an angle beyond that, or a non-finite one, gives NaN for
+// both, so the body and its descendants drop out of the frame.
 
 #include <hip/hip_runtime.h>
 
@@ -25,6 +26,8 @@ namespace {
 
 constexpr uint32_t kFkLanes = 64;            // frames per workgroup (one wavefront)
 constexpr uint32_t kFkStride = kFkLanes + 1; // LDS row stride in floats
+
+constexpr float kMaxHingeAngle = 65536.0f;  // radians; the reduction below is accurate up to here
 
 __device__ __forceinline__ void sincos_half(float theta, float& s, float& c) {
     const float h = 0.5f * theta;
@@ -41,9 +44,10 @@ __device__ __forceinline__ void sincos_half(float theta, float& s, float& c) {
     pc = __builtin_fmaf(pc, r2, 4.16666667e-02f);
     pc = __builtin_fmaf(pc, r2, -0.5f);
     const float cp = __builtin_fmaf(pc, r2, 1.0f);
-    const int q = (int)kf & 3;
+    const int q = (int)kf & 3;  // (|kf| < 2^15 inside the domain)
     s = q == 0 ? sp : (q == 1 ? cp : (q == 2 ? -sp : -cp));
     c = q == 0 ? cp : (q == 1 ? -sp : (q == 2 ? -cp : sp));
+    if (!(__builtin_fabsf(theta) <= kMaxHingeAngle)) s = c = __builtin_nanf("");
 }
 
 // Row r of the rotation matrix of quaternion (w,x,y,z) applied to v, as

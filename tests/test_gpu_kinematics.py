@@ -1,7 +1,23 @@
 """GPU parity of the kinematics stage (joint angles -> poses -> frames) against the CPU oracle.
 
-Bar: poses bit-exact (both sides run the same fp32 operation sequence, including their own sin/cos);
-frames rendered from them: ids bit-exact, RGB equal.
+The oracle takes sin and cos of the half angle from the C library in double (rounded once); the kernel
+evaluates a range reduction and two polynomials in fp32.  Poses are therefore compared within a bound, derived
+here (u = 2^-24, the fp32 unit roundoff; d = a body's depth below its free root):
+
+  joint quaternion j = (cos, sin * axis): the kernel's sin / cos are within 1.25u of the true values on the
+      stage's domain (|angle| <= 65536), the oracle's within 0.5u, the product with the axis adds 0.5u on each
+      side: |dj| <= 4u in the 2-norm.
+  orientation q = q_parent (x) j: the quaternion product is norm-multiplicative, so in the 2-norm
+      e_q(d) <= e_q(d-1) |j| + |q_parent| |dj| + rounding; each of the four components is a chain of four
+      operations on partial sums below 2 (<= 4u per side, 16u in the 2-norm for both sides together):
+      e_q(d) <= (1 + 4u) e_q(d-1) + 20u,  e_q(free body) = 0 (copied).
+  position p = (p_parent + R(q_parent) a) + R(q) c: an entry of R moves by at most 5.7 e_q (it is bilinear in
+      a quaternion whose 1-norm is at most 2) and carries 4u of rounding from both sides, a row times a vector
+      3u more per unit of the vector's 1-norm, the two additions 2u |p|:
+      e_p <= e_p(parent) + (5.7 e_q(parent) + 7u) |a|_1 + (5.7 e_q + 7u) |c|_1 + 2u max|p|.
+
+These are worst-case sums; typical differences are around 1u (asserted as a median).  Frames are then checked
+exactly: the oracle renders the poses THE KERNEL produced, and ids must agree bit for bit, RGB with difference 0.
 """
 import numpy as np
 import pytest
@@ -29,6 +45,37 @@ def _bits(a):
     return np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
 
 
+U = 2.0 ** -24
+
+
+def assert_poses_close(got, ref, skel):
+    """got, ref [..., K, 7] against the bound derived in this file's header."""
+    got, ref = np.asarray(got, np.float32), np.asarray(ref, np.float32)
+    K = ref.shape[-2]
+    nan = np.isnan(ref)
+    assert np.array_equal(np.isnan(got), nan)
+    g, r = np.where(nan, 0.0, got.astype(np.float64)), np.where(nan, 0.0, ref.astype(np.float64))
+    e_q, e_p = np.zeros(K), [None] * K
+    pmax = np.abs(r[..., :3]).max(axis=(-1, -2))  # per frame
+    for k in range(K):
+        par = int(skel["parent"][k])
+        if par < 0:
+            e_p[k] = np.zeros_like(pmax)
+            assert np.array_equal(got[..., k, :].view(np.uint32)[~nan[..., k, :]], ref[..., k, :].view(np.uint32)[~nan[..., k, :]])
+            continue
+        e_q[k] = (1 + 4 * U) * e_q[par] + 20 * U
+        a1, c1 = np.abs(skel["anchor"][k]).sum(), np.abs(skel["offset"][k]).sum()
+        e_p[k] = e_p[par] + (5.7 * e_q[par] + 7 * U) * a1 + (5.7 * e_q[k] + 7 * U) * c1 + 2 * U * pmax
+        dq = np.abs(g[..., k, 3:] - r[..., k, 3:]).max(axis=-1)
+        dp = np.abs(g[..., k, :3] - r[..., k, :3]).max(axis=-1)
+        assert np.all(dq <= e_q[k]), (k, dq.max(), e_q[k])
+        assert np.all(dp <= e_p[k]), (k, dp.max(), e_p[k].min())
+    hinged = np.asarray(skel["parent"]) >= 0
+    if hinged.any() and not nan.any():  # roundings add up like a random walk along a chain, not linearly
+        assert np.median(np.abs(g[..., hinged, 3:] - r[..., hinged, 3:])) <= U * (1 + np.sqrt(e_q.max() / (20 * U)))
+    return float(np.abs(g - r).max())
+
+
 def _scene_with_skeleton(pxr, w):
     fk = w["fk"]
     sc = pxr.Scene(w["desc"])
@@ -37,7 +84,7 @@ def _scene_with_skeleton(pxr, w):
 
 
 @pytest.mark.parametrize("cfg,B", [(2, 150), (3, 64), (3, 1), (4, 131), (5, 50)])
-def test_poses_bit_exact(torch, pxr, orc, cfg, B):
+def test_poses_within_the_derived_bound(torch, pxr, orc, cfg, B):
     """Several 64-frame workgroups and a ragged tail."""
     w = wl.make(cfg, B=B)
     fk = w["fk"]
@@ -45,7 +92,8 @@ def test_poses_bit_exact(torch, pxr, orc, cfg, B):
     got = sc.pose_batch(torch.from_numpy(fk["free_poses"]).cuda(), torch.from_numpy(fk["angles"]).cuda())
     torch.cuda.synchronize()
     ref = orc.fk(fk["skel"], fk["free_poses"], fk["angles"])
-    assert np.array_equal(_bits(got.cpu().numpy()), _bits(ref))
+    worst = assert_poses_close(got.cpu().numpy(), ref, fk["skel"])
+    assert worst < 2e-6  # (what the bound comes to for these shallow trees is a few times this)
     sc.close()
 
 
@@ -59,15 +107,17 @@ def test_extreme_angles_and_non_finite_inputs(torch, pxr, orc):
     ang[40, 0, 3] = np.nan
     ang[41, 0, 5] = np.inf
     ang[42] = 0.0
+    ang[45, 0, 2] = 1e10      # outside the stage's domain: NaN on both sides
+    ang[46, 0, 4] = -65540.0
+    ang[47] = rng.uniform(-65536.0, 65536.0, ang[47].shape).astype(np.float32)  # its far end
     free = fk["free_poses"].copy()
     free[43, 0, 0, 3:] = 0.0  # zero root quaternion
     free[44, 0, 0, 0] = np.nan
     sc = _scene_with_skeleton(pxr, w)
     got = sc.pose_batch(torch.from_numpy(free).cuda(), torch.from_numpy(ang).cuda()).cpu().numpy()
     ref = orc.fk(fk["skel"], free, ang)
-    nan = np.isnan(ref)
-    assert np.array_equal(np.isnan(got), nan) and nan.any()
-    assert np.array_equal(_bits(got)[~nan], _bits(ref)[~nan])  # NaN payloads are not part of the contract
+    assert np.isnan(ref).any() and np.isnan(ref[45]).any() and np.isnan(ref[46]).any() and not np.isnan(ref[47]).any()
+    assert_poses_close(got, ref, fk["skel"])
     sc.close()
 
 
@@ -88,12 +138,12 @@ def test_free_only_and_rigid_only_skeletons(torch, pxr, orc):
     sc.set_skeleton(skel, 1, 0)
     free = np.ascontiguousarray(w["poses"][:, :, :1])
     got = sc.pose_batch(torch.from_numpy(free).cuda(), None).cpu().numpy()
-    assert np.array_equal(_bits(got), _bits(orc.fk(skel, free, np.zeros((70, 1, 0), np.float32))))
+    assert_poses_close(got, orc.fk(skel, free, np.zeros((70, 1, 0), np.float32)), skel)
     sc.close()
 
 
 def test_sixty_four_link_chain(torch, pxr, orc):
-    """The body-count limit as one chain of depth 63 (rounding accumulates identically on both sides)."""
+    """The body-count limit as one chain of depth 63."""
     rng = np.random.default_rng(66)
     K = 64
     bodies = [wl.capsule(0.03, 0.05, rng.uniform(0.2, 0.9, 3), 4, 1) for _ in range(K)]
@@ -110,7 +160,7 @@ def test_sixty_four_link_chain(torch, pxr, orc):
     free[:, 0, 3:] = wl.random_quats(rng, (N,))
     ang = rng.uniform(-1.5, 1.5, (N, K - 1)).astype(np.float32)
     got = sc.pose_batch(torch.from_numpy(free).cuda(), torch.from_numpy(ang).cuda()).cpu().numpy()
-    assert np.array_equal(_bits(got), _bits(orc.fk(skel, free, ang)))
+    assert_poses_close(got, orc.fk(skel, free, ang), skel)
     sc.close()
 
 
@@ -126,13 +176,17 @@ def test_angles_to_frames_match_oracle(torch, pxr, orc, cfg, B):
                                                    torch.from_numpy(fk["angles"]).cuda(), shapes, step0=4, env0=9,
                                                    want_ids=True)
     torch.cuda.synchronize()
+    got_poses = poses.cpu().numpy()
     ref_poses = orc.fk(fk["skel"], fk["free_poses"], fk["angles"])
-    assert np.array_equal(_bits(poses.cpu().numpy()), _bits(ref_poses))
-    ref = orc.Scene(w["desc"]).render(ref_poses, w["shapes"], step0=4, env0=9, distractor=w["distractor"])
+    assert_poses_close(got_poses, ref_poses, fk["skel"])
+    # the frames are exactly those of the poses the kernel produced ...
+    ref = orc.Scene(w["desc"]).render(got_poses, w["shapes"], step0=4, env0=9, distractor=w["distractor"])
     assert_parity(dict(frames=frames.cpu().numpy(), ids=pxr.ids_to_numpy(ids)), ref)
-    # the frames differ from those of the float64-generated poses only where rounding moved a vertex
-    base = orc.Scene(w["desc"]).render(w["poses"], w["shapes"], step0=4, env0=9, distractor=w["distractor"])
-    assert (base["ids"] != ref["ids"]).mean() < 0.01
+    # ... and differ from those of the oracle's own poses, and of the float64-generated ones, only where the
+    # last bits of a pose moved a vertex across a pixel centre
+    for other in (ref_poses, w["poses"]):
+        base = orc.Scene(w["desc"]).render(other, w["shapes"], step0=4, env0=9, distractor=w["distractor"])
+        assert (base["ids"] != ref["ids"]).mean() < 0.01
     sc.close()
 
 
@@ -146,15 +200,15 @@ def test_paper_environment_stand_ins(torch, pxr, orc, env):
     frames, ids, poses = sc.render_batch_kinematic(torch.from_numpy(fk["free_poses"]).cuda(),
                                                    torch.from_numpy(fk["angles"]).cuda(), None, want_ids=True)
     torch.cuda.synchronize()
-    ref_poses = orc.fk(fk["skel"], fk["free_poses"], fk["angles"])
-    assert np.array_equal(_bits(poses.cpu().numpy()), _bits(ref_poses))
-    ref = orc.Scene(w["desc"]).render(ref_poses)
+    got_poses = poses.cpu().numpy()
+    assert_poses_close(got_poses, orc.fk(fk["skel"], fk["free_poses"], fk["angles"]), fk["skel"])
+    ref = orc.Scene(w["desc"]).render(got_poses)
     assert (ref["ids"] < 0xFFFFFFFE).mean() > 0.015
     assert_parity(dict(frames=frames.cpu().numpy(), ids=pxr.ids_to_numpy(ids)), ref)
     sc.close()
 
 
-def test_full_size_pose_batch_bit_exact(torch, pxr, orc):
+def test_full_size_pose_batch(torch, pxr, orc):
     """The headline workload's 196 608 frames, every pose compared."""
     w = wl.make(5)
     fk = w["fk"]
@@ -166,7 +220,7 @@ def test_full_size_pose_batch_bit_exact(torch, pxr, orc):
     B = got.shape[0]
     for lo in (0, B // 2 - n // 2, B - n):
         ref = orc.fk(fk["skel"], fk["free_poses"][lo:lo + n], fk["angles"][lo:lo + n])
-        assert np.array_equal(_bits(got[lo:lo + n]), _bits(ref))
+        assert_poses_close(got[lo:lo + n], ref, fk["skel"])
     sc.close()
 
 

@@ -1,5 +1,6 @@
-"""Pins for the oracle's kinematics stage: its sin/cos against libm, and hinge chains against the workload
-generators' float64 quaternion algebra (an independent numpy implementation)."""
+"""Pins for the oracle's kinematics stage: the half-angle sine and cosine at angles with closed forms and by their
+identities, hinge geometry in closed form, and hinge chains against the workload generators' float64 quaternion
+algebra (an independent numpy implementation)."""
 import math
 
 import numpy as np
@@ -8,19 +9,51 @@ import pytest
 from paper_2502_00021_amd import workloads as wl
 
 
-def test_sincos_half_against_libm(orc):
-    worst = 0.0
-    for t in np.concatenate([np.linspace(-7, 7, 4001), np.linspace(-300, 300, 2001), [0.0, math.pi, -math.pi, 2 * math.pi]]):
-        t = float(np.float32(t))
-        s, c = orc.sincos_half(t)
-        worst = max(worst, abs(s - math.sin(t / 2)), abs(c - math.cos(t / 2)))
-        assert abs(s * s + c * c - 1.0) < 3e-7
-    assert worst < 1.5e-7
-    assert orc.sincos_half(0.0) == (0.0, 1.0)
-    # quadrants: theta/2 = pi/2, pi, 3pi/2
-    for t, (es, ec) in [(math.pi, (1, 0)), (2 * math.pi, (0, -1)), (3 * math.pi, (-1, 0)), (-math.pi, (-1, 0))]:
-        s, c = orc.sincos_half(t)
-        assert abs(s - es) < 2e-7 and abs(c - ec) < 2e-7
+def _one_hinge(orc, theta, axis=(0.0, 0.0, 1.0)):
+    """Orientation of a body hinged to an identity-posed root by `theta` about `axis`: (cos(theta/2), sin(theta/2) axis)."""
+    skel = wl._skeleton(2)
+    skel["slot"][0] = 0
+    wl._hinge(skel, 1, parent=0, slot=0, anchor=(0, 0, 0), axis=axis, offset=(0, 0, 0))
+    free = np.array([[[0, 0, 0, 1, 0, 0, 0]]], np.float32)
+    return orc.fk(skel, free, np.array([[theta]], np.float32))[0, 1, 3:].astype(np.float64)
+
+
+def test_half_angle_sine_and_cosine_at_angles_with_closed_forms(orc):
+    """The hinge quaternion at angles whose half-angle sine and cosine are known surds (the angle itself is
+    rounded to fp32, which moves the result by at most |d theta| / 2 <= 2^-24 * |theta| / 2)."""
+    r2, r3 = math.sqrt(0.5), math.sqrt(0.75)
+    for theta, c, s in [(0.0, 1.0, 0.0), (math.pi / 3, r3, 0.5), (math.pi / 2, r2, r2), (2 * math.pi / 3, 0.5, r3),
+                        (math.pi, 0.0, 1.0), (4 * math.pi / 3, -0.5, r3), (2 * math.pi, -1.0, 0.0),
+                        (3 * math.pi, 0.0, -1.0), (-math.pi / 3, r3, -0.5), (-math.pi, 0.0, -1.0),
+                        (100 * math.pi + math.pi / 3, r3, 0.5), (20001 * math.pi, 0.0, 1.0)]:
+        q = _one_hinge(orc, theta)
+        tol = 2.0 ** -24 * (1.0 + abs(theta) / 2)
+        assert abs(q[0] - c) <= tol and abs(q[3] - s) <= tol and q[1] == 0.0 and q[2] == 0.0, (theta, q)
+    assert np.array_equal(_one_hinge(orc, 0.0), [1.0, 0.0, 0.0, 0.0])
+
+
+def test_half_angle_identities(orc):
+    """Unit norm, odd sine / even cosine, and the half-turn shift, over the whole domain (the axis is a
+    coordinate axis, so the quaternion holds the two values themselves)."""
+    rng = np.random.default_rng(5)
+    for theta in np.concatenate([rng.uniform(-7, 7, 300), rng.uniform(-300, 300, 200), rng.uniform(-65536, 65536, 200)]):
+        theta = float(np.float32(theta))
+        q, qn = _one_hinge(orc, theta, (1, 0, 0)), _one_hinge(orc, -theta, (1, 0, 0))
+        assert abs(q[0] * q[0] + q[1] * q[1] - 1.0) < 2.5e-7
+        assert q[0] == qn[0] and q[1] == -qn[1]
+    # small angles: sin(theta/2) = theta/2 - theta^3/48 + ..., cos(theta/2) = 1 - theta^2/8 + ...
+    for theta in (1e-3, -2.5e-4, 3e-2):
+        t = float(np.float32(theta))
+        q = _one_hinge(orc, t, (0, 1, 0))
+        assert abs(q[2] - (t / 2 - t ** 3 / 48 + t ** 5 / 3840)) < 1e-9 + 2.0 ** -24 * abs(t)
+        assert abs(q[0] - (1 - t * t / 8 + t ** 4 / 384)) < 6.1e-8
+
+
+def test_angles_outside_the_domain_give_nan(orc):
+    for theta in (65536.0, -65536.0):
+        assert np.all(np.isfinite(_one_hinge(orc, theta)))
+    for theta in (65540.0, -1e10, math.inf, -math.inf, math.nan):
+        assert np.all(np.isnan(_one_hinge(orc, theta)))
 
 
 @pytest.mark.parametrize("cfg,B", [(2, 64), (3, 64), (4, 64), (5, 32)])
