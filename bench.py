@@ -274,8 +274,11 @@ def main():
     ap.add_argument("--next-stages-only", action="store_true",
                     help="time only the kinematics and conv-consumer stages of the chosen workload (for profiler runs)")
     ap.add_argument("--extras", action="store_true", help="also time the other configurations (reported under 'others')")
+    ap.add_argument("--profile-lib", default=None, metavar="FILE",
+                    help="profiling only: load this build of the library (paper_2502_00021_amd/build.py --define ... --out FILE) "
+                         "instead of the in-tree one; the numbers of such a run are not the product's")
     ap.add_argument("--phase-clocks", action="store_true",
-                    help="with PXR_LIB set to a build made with --define PXR_PHASE_TIMING (see paper_2502_00021_amd/build.py): "
+                    help="with --profile-lib naming a build made with --define PXR_PHASE_TIMING: "
                          "report the shader-clock ticks per frame a workgroup spends in each phase of the render kernel")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -285,6 +288,8 @@ def main():
     import torch
     from paper_2502_00021_amd import pxr
 
+    if args.profile_lib:
+        pxr.use_library_file(args.profile_lib)
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
 
@@ -322,7 +327,7 @@ def main():
             import ctypes
             L = pxr.lib()
             if not hasattr(L, "pxr_debug_phase_cycles"):
-                sys.exit("bench.py --phase-clocks: the loaded library is not a PXR_PHASE_TIMING build (set PXR_LIB)")
+                sys.exit("bench.py --phase-clocks: the loaded library is not a PXR_PHASE_TIMING build (give one with --profile-lib)")
             L.pxr_debug_phase_cycles.argtypes = [ctypes.c_void_p, ctypes.c_int]
             L.pxr_debug_wave_arrival.argtypes = [ctypes.c_void_p]
             scratch = (ctypes.c_ulonglong * 128)()

@@ -87,9 +87,9 @@ typedef struct {
  *          onto pixels whose winner is the ground or the background.
  *          d_env_offset: device uint32 [B] (indexed by the env's position in
  *          the batch), or NULL = drawn from the generator.  With n_videos > 1
- *          every environment plays one clip of a set (the paper: "a random
- *          video" per environment), chosen by d_env_video or drawn from the
- *          generator.  All buffers are caller-owned and must stay alive while bound. */
+ *          every environment plays one clip of a set (paper section 2: each
+ *          environment gets a clip picked at random), chosen by d_env_video or
+ *          drawn from the generator.  All buffers are caller-owned and must stay alive while bound. */
 typedef struct {
     uint32_t mode;
     uint64_t seed;
@@ -105,18 +105,22 @@ typedef struct {
 
 /* Build a scene on the current HIP device: validate, tessellate, derive the
  * camera constants, upload (one allocation, one synchronous copy).  Host only,
- * not on the hot path.
+ * not on the hot path.  (Paper section 1: an environment is a set of rigid bodies seen by a camera; the
+ * paper gives no geometry, camera or lighting model, so primitives, tessellation, the root-tracking pinhole
+ * camera and the flat Lambert-plus-ambient light are this library's reading of "rendered from the
+ * simulator's state".)
  * Errors: INVALID_ARG (null pointer, root_body out of range, unknown body
- * type, non-finite or non-positive parameter, degenerate camera, mesh index out of
- * range or non-finite mesh vertex);
+ * type, non-finite or non-positive parameter, a colour (rgb, ground_grey, background_rgb) outside [0,1], a
+ * negative mesh colour multiplier, degenerate camera, mesh index out of range or non-finite mesh vertex);
  * UNSUPPORTED (width or height outside [8,512], n_bodies outside [1,64], more
  * than 65535 vertices or triangles, tessellation counts outside [3,64]x[1,32]
  * (box [1,16]), or a frame that does not fit the 160 KB of LDS of one
  * compute unit); OOM; DEVICE. */
 int pxr_create_scene(const pxr_scene_desc* desc, pxr_scene** out);
 
-/* Free the scene and its device constants.  The caller must have synchronised
- * every stream that still renders from it.  NULL is accepted. */
+/* Free the scene and its device constants (the counterpart of pxr_create_scene; paper section 1: the
+ * renderer's state lives on the device for as long as the environments do).  The caller must have
+ * synchronised every stream that still renders from it.  NULL is accepted. */
 int pxr_destroy_scene(pxr_scene* s);
 
 /* Bind (or with d == NULL / mode NONE, unbind) the distractor that later
@@ -139,8 +143,10 @@ int pxr_apply_distractor(pxr_scene* s, const pxr_distractor_desc* d);
  *            or NULL
  *   hip_stream  hipStream_t to enqueue on; NULL = the default stream
  * Only enqueues and returns: no synchronisation, no host<->device copy, no
- * allocation.  Pose VALUES are not validated: a vertex behind the near plane,
- * far outside the image or non-finite removes its triangles from the frame.
+ * allocation.  Pose VALUES are not validated.  A triangle with corners on both sides of the near plane
+ * z_near is clipped against it (the part in front is drawn); one wholly behind it is not drawn; a vertex
+ * in front that projects more than 16384 pixels from the image centre, or a non-finite one, removes its
+ * triangles from the frame.
  * Alignment: d_poses, d_frames 4 bytes; d_shapes (16-byte records), d_ids 16 bytes.
  * Errors: INVALID_ARG (null scene/poses/frames, B*S == 0, B*S > 2^31-1,
  * step0 + S or env0 + B overflow, misaligned buffer); DEVICE (launch failure). */
@@ -209,7 +215,8 @@ typedef struct {
 /* Host only.  Errors: INVALID_ARG (null, non-finite weight or bias); UNSUPPORTED (other layer shapes,
  * n_stack outside [1,4], in_h outside [3,512], in_w outside [4,256] or not a multiple of 4); OOM; DEVICE. */
 int pxr_conv_create(const pxr_conv_desc* desc, pxr_conv** out);
-int pxr_conv_destroy(pxr_conv* c); /* NULL accepted; synchronise streams still using it first */
+/* Free a layer made by pxr_conv_create (same passage).  NULL accepted; synchronise streams still using it first. */
+int pxr_conv_destroy(pxr_conv* c);
 
 /* d_frames [B,n_stack,in_h,in_w,3] uint8 (what pxr_render_batch writes for S = n_stack) ->
  * d_out [B,out_h,out_w,32] bfloat16 bit patterns, out_h = (in_h-3)/2+1, out_w = (in_w-3)/2+1.
@@ -217,8 +224,8 @@ int pxr_conv_destroy(pxr_conv* c); /* NULL accepted; synchronise streams still u
  * Errors: INVALID_ARG (null, B == 0 or too large, misaligned); DEVICE. */
 int pxr_conv_forward(pxr_conv* c, const uint8_t* d_frames, uint32_t B, uint16_t* d_out, void* hip_stream);
 
-/* Output size, output rows per work item, LDS bytes per workgroup, persistent workgroups per launch.  Any
- * pointer may be NULL. */
+/* Facts about a layer (no passage of the paper): output size, output rows per work item, LDS bytes per
+ * workgroup, persistent workgroups per launch.  Any pointer may be NULL.  Errors: INVALID_ARG (null layer). */
 int pxr_conv_info(const pxr_conv* c, uint32_t* out_h, uint32_t* out_w, uint32_t* band_rows, uint32_t* lds_bytes,
                   uint32_t* n_groups);
 
@@ -226,9 +233,9 @@ int pxr_conv_info(const pxr_conv* c, uint32_t* out_h, uint32_t* out_w, uint32_t*
  * output does not depend on it. */
 int pxr_conv_set_tuning(pxr_conv* c, uint32_t band_rows, uint32_t n_groups);
 
-/* Scene facts for callers and tests: total template vertices and triangles,
- * dynamic LDS bytes per frame workgroup, threads per workgroup.  Any out
- * pointer may be NULL. */
+/* Scene facts for callers and tests (sizes of what pxr_create_scene built; no passage of the paper): total
+ * template vertices and triangles, dynamic LDS bytes per frame workgroup, threads per workgroup.  Any out
+ * pointer may be NULL.  Errors: INVALID_ARG (null scene). */
 int pxr_scene_info(const pxr_scene* s, uint32_t* n_verts, uint32_t* n_tris, uint32_t* lds_bytes,
                    uint32_t* block_threads);
 
@@ -267,7 +274,8 @@ int pxr_selftest_arithmetic(uint64_t* counts);
 int pxr_host_tables(const pxr_scene_desc* desc, uint32_t* n_verts, uint32_t* n_tris, float* vtmpl, uint32_t* tri_idx,
                     float* tri_shade, float* cxcy, float* consts, uint32_t* n_pairs, uint32_t* pair_tbl);
 
-/* Reason for the last failure on this thread; valid until the next call on it. */
+/* Reason for the last failure on this thread; valid until the next call on it.  (Error reporting of this
+ * interface; no passage of the paper.) */
 const char* pxr_last_error(void);
 
 #ifdef __cplusplus

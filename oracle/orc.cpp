@@ -21,6 +21,7 @@
 
 #include "orc.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
@@ -234,6 +235,7 @@ bool build_mesh(MeshOut out, uint32_t base, uint32_t nv, const float* verts, uin
     for (uint32_t t = 0; t < nt; ++t) {
         const uint32_t* ix = tris + (size_t)t * 3;
         if (ix[0] >= nv || ix[1] >= nv || ix[2] >= nv) return false;
+        if (mul && !(mul[t] >= 0.0f)) return false;  // a colour multiplier cannot be negative
         D3 p[3];
         for (int q = 0; q < 3; ++q) p[q] = D3{verts[(size_t)ix[q] * 3], verts[(size_t)ix[q] * 3 + 1], verts[(size_t)ix[q] * 3 + 2]};
         D3 n = unit_normal(p[0], p[1], p[2]);
@@ -520,6 +522,11 @@ orc_scene* orc_scene_create_meshes(uint32_t width, uint32_t height, uint32_t n_b
     size_t mesh_v0 = 0, mesh_t0 = 0;  // running offsets into the concatenated mesh arrays
     if (!kinds || !shapes || !rgbs || !n_lon || !n_lat || !cam || !light || !ground || !bg) return nullptr;
     if (width < 1 || height < 1 || n_bodies < 1 || root_body >= n_bodies) return nullptr;
+    // colours are fractions of full intensity: base colours outside [0,1] are invalid input
+    auto unit = [](float v) { return v >= 0.0f && v <= 1.0f; };
+    for (uint32_t i = 0; i < n_bodies * 3; ++i)
+        if (!unit(rgbs[i])) return nullptr;
+    if (!unit(ground[2]) || !unit(ground[3]) || !unit(bg[0]) || !unit(bg[1]) || !unit(bg[2])) return nullptr;
     orc_scene* s = new orc_scene();
     s->W = width; s->H = height; s->K = n_bodies; s->root = root_body;
     MeshOut out{s->uv, s->tri, s->nrm, s->mul};
@@ -584,8 +591,9 @@ orc_scene* orc_scene_create_meshes(uint32_t width, uint32_t height, uint32_t n_b
     s->cell = ground[1];
     double lz = ld[2] / ln;
     double lit = (double)light[3] + (double)light[4] * (lz > 0.0 ? lz : 0.0);
-    s->gs[0] = (float)((double)ground[2] * lit);
-    s->gs[1] = (float)((double)ground[3] * lit);
+    // (like a shaded triangle, the lit ground never exceeds full intensity)
+    s->gs[0] = std::min(1.0f, (float)((double)ground[2] * lit));
+    s->gs[1] = std::min(1.0f, (float)((double)ground[3] * lit));
     for (int i = 0; i < 3; ++i) s->bg[i] = bg[i];
     return s;
 }

@@ -24,7 +24,8 @@ def stale():
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC)] + [os.path.join(ROOT, "include", "pxr.h")]
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if os.path.isfile(os.path.join(CSRC, f))]
+    deps.append(os.path.join(ROOT, "include", "pxr.h"))
     return any(os.path.getmtime(d) > t for d in deps)
 
 
@@ -42,7 +43,8 @@ def build(force=True, verbose=False, extra=(), out=None):
 
 
 if __name__ == "__main__":
-    # Profiling builds of the render kernel, loaded by setting PXR_LIB to the file:
+    # Profiling builds of the render kernel (csrc/profiling/, never part of the library), written to a file of
+    # their own and loaded with `bench.py --profile-lib FILE`:
     #   --define PXR_STOP_AFTER=k   the kernel returns after phase k = 0..5 (hardware counters of k minus those of
     #                               k - 1 are phase k's); the frames are NOT rendered
     #   --define PXR_PHASE_TIMING   the first wavefront of every workgroup notes the shader clock at each barrier
@@ -56,4 +58,4 @@ if __name__ == "__main__":
     a = ap.parse_args()
     if a.define and not a.out:
         ap.error("a build with --define is a profiling build: give it a file of its own with --out")
-    build(verbose=True, extra=["-D" + d for d in a.define], out=a.out)
+    build(verbose=True, extra=["-D" + d for d in a.define] + (["-DPXR_PROFILING_BUILD"] if a.define else []), out=a.out)

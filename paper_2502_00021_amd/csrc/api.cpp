@@ -5,6 +5,7 @@
 
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "pxr_internal.h"
@@ -47,6 +48,18 @@ uint32_t pick_block_threads(const pxr::SceneConsts& sc) {
     return 1024;
 }
 
+// The kernels' dynamic-LDS caps are raised once per device and process, by the first scene created there.
+int prepare_device_once(int device, std::string& err) {
+    static std::mutex mu;
+    static bool done[64] = {};
+    if (device < 0 || device >= 64) return pxr::prepare_kernels(err);
+    std::lock_guard<std::mutex> lock(mu);
+    if (done[device]) return PXR_OK;
+    const int rc = pxr::prepare_kernels(err);
+    if (rc == PXR_OK) done[device] = true;
+    return rc;
+}
+
 }  // namespace
 
 extern "C" {
@@ -59,14 +72,6 @@ int pxr_create_scene(const pxr_scene_desc* desc, pxr_scene** out) {
     std::string err;
     int rc = pxr::build_host_scene(*desc, hs, err);
     if (rc != PXR_OK) return fail(rc, "pxr_create_scene: " + err);
-
-    pxr_scene* s = new (std::nothrow) pxr_scene();
-    if (!s) return fail(PXR_ERR_OOM, "pxr_create_scene: host allocation failed");
-    s->sc = hs.c;
-    if (hipGetDevice(&s->device) != hipSuccess) {
-        delete s;
-        return fail(PXR_ERR_DEVICE, "pxr_create_scene: no HIP device");
-    }
 
     // one arena, 256-byte aligned sub-tables, one synchronous upload
     struct Part {
@@ -82,6 +87,14 @@ int pxr_create_scene(const pxr_scene_desc* desc, pxr_scene** out) {
     // hold no triangle and point four times at the word after the last code, which the kernel sets to code 0.
     if ((uint64_t)hs.c.lds_keys + 4ull * (hs.c.V + 1ull) > 0x10000ull)
         return fail(PXR_ERR_UNSUPPORTED, "pxr_create_scene: too many vertices for 16-bit LDS addresses in the pair table");
+
+    pxr_scene* s = new (std::nothrow) pxr_scene();
+    if (!s) return fail(PXR_ERR_OOM, "pxr_create_scene: host allocation failed");
+    s->sc = hs.c;
+    if (hipGetDevice(&s->device) != hipSuccess) {
+        delete s;
+        return fail(PXR_ERR_DEVICE, "pxr_create_scene: no HIP device");
+    }
     std::vector<uint32_t> pair_dev(hs.pair_tbl);
     for (size_t p = 0; p < pair_dev.size() / 4; ++p)
         for (int w = 0; w < 2; ++w) {
@@ -144,7 +157,7 @@ int pxr_create_scene(const pxr_scene_desc* desc, pxr_scene** out) {
     s->sc.pair_tbl = reinterpret_cast<const uint32_t*>(base + parts[5].off);
     s->sc.P = (uint32_t)(pair_dev.size() / 4);  // (with the padding)
 
-    rc = pxr::prepare_kernels(s->sc.lds_total, err);
+    rc = prepare_device_once(s->device, err);
     if (rc != PXR_OK) {
         (void)hipFree(s->d_arena);
         delete s;

@@ -3,6 +3,7 @@
 #ifndef PXR_INTERNAL_H
 #define PXR_INTERNAL_H
 
+#include <cstddef>
 #include <cstdint>
 #include <string>
 #include <vector>
@@ -24,18 +25,9 @@ constexpr int32_t kBehindX = INT32_MIN + 1;
 //   large otherwise           a whole wavefront, one row per lane (also: triangles to be clipped)
 // What is balanced here is the longest chain in the raster phase, not the instruction count: one lane
 // walking a 12-pixel triangle holds up its whole workgroup at the next barrier.
-#ifndef PXR_TINY_MAX
-#define PXR_TINY_MAX 3
-#endif
-#ifndef PXR_SMALL_MAX
-#define PXR_SMALL_MAX 128
-#endif
-#ifndef PXR_SMALL_LANES_LOG2
-#define PXR_SMALL_LANES_LOG2 2
-#endif
-constexpr uint32_t kTinyMaxPixels = PXR_TINY_MAX;
-constexpr uint32_t kSmallMaxPixels = PXR_SMALL_MAX;
-constexpr uint32_t kSmallLanesLog2 = PXR_SMALL_LANES_LOG2;
+constexpr uint32_t kTinyMaxPixels = 3;
+constexpr uint32_t kSmallMaxPixels = 128;
+constexpr uint32_t kSmallLanesLog2 = 2;
 constexpr uint32_t kNoTriangle = 0xFFFFu;
 
 // Per-body record kept in LDS for the duration of one frame (floats).
@@ -119,8 +111,9 @@ int launch_render(const SceneConsts& sc, const DistractConsts& dc, const float* 
                   uint32_t n_frames, uint32_t S, uint32_t step0, uint32_t env0, uint8_t* d_frames, uint32_t* d_ids,
                   uint32_t block_threads, void* stream, std::string& err);
 
-// render.hip: raise the dynamic-LDS limit of every kernel instantiation once.
-int prepare_kernels(uint32_t lds_bytes, std::string& err);
+// render.hip: raise the dynamic-LDS limit of every kernel instantiation on the current device (the caller sees
+// to it that this runs once per device).
+int prepare_kernels(std::string& err);
 
 // Frame consumer (first convolutional layer of the policy), bound by pxr_conv_create.
 // 3x3 kernel, stride 2, 32 output channels; the frame stack is the channel axis.

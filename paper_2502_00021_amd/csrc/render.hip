@@ -352,50 +352,10 @@ __device__ __forceinline__ uint32_t quantise(float c) {
 
 // ---------------------------------------------------------------- the kernel
 
-#ifdef PXR_PHASE_TIMING
-// Profiling build only: the first wavefront of every workgroup notes the clock at each phase boundary (in
-// registers) and lane 0 adds the spans to global counters when the kernel ends (1024 sets of counters: one
-// shared set would serialise the kernel's tail).
-__device__ unsigned long long g_phase_cycles[1024 * 8];
-__device__ unsigned long long g_wave_arrival[1024 * 8 * 16];  // per barrier and wavefront: arrival after the barrier's first wavefront
-#define PXR_PHASE_BEGIN()                      \
-    unsigned long long phase_span[8] = {0};    \
-    unsigned long long phase_t0 = __builtin_readcyclecounter()
-#define PXR_PHASE_MARK(i)                                                \
-    {                                                                    \
-        const unsigned long long now = __builtin_readcyclecounter();    \
-        phase_span[i] += now - phase_t0;                                 \
-        phase_t0 = now;                                                  \
-    }
-// (with -DPXR_WAVE_ARRIVAL: a barrier that also notes, per wavefront, how long after the first one it arrived;
-// the second barrier it needs slows the kernel, so the phase clocks are best read without it)
-#ifndef PXR_WAVE_ARRIVAL
-#define PXR_TIMED_BARRIER(i) __syncthreads()
-#else
-#define PXR_TIMED_BARRIER(i)                                                                              \
-    {                                                                                                         \
-        unsigned long long* arr = reinterpret_cast<unsigned long long*>(lds + sc.lds_misc + 128);             \
-        if (lane == 0) arr[tid >> 6] = __builtin_readcyclecounter();                                          \
-        __syncthreads();                                                                                      \
-        if (tid < NT / 64) {                                                                                  \
-            unsigned long long first = arr[0];                                                                \
-            for (uint32_t k = 1; k < NT / 64; ++k) first = arr[k] < first ? arr[k] : first;                   \
-            atomicAdd(&g_wave_arrival[((blockIdx.x & 1023u) * 8u + (i)) * 16u + tid], arr[tid] - first);      \
-        }                                                                                                     \
-        __syncthreads();                                                                                      \
-    }
-#endif
-#define PXR_PHASE_END()                                                                                      \
-    if (tid == 0) {                                                                                          \
-        for (int i = 0; i < 7; ++i) atomicAdd(&g_phase_cycles[(blockIdx.x & 1023u) * 8u + i], phase_span[i]); \
-    }
-#elif defined(PXR_STOP_AFTER)
-// Profiling build only: the kernel ends after phase PXR_STOP_AFTER (counter deltas give per-phase cost).
-#define PXR_PHASE_BEGIN()
-#define PXR_PHASE_MARK(i) \
-    if ((i) == PXR_STOP_AFTER) return
-#define PXR_TIMED_BARRIER(i) __syncthreads()
-#define PXR_PHASE_END()
+// Phase probes: empty in the library.  A profiling build (-DPXR_PROFILING_BUILD, made into a file of its own
+// by build.py --define) takes them from a header that the library's build never includes.
+#ifdef PXR_PROFILING_BUILD
+#include "profiling/phase_probes.h"
 #else
 #define PXR_PHASE_BEGIN()
 #define PXR_PHASE_MARK(i)
@@ -1104,39 +1064,15 @@ int prepare_all(uint32_t cap, std::string& err) {
     return PXR_OK;
 }
 
-#ifdef PXR_PHASE_TIMING
-extern "C" int pxr_debug_wave_arrival(unsigned long long* out) {  // out[8][16]
-    static unsigned long long host[1024 * 8 * 16];
-    if (hipMemcpyFromSymbol(host, HIP_SYMBOL(g_wave_arrival), sizeof(host)) != hipSuccess) return 1;
-    for (int i = 0; i < 128; ++i) out[i] = 0;
-    for (int k = 0; k < 1024; ++k)
-        for (int i = 0; i < 128; ++i) out[i] += host[k * 128 + i];
-    for (auto& h : host) h = 0;
-    return hipMemcpyToSymbol(HIP_SYMBOL(g_wave_arrival), host, sizeof(host)) != hipSuccess;
-}
-
-extern "C" int pxr_debug_phase_cycles(unsigned long long* out, int reset) {
-    static unsigned long long host[1024 * 8];
-    if (out) {
-        if (hipMemcpyFromSymbol(host, HIP_SYMBOL(g_phase_cycles), sizeof(host)) != hipSuccess) return 1;
-        for (int i = 0; i < 8; ++i) out[i] = 0;
-        for (int k = 0; k < 1024; ++k)
-            for (int i = 0; i < 8; ++i) out[i] += host[k * 8 + i];
-    }
-    if (reset) {
-        for (auto& h : host) h = 0;
-        if (hipMemcpyToSymbol(HIP_SYMBOL(g_phase_cycles), host, sizeof(host)) != hipSuccess) return 1;
-    }
-    return 0;
-}
+#if defined(PXR_PROFILING_BUILD) && defined(PXR_PHASE_TIMING)
+#include "profiling/phase_exports.h"
 #endif
 
 }  // namespace
 
-int prepare_kernels(uint32_t lds_bytes, std::string& err) {
-    // The attribute is a per-kernel cap, not a per-launch size: always raise it
-    // to the whole 160 KB so that scenes of different sizes can coexist.
-    (void)lds_bytes;
+int prepare_kernels(std::string& err) {
+    // The attribute is a per-kernel cap, not a per-launch size: raise it to the whole 160 KB, so that scenes
+    // of any size can coexist.
     const uint32_t cap = 160u * 1024u;
     int rc;
     if ((rc = prepare_all<256>(cap, err))) return rc;

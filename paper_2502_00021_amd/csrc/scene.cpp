@@ -260,6 +260,12 @@ bool finite_all(const float* p, int n) {
     return true;
 }
 
+bool unit_all(const float* p, int n) {  // colours: fractions of full intensity
+    for (int i = 0; i < n; ++i)
+        if (!(p[i] >= 0.0f && p[i] <= 1.0f)) return false;
+    return true;
+}
+
 }  // namespace
 
 int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
@@ -296,6 +302,10 @@ int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
         err = "ground / background parameters must be finite, ground_cell > 0";
         return PXR_ERR_INVALID_ARG;
     }
+    if (!unit_all(d.ground_grey, 2) || !unit_all(d.background_rgb, 3)) {
+        err = "ground_grey and background_rgb must lie in [0,1]";
+        return PXR_ERR_INVALID_ARG;
+    }
 
     c.W = d.width;
     c.H = d.height;
@@ -311,6 +321,10 @@ int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
         const pxr_body_desc& bd = d.bodies[b];
         if (!finite_all(bd.shape, 4) || !finite_all(bd.rgb, 3)) {
             err = "body " + std::to_string(b) + ": non-finite shape or colour";
+            return PXR_ERR_INVALID_ARG;
+        }
+        if (!unit_all(bd.rgb, 3)) {
+            err = "body " + std::to_string(b) + ": rgb must lie in [0,1]";
             return PXR_ERR_INVALID_ARG;
         }
         BodyMesh m;
@@ -340,6 +354,11 @@ int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
                 err = "body " + std::to_string(b) + ": non-finite mesh vertex or multiplier";
                 return PXR_ERR_INVALID_ARG;
             }
+            for (uint32_t t = 0; bd.mesh_tri_mul && t < bd.n_mesh_tris; ++t)
+                if (bd.mesh_tri_mul[t] < 0.0f) {
+                    err = "body " + std::to_string(b) + ": negative colour multiplier";
+                    return PXR_ERR_INVALID_ARG;
+                }
             for (uint32_t i = 0; i < bd.n_mesh_tris * 3; ++i)
                 if (bd.mesh_tris[i] >= bd.n_mesh_verts) {
                     err = "body " + std::to_string(b) + ": mesh index out of range";
@@ -437,8 +456,8 @@ int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
     c.checker_short_form = (d.ground_cell == 1.0f && d.z_far <= 0x1p64f) ? 1u : 0u;
     const double lz = ld.z / ld_len;
     const double lit = (double)d.ambient + (double)d.diffuse * (lz > 0.0 ? lz : 0.0);
-    c.gs[0] = (float)((double)d.ground_grey[0] * lit);
-    c.gs[1] = (float)((double)d.ground_grey[1] * lit);
+    c.gs[0] = std::fmin(1.0f, (float)((double)d.ground_grey[0] * lit));  // (capped like a shaded triangle)
+    c.gs[1] = std::fmin(1.0f, (float)((double)d.ground_grey[1] * lit));
     for (int i = 0; i < 3; ++i) c.bg[i] = d.background_rgb[i];
 
     // ---- LDS carve-up of one frame workgroup.  The pixel keys dominate for tall frames; they are

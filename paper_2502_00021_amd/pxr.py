@@ -63,13 +63,24 @@ class ConvDesc(C.Structure):
 
 
 _lib = None
+_lib_path = LIB_PATH
+
+
+def use_library_file(path):
+    """Profiling only (bench.py --profile-lib): load another build of the same sources, e.g. one with phase
+    clocks compiled in (paper_2502_00021_amd/build.py --define ... --out FILE).  Must be called before the
+    library is first used; nothing in the product path calls it, and no environment variable can."""
+    global _lib_path
+    if _lib is not None:
+        raise RuntimeError("the library is already loaded")
+    _lib_path = os.path.abspath(path)
 
 
 def lib():
     """Load libpxr.so (built in-tree by __graft_entry__.build / paper_2502_00021_amd.build)."""
     global _lib
     if _lib is None:
-        path = os.environ.get("PXR_LIB") or LIB_PATH  # (PXR_LIB: a profiling build of the same sources)
+        path = _lib_path
         if not os.path.exists(path):
             raise ImportError(f"{path} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` first")
         L = C.CDLL(path)

@@ -138,9 +138,27 @@ def test_scene_validation_errors():
     _expect(dict(base, bodies=[bad]), pxr.ERR_INVALID_ARG)
     _expect(dict(base, bodies=[dict(base["bodies"][0], n_lon=2)]), pxr.ERR_UNSUPPORTED)
     _expect(dict(base, bodies=[dict(base["bodies"][0], shape=(float("inf"), 1, 1, 1))]), pxr.ERR_INVALID_ARG)
+    # colours are fractions of full intensity (a value outside [0,1] would wrap in the byte it is quantised to)
+    _expect(dict(base, background_rgb=(0.5, 1.2, 0.5)), pxr.ERR_INVALID_ARG)
+    _expect(dict(base, ground_grey=(-0.1, 0.5)), pxr.ERR_INVALID_ARG)
+    _expect(dict(base, bodies=[dict(base["bodies"][0], rgb=(0.2, 0.3, -0.01))]), pxr.ERR_INVALID_ARG)
+    _expect(dict(base, bodies=[dict(base["bodies"][0], rgb=(0.2, 1.5, 0.3))]), pxr.ERR_INVALID_ARG)
     # too much geometry for 65535 vertices / the LDS budget
     _expect(dict(base, bodies=[wl.sphere(0.1, (0.5, 0.5, 0.5), 64, 32)] * 20), pxr.ERR_UNSUPPORTED)
     _expect(dict(base, width=128, height=128, bodies=[wl.sphere(0.1, (0.5, 0.5, 0.5), 64, 32)] * 2), pxr.ERR_UNSUPPORTED)
+
+
+def test_colours_outside_the_unit_range_are_invalid_for_the_oracle_too(orc):
+    base = wl.make(1, B=1)["desc"]
+    for bad in (dict(base, background_rgb=(0.5, 1.2, 0.5)), dict(base, ground_grey=(-0.1, 0.5)),
+                dict(base, bodies=[dict(base["bodies"][0], rgb=(0.2, 0.3, -0.01))])):
+        with pytest.raises(Exception):
+            orc.Scene(bad)
+    # a ground brighter than full intensity under the light is capped, on both sides, like a shaded triangle
+    lit = dict(base, ground_grey=(0.9, 1.0), ambient=0.8, diffuse=0.9)
+    t = pxr.host_tables(lit)
+    assert np.array_equal(t["gs"], [1.0, 1.0])
+    assert np.array_equal(orc.Scene(lit).camera()["gs"], t["gs"])
 
 
 def test_null_arguments_are_errors_not_crashes():
