@@ -195,6 +195,19 @@ int pxr_render_batch_kinematic(pxr_scene* s, const float* d_free_poses, const fl
                                uint32_t B, uint32_t S, uint32_t step0, uint32_t env0, float* d_poses,
                                uint8_t* d_frames, uint32_t* d_ids, void* hip_stream);
 
+/* pxr_render_batch_kinematic for callers that cannot allocate device memory or provide a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The poses between the two
+ * kernels live in a 32 MiB buffer that is part of the library's image on each GPU (held until the process
+ * ends) instead of in d_poses; they are not returned.  The call allocates and frees nothing and only enqueues.
+ * Calls on one GPU share that buffer: two calls whose kernels may overlap (different streams without an
+ * ordering between them) race; calls on one stream, or ordered by events, are safe.  Nothing carries over
+ * from one call to the next.
+ * Errors: those of pxr_render_batch_kinematic, and UNSUPPORTED when B * S * n_bodies * 28 bytes exceed
+ * 32 MiB (33 554 432); DEVICE if the buffer's address cannot be obtained. */
+int pxr_render_batch_kinematic_static(pxr_scene* s, const float* d_free_poses, const float* d_angles,
+                                      const float* d_shapes, uint32_t B, uint32_t S, uint32_t step0, uint32_t env0,
+                                      uint8_t* d_frames, uint32_t* d_ids, void* hip_stream);
+
 /* ---- frame consumer: the policy's first convolutional layer on the frame stack ----
  * The paper's throughput loop ends every environment step with a forward pass through one convolutional
  * layer on the observations (section 2); it gives no hyper-parameters.  Built here: 3x3 kernel, stride 2, no

@@ -299,6 +299,13 @@ int pxr_set_skeleton(pxr_scene* s, const pxr_skeleton_desc* k) {
         (void)hipFree(d);
         return fail(PXR_ERR_DEVICE, std::string("pxr_set_skeleton: upload failed: ") + hipGetErrorString(hrc));
     }
+    {
+        // set-up is the place to look up this device's copy of the static pose buffer (used by
+        // pxr_render_batch_kinematic_static), so that the hot call finds it cached
+        float* unused = nullptr;
+        std::string e2;
+        (void)pxr::static_pose_scratch(&unused, nullptr, e2);
+    }
     if (s->d_skeleton) (void)hipFree(s->d_skeleton);
     s->d_skeleton = d;
     sk.parent = static_cast<const int32_t*>(d);
@@ -333,6 +340,32 @@ int pxr_render_batch_kinematic(pxr_scene* s, const float* d_free_poses, const fl
     int rc = pxr_pose_batch(s, d_free_poses, d_angles, B * S, d_poses, hip_stream);
     if (rc != PXR_OK) return rc;
     return pxr_render_batch(s, d_poses, d_shapes, B, S, step0, env0, d_frames, d_ids, hip_stream);
+}
+
+int pxr_render_batch_kinematic_static(pxr_scene* s, const float* d_free_poses, const float* d_angles,
+                                      const float* d_shapes, uint32_t B, uint32_t S, uint32_t step0, uint32_t env0,
+                                      uint8_t* d_frames, uint32_t* d_ids, void* hip_stream) {
+    if (!s) return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch_kinematic_static: null scene");
+    if (B == 0 || S == 0 || (uint64_t)B * S > 0x7FFFFFFFull)
+        return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch_kinematic_static: B*S must lie in [1, 2^31-1]");
+    if (!d_frames) return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch_kinematic_static: null frames");
+    float* d_poses = nullptr;
+    size_t capacity = 0;
+    std::string err;
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess || device != s->device)
+        return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch_kinematic_static: the scene's device must be the current one");
+    const int rc = pxr::static_pose_scratch(&d_poses, &capacity, err);
+    if (rc != PXR_OK) return fail(rc, "pxr_render_batch_kinematic_static: " + err);
+    const uint64_t need = (uint64_t)B * S * s->sc.K * 7ull * sizeof(float);
+    if (need > capacity)
+        return fail(PXR_ERR_UNSUPPORTED, "pxr_render_batch_kinematic_static: B*S*n_bodies*28 = " + std::to_string(need) +
+                                             " bytes of poses exceed the library's " + std::to_string(capacity) +
+                                             "-byte static buffer; use pxr_render_batch_kinematic with a buffer of your own");
+    // (every pose the render kernel reads is written by the kinematics kernel in front of it on the same stream:
+    // nothing of an earlier call's contents is used, so nothing needs clearing)
+    return pxr_render_batch_kinematic(s, d_free_poses, d_angles, d_shapes, B, S, step0, env0, d_poses, d_frames, d_ids,
+                                      hip_stream);
 }
 
 int pxr_scene_info(const pxr_scene* s, uint32_t* n_verts, uint32_t* n_tris, uint32_t* lds_bytes, uint32_t* block_threads) {

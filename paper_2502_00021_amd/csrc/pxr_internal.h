@@ -155,6 +155,10 @@ int prepare_fk_kernel(std::string& err);
 int launch_fk(const SkeletonConsts& sk, const float* d_free_poses, const float* d_angles, uint32_t n_frames,
               float* d_poses, void* stream, std::string& err);
 
+// static_scratch.hip: this device's copy of the library's file-scope pose buffer (looked up on the first call
+// per device, cached afterwards) and its size.  Allocates nothing.
+int static_pose_scratch(float** out, size_t* capacity_bytes, std::string& err);
+
 }  // namespace pxr
 
 #endif

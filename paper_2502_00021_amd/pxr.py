@@ -95,6 +95,8 @@ def lib():
         L.pxr_set_skeleton.argtypes = [vp, C.POINTER(SkeletonDesc)]
         L.pxr_pose_batch.argtypes = [vp, vp, vp, u32, vp, vp]
         L.pxr_render_batch_kinematic.argtypes = [vp, vp, vp, vp, u32, u32, u32, u32, vp, vp, vp, vp]
+        L.pxr_render_batch_kinematic_static.argtypes = [vp, vp, vp, vp, u32, u32, u32, u32, vp, vp, vp]
+        L.pxr_render_batch_kinematic_static.restype = C.c_int
         L.pxr_conv_create.argtypes = [C.POINTER(ConvDesc), C.POINTER(vp)]
         L.pxr_conv_destroy.argtypes = [vp]
         L.pxr_conv_forward.argtypes = [vp, vp, u32, vp, vp]
@@ -347,6 +349,28 @@ class Scene:
                                                 int(step0), int(env0), poses.data_ptr(), frames.data_ptr(),
                                                 None if ids is None else ids.data_ptr(), C.c_void_p(stream)))
         return frames, ids, poses
+
+
+    def render_batch_kinematic_static(self, free_poses, angles, shapes=None, step0=0, env0=0, frames=None, ids=None,
+                                      stream=None):
+        """pxr_render_batch_kinematic_static: like render_batch_kinematic, the poses staying in the library's own
+        static device buffer.  `frames` (and `ids`, if wanted) must be given: this call allocates nothing."""
+        import torch
+        lead, n, dev, pf, pa = self._fk_args(free_poses, angles)
+        B, S = lead
+        assert frames is not None and frames.is_cuda and frames.is_contiguous() and frames.dtype == torch.uint8
+        assert tuple(frames.shape) == (B, S, self.H, self.W, 3)
+        if ids is not None:
+            assert ids.is_cuda and ids.is_contiguous() and ids.dtype == torch.int32 and tuple(ids.shape) == (B, S, self.H, self.W)
+        if shapes is not None:
+            assert shapes.is_cuda and shapes.dtype == torch.float32 and shapes.is_contiguous()
+            assert tuple(shapes.shape) == (B, self.K, 4)
+        if stream is None:
+            stream = torch.cuda.current_stream(dev).cuda_stream
+        _check(lib().pxr_render_batch_kinematic_static(self._h, pf, pa, None if shapes is None else shapes.data_ptr(), B, S,
+                                                       int(step0), int(env0), frames.data_ptr(),
+                                                       None if ids is None else ids.data_ptr(), C.c_void_p(stream)))
+        return frames, ids
 
 
 class Conv:
