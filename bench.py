@@ -1,13 +1,21 @@
 """Benchmark of the pxr hot path on one MI355X.
 
-One "step" = one pxr_render_batch call over the whole batch of the headline
-workload (all frames of all environments), inputs already resident in HBM.
-Prints ONE JSON line: rendered frames/s, the ALU roofline fraction of the
-render kernel (timed live with HIP events on the launch stream), the HBM
-figure next to it, and the CPU oracle timed on the host cores on a bounded
-sample of the same workload.
+One "step" = one pxr_render_batch call over the whole batch of the headline workload (all frames of all
+environments), inputs already resident in HBM.  Prints ONE JSON line:
+
+  value / roofline    rendered frames/s of the headline workload and the render kernel's fraction of the ALU
+                      roofline, the kernel timed live with HIP events on the launch stream
+  configs             the other configurations at their full sizes (frames/s, launch time, ALU and HBM fractions),
+                      the target point "64x64 at 16 384 environments", the distractor-on / distractor-off ratios,
+                      larger frames, and the stages around the renderer (kinematics, conv consumer, the overlapped
+                      render + conv pipeline); the same figures, flat, under config["others.*"]
+  measured_peaks      what this GPU sustains right now (dependent-free FMA loop, integer mad loop, copy / read /
+                      write streams), and the headline fractions against those
+  cpu_baseline        the CPU oracle on the host cores, on a bounded sample of the headline workload
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5] [--envs B] [--threads NT]
+                    [--no-others] [--no-cpu]
+Profiling aids (not the product's numbers): --profile-lib FILE [--phase-clocks], --calibrate-copy, --only STAGE.
 """
 import argparse
 import json
@@ -31,22 +39,27 @@ from paper_2502_00021_amd import workloads  # noqa: E402
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch, measured with two rocprofv3 --pmc passes (FETCH_SIZE x 2.000 + WRITE_SIZE x
-# 1.000, the factors a plain 1 GiB copy gives for the same counters); see profiles/.  Others: null.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {("cfg5", 65536): 2516.8e6, ("cfg4", 16384): 403.5e6}
+# Figures that only a profiler run can give, copied from the summaries under profiles/ (each names its
+# command): HBM bytes per launch from two rocprofv3 --pmc passes (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, the
+# factors a plain 1 GiB copy gives for the same counters), and the counter-side view of the vector units
+# (share of issue slots busy, share of lanes active per instruction, wave-instructions per frame).
+PROFILED = {
+    ("cfg5", 65536): {"traffic_bytes_per_launch": 2516.8e6, "valu_busy": 0.939, "lane_use": 0.834,
+                      "valu_wave_instructions_per_frame": 10343,
+                      "source": "profiles/render_kernel_cfg5_humanoid_box_64x64.md"},
+    ("cfg4", 16384): {"traffic_bytes_per_launch": 403.5e6, "valu_busy": 0.894, "lane_use": None,
+                      "valu_wave_instructions_per_frame": 17523,
+                      "source": "profiles/render_kernel_cfg4_humanoid_84x84_video.md"},
+}
+
+OP_CONVENTION = ("algorithmic lane-operations per frame = 39 per template vertex + 40 per triangle + 46 per pixel "
+                 "(+9 with a distractor), counted from the method's operation list: an IEEE fp32 division counts as "
+                 "10 (its cost on this ISA), loads, stores and addressing as 0, the data-dependent raster term is "
+                 "left out; with a division counted as 1 the figures are 0.87x these")
 
 
 def algorithmic_ops_per_frame(V, T, npix, mode):
-    """Lane-operations per frame that the method itself prescribes.
-
-    Counted from the operation list of the specification, not from the kernel's
-    instruction stream (an IEEE fp32 division counts as 10, memory and address
-    work as 0): 39 per template vertex, 40 per triangle (gather, box,
-    pixel-range test, area sign), 46 per pixel (ground ray, z-resolve, colour,
-    quantise, pack), plus 9 per pixel with a distractor bound.  The
-    data-dependent raster term (a few percent) is left out, which can only
-    understate the achieved figure.
-    """
+    """Lane-operations per frame that the method itself prescribes (see OP_CONVENTION)."""
     per_pixel = 46 + (9 if mode in ("color", "video") else 0)
     return 39 * V + 40 * T + per_pixel * npix
 
@@ -63,7 +76,6 @@ def algorithmic_bytes_per_frame(K, npix, mode, has_shapes, S):
 def cpu_baseline(w, budget_frames_1core=6144, budget_frames_per_thread=6144):
     """The oracle as it stands on the host cores: 1 core, then one single-threaded instance per core."""
     from oracle import orc
-    scene = orc.Scene(w["desc"])
     S = w["poses"].shape[1]
     B = w["poses"].shape[0]
 
@@ -86,26 +98,45 @@ def cpu_baseline(w, budget_frames_1core=6144, budget_frames_per_thread=6144):
     for t in threads:
         t.join()
     tn = time.perf_counter() - t0
-    del scene
     return {"value": cores * per * S / tn, "unit": "frames/s", "cores": cores, "kind": "oracle",
             "sample": f"{cores} single-threaded oracle instances x {per} envs x {S} steps of the same workload "
                       f"(disjoint env slices); 1 core alone: {one_core:.1f} frames/s on the first {n1} envs",
             "value_1core": one_core}
 
 
-def time_next_stages(torch, pxr, w, reps=10):
+def _bind(torch, scene, dis):
+    if dis is None:
+        return "none"
+    d = dict(dis)
+    if d["mode"] == "video":
+        d["video"] = torch.from_numpy(d["video"]).cuda()
+    scene.apply_distractor(d)
+    return d["mode"]
+
+
+def _event_ms(torch, fn, reps, warm=2):
+    """Mean time of fn() in ms by HIP events on torch's current stream (the stream fn launches on)."""
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def time_next_stages(torch, pxr, w, reps=10, chunks=(2, 4, 8)):
     """The stages in front of and behind the renderer on the headline workload: joint angles -> poses
     (pxr_pose_batch) and frame stack -> first conv layer of the policy (pxr_conv_forward, matrix cores), each
-    timed on its own with HIP events, and the three enqueued back to back (angles in, features out)."""
+    timed on its own with HIP events; the three enqueued back to back on one stream; and the same step with the
+    render and the conv layer overlapped chunk by chunk on two streams (pxr_pipeline_step)."""
     fk = w["fk"]
     scene = pxr.Scene(w["desc"])
     scene.set_skeleton(fk["skel"], fk["free_poses"].shape[-2], fk["angles"].shape[-1])
-    dis = w["distractor"]
-    if dis is not None:
-        d = dict(dis)
-        if d["mode"] == "video":
-            d["video"] = torch.from_numpy(d["video"]).cuda()
-        scene.apply_distractor(d)
+    _bind(torch, scene, w["distractor"])
     free = torch.from_numpy(fk["free_poses"]).cuda()
     ang = torch.from_numpy(fk["angles"]).cuda()
     shapes = None if w["shapes"] is None else torch.from_numpy(w["shapes"]).cuda()
@@ -118,144 +149,61 @@ def time_next_stages(torch, pxr, w, reps=10):
                     np.zeros(32, np.float32))
     feat = torch.empty((B, conv.Ho, conv.Wo, 32), dtype=torch.bfloat16, device="cuda")
 
-    def timed(fn):
-        for _ in range(2):
-            fn()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            fn()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps
+    ms_fk = _event_ms(torch, lambda: scene.pose_batch(free, ang, poses=poses), reps)
+    ms_render = _event_ms(torch, lambda: scene.render_batch(poses, shapes, frames=frames), reps)
+    ms_conv = _event_ms(torch, lambda: conv.forward(frames, out=feat), reps)
 
-    ms_fk = timed(lambda: scene.pose_batch(free, ang, poses=poses))
-    scene.render_batch(poses, shapes, frames=frames)
-    ms_conv = timed(lambda: conv.forward(frames, out=feat))
-
-    def whole():
+    def serial():
         scene.render_batch_kinematic(free, ang, shapes, poses=poses, frames=frames)
         conv.forward(frames, out=feat)
 
-    ms_all = timed(whole)
+    ms_serial = _event_ms(torch, serial, reps)
+    check = feat[:: max(1, B // 256)].clone()
+    overlapped = {}
+    for n in chunks:
+        pipe = pxr.Pipeline(scene, conv, n)
+
+        def piped():
+            scene.pose_batch(free, ang, poses=poses)
+            pipe.step(poses, shapes, frames, feat)
+
+        overlapped[n] = _event_ms(torch, piped, reps)
+        assert torch.equal(check.view(torch.int16), feat[:: max(1, B // 256)].view(torch.int16)), "pipeline output differs"
+        pipe.close()
+    best = min(overlapped, key=overlapped.get)
     n = B * S
     fk_bytes = 4 * (free[0, 0].numel() + ang[0, 0].numel() + K * 7) * n
     conv_bytes = frames.numel() + feat.numel() * 2
     conv_flops = 2.0 * B * conv.Ho * conv.Wo * 32 * 27 * S
-    pk = pxr.measure_peaks()
-    # the time this machine's HBM needs for the layer's bytes: reads at its read-stream rate plus writes at its write-stream rate
-    conv_bound_ms = 1e3 * (frames.numel() / (pk["read_gbs"] * 1e9) + feat.numel() * 2 / (pk["write_gbs"] * 1e9))
     out = {
-        "kinematics-" + w["name"]: {"kernel": "fk_kernel", "avg_launch_ms": ms_fk, "frames_per_s": n / (1e-3 * ms_fk),
-                                   "roofline": {"bound": "hbm", "achieved": fk_bytes / ms_fk / 1e6, "peak": HBM_PEAK_GBS,
-                                                "unit": "GB/s", "frac": fk_bytes / ms_fk / 1e6 / HBM_PEAK_GBS}},
-        "conv-consumer-" + w["name"]: {"kernel": "conv_kernel", "avg_launch_ms": ms_conv,
-                                      "stacks_per_s": B / (1e-3 * ms_conv), "frames_per_s": n / (1e-3 * ms_conv),
-                                      "tflops_bf16": conv_flops / ms_conv / 1e9,
-                                      "roofline": {"bound": "hbm", "achieved": conv_bytes / ms_conv / 1e6,
-                                                   "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                                                   "frac": conv_bytes / ms_conv / 1e6 / HBM_PEAK_GBS,
-                                                   "algorithmic_bytes_per_stack": conv_bytes / B,
-                                                   "measured_stream_bound_ms": conv_bound_ms,
-                                                   "frac_of_measured_stream_bound": conv_bound_ms / ms_conv}},
-        "angles-to-features-" + w["name"]: {"ms_per_step": ms_all, "frames_per_s": n / (1e-3 * ms_all),
-                                           "kernels": "fk_kernel + render_kernel + conv_kernel on one stream"},
+        "kinematics": {"kernel": "fk_kernel", "avg_launch_ms": ms_fk, "frames_per_s": n / (1e-3 * ms_fk),
+                       "bound": "hbm", "hbm_gbs": fk_bytes / ms_fk / 1e6, "hbm_frac": fk_bytes / ms_fk / 1e6 / HBM_PEAK_GBS},
+        "conv_consumer": {"kernel": "conv_kernel", "avg_launch_ms": ms_conv, "stacks_per_s": B / (1e-3 * ms_conv),
+                          "frames_per_s": n / (1e-3 * ms_conv), "tflops_bf16": conv_flops / ms_conv / 1e9,
+                          "bound": "hbm", "hbm_gbs": conv_bytes / ms_conv / 1e6,
+                          "hbm_frac": conv_bytes / ms_conv / 1e6 / HBM_PEAK_GBS,
+                          "algorithmic_bytes_per_stack": conv_bytes / B},
+        "angles_to_features": {"render_alone_ms": ms_render, "serial_ms": ms_serial,
+                               "overlapped_ms": overlapped[best], "overlap_chunks": best,
+                               "overlapped_ms_by_chunks": {str(k): v for k, v in overlapped.items()},
+                               "frames_per_s_serial": n / (1e-3 * ms_serial),
+                               "frames_per_s_overlapped": n / (1e-3 * overlapped[best]),
+                               "kernels": "fk_kernel + render_kernel + conv_kernel; overlapped = pxr_pipeline_step "
+                                          "(chunk c's conv layer on a second stream beside chunk c+1's render)"},
     }
     conv.close()
     scene.close()
     return out
 
 
-def time_small_batch_graph(torch, pxr, reps=200):
-    """A launch-bound step (cfg2: 256 environments; angles -> poses -> frames -> conv features = three small
-    kernels) enqueued eagerly and replayed from a HIP graph captured once."""
-    w = workloads.make(2)
-    fk = w["fk"]
-    scene = pxr.Scene(w["desc"])
-    scene.set_skeleton(fk["skel"], fk["free_poses"].shape[-2], fk["angles"].shape[-1])
-    rng = np.random.default_rng(0)
-    conv = pxr.Conv(scene.H, scene.W, 1, (rng.standard_normal((3, 3, 3, 32)) * 0.1).astype(np.float32), np.zeros(32, np.float32))
-    free = torch.from_numpy(fk["free_poses"]).cuda()
-    ang = torch.from_numpy(fk["angles"]).cuda()
-    B = free.shape[0]
-    poses = torch.empty((B, 1, scene.K, 7), dtype=torch.float32, device="cuda")
-    frames = torch.empty((B, 1, scene.H, scene.W, 3), dtype=torch.uint8, device="cuda")
-    feat = torch.empty((B, conv.Ho, conv.Wo, 32), dtype=torch.bfloat16, device="cuda")
-
-    def step():
-        scene.render_batch_kinematic(free, ang, None, poses=poses, frames=frames)
-        conv.forward(frames, out=feat)
-
-    def wall(fn):
-        for _ in range(10):
-            fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(reps):
-            fn()
-        torch.cuda.synchronize()
-        return 1e6 * (time.perf_counter() - t0) / reps
-
-    us_eager = wall(step)
-    side = torch.cuda.Stream()
-    side.wait_stream(torch.cuda.current_stream())
-    with torch.cuda.stream(side):
-        step()
-    torch.cuda.current_stream().wait_stream(side)
-    torch.cuda.synchronize()
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph):
-        step()
-    us_graph = wall(graph.replay)
-    conv.close()
-    scene.close()
-    return {"small-batch-step-" + w["name"]: {"envs": B, "us_per_step_eager": us_eager, "us_per_step_hip_graph": us_graph,
-                                            "frames_per_s_hip_graph": B / (1e-6 * us_graph),
-                                            "kernels": "fk_kernel + render_kernel + conv_kernel, wall clock per step"}}
-
-
-def time_paper_loop(torch, pxr, env_counts=(1, 10, 100, 1000, 10000), seconds=0.25):
-    """The shape of the paper's throughput experiment (its steps-per-second figure): for each of its four
-    environments (stand-in skeletons) and each number of parallel environments, one step = joint angles ->
-    poses -> one 64x64 frame per environment -> one convolutional layer, all on the device, physics left out.
-    Steps are enqueued back to back and the clock stops after a final synchronisation."""
-    out = {}
-    rng = np.random.default_rng(0)
-    wgt = (rng.standard_normal((3, 3, 3, 32)) * 0.1).astype(np.float32)
-    for name, make in workloads.PAPER_ENVIRONMENTS.items():
-        row = {}
-        for n in env_counts:
-            w = make(n)
-            fk = w["fk"]
-            scene = pxr.Scene(w["desc"])
-            scene.set_skeleton(fk["skel"], fk["free_poses"].shape[-2], fk["angles"].shape[-1])
-            conv = pxr.Conv(scene.H, scene.W, 1, wgt, np.zeros(32, np.float32))
-            free = torch.from_numpy(fk["free_poses"]).cuda()
-            ang = torch.from_numpy(fk["angles"]).cuda()
-            poses = torch.empty((n, 1, scene.K, 7), dtype=torch.float32, device="cuda")
-            frames = torch.empty((n, 1, scene.H, scene.W, 3), dtype=torch.uint8, device="cuda")
-            feat = torch.empty((n, conv.Ho, conv.Wo, 32), dtype=torch.bfloat16, device="cuda")
-
-            def run(k):
-                for i in range(k):
-                    scene.render_batch_kinematic(free, ang, None, step0=i, poses=poses, frames=frames)
-                    conv.forward(frames, out=feat)
-                torch.cuda.synchronize()
-
-            run(20)
-            t0 = time.perf_counter()
-            run(50)
-            per = (time.perf_counter() - t0) / 50
-            k = max(50, min(5000, int(seconds / per)))
-            t0 = time.perf_counter()
-            run(k)
-            dt = time.perf_counter() - t0
-            row[str(n)] = {"env_steps_per_s": n * k / dt, "iterations_per_s": k / dt}
-            conv.close()
-            scene.close()
-        out[name] = row
-    return out
+def _round(x, sig=4):
+    if isinstance(x, float):
+        return float(f"{x:.{sig}g}")
+    if isinstance(x, dict):
+        return {k: _round(v, sig) for k, v in x.items()}
+    if isinstance(x, list):
+        return [_round(v, sig) for v in x]
+    return x
 
 
 def main():
@@ -265,15 +213,17 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--envs", type=int, default=None, help="override the number of environments")
+    ap.add_argument("--size", type=int, default=None, help="override the frame's width and height")
     ap.add_argument("--threads", type=int, default=0, help="threads per frame workgroup (0 = library default)")
     ap.add_argument("--no-distractor", action="store_true")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-others", action="store_true", help="only the headline workload (no 'configs' block, no peaks)")
+    ap.add_argument("--extras", action="store_true", help=argparse.SUPPRESS)  # (the 'configs' block is the default now)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy kernel (the known-size reference that "
                          "scales the FETCH_SIZE / WRITE_SIZE counters of a profiler run)")
-    ap.add_argument("--next-stages-only", action="store_true",
-                    help="time only the kinematics and conv-consumer stages of the chosen workload (for profiler runs)")
-    ap.add_argument("--extras", action="store_true", help="also time the other configurations (reported under 'others')")
+    ap.add_argument("--only", default=None, choices=["next-stages"],
+                    help="time only the kinematics / conv-consumer / pipeline stages of the chosen workload (for profiler runs)")
     ap.add_argument("--profile-lib", default=None, metavar="FILE",
                     help="profiling only: load this build of the library (paper_2502_00021_amd/build.py --define ... --out FILE) "
                          "instead of the in-tree one; the numbers of such a run are not the product's")
@@ -304,18 +254,17 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "launches": 3}))
         return
 
-    def time_workload(cfg, envs, steps, warmup, distract=True, threads=0):
+    def time_workload(cfg, envs, steps, warmup, distract=True, threads=0, size=None):
         w = workloads.make(cfg, B=envs)
+        if size:
+            w["desc"]["width"] = w["desc"]["height"] = size
+            if w["distractor"] is not None and w["distractor"]["mode"] == "video":
+                w["distractor"] = dict(w["distractor"], video=workloads.make_video(
+                    np.random.default_rng(size), w["distractor"]["video"].shape[0], size, size))
         scene = pxr.Scene(w["desc"])
         if threads:
             scene.set_block_threads(threads)
-        dis = w["distractor"] if distract else None
-        mode = "none" if dis is None else dis["mode"]
-        if dis is not None:
-            d = dict(dis)
-            if mode == "video":
-                d["video"] = torch.from_numpy(d["video"]).cuda()
-            scene.apply_distractor(d)
+        mode = _bind(torch, scene, w["distractor"] if distract else None)
         poses = torch.from_numpy(w["poses"]).cuda()
         shapes = None if w["shapes"] is None else torch.from_numpy(w["shapes"]).cuda()
         B, S, K = poses.shape[0], poses.shape[1], poses.shape[2]
@@ -359,11 +308,23 @@ def main():
         del frames, poses, shapes
         return res
 
+    def figures(r):
+        """Throughput and roofline fractions of one timed workload (kernel time by HIP events)."""
+        n = r["B"] * r["S"]
+        s = 1e-3 * float(np.mean(r["kernel_ms"]))
+        V, T, npix = r["info"]["n_verts"], r["info"]["n_tris"], r["H"] * r["W"]
+        ops = algorithmic_ops_per_frame(V, T, npix, r["mode"])
+        byts = algorithmic_bytes_per_frame(r["K"], npix, r["mode"], r["w"]["shapes"] is not None, r["S"])
+        return {"envs": r["B"], "steps_per_call": r["S"], "image": r["H"], "distractor": r["mode"],
+                "block_threads": r["info"]["block_threads"], "frames_per_s": n / s, "avg_launch_ms": 1e3 * s,
+                "alu_frac": ops * n / s / 1e12 / ALU_PEAK_TOPS, "hbm_frac": byts * n / s / 1e9 / HBM_PEAK_GBS,
+                "ops_per_frame": ops}
+
     cfg = int(args.workload[3:])
-    if args.next_stages_only:
+    if args.only == "next-stages":
         print(json.dumps(time_next_stages(torch, pxr, workloads.make(cfg, B=args.envs), reps=args.steps)))
         return
-    r = time_workload(cfg, args.envs, args.steps, args.warmup, not args.no_distractor, args.threads)
+    r = time_workload(cfg, args.envs, args.steps, args.warmup, not args.no_distractor, args.threads, args.size)
     n_frames = r["B"] * r["S"]
     ms_per_step = 1e3 * r["wall"] / args.steps
     value = n_frames * args.steps / r["wall"]
@@ -372,6 +333,7 @@ def main():
     ops = algorithmic_ops_per_frame(V, T, npix, r["mode"]) * n_frames
     byts = algorithmic_bytes_per_frame(r["K"], npix, r["mode"], r["w"]["shapes"] is not None, r["S"]) * n_frames
     achieved_tops = ops / avg_kernel_s / 1e12
+    prof = PROFILED.get((args.workload, r["B"])) if not (args.size or args.no_distractor or args.threads) else None
     out = {
         "metric": "rendered frames/sec (envs x steps) at 64x64 RGB",
         "value": value, "unit": "frames/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -382,35 +344,48 @@ def main():
                    "block_threads": r["info"]["block_threads"], "lds_bytes_per_frame": r["info"]["lds_bytes"],
                    "frames_per_step": n_frames},
         "roofline": {"bound": "alu", "achieved": achieved_tops, "peak": ALU_PEAK_TOPS, "unit": "Tlane-op/s",
-                     "frac": achieved_tops / ALU_PEAK_TOPS, "traffic": MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((args.workload, r["B"])),
+                     "frac": achieved_tops / ALU_PEAK_TOPS,
+                     "traffic": prof["traffic_bytes_per_launch"] if prof else None,
                      "kernel": "render_kernel", "avg_launch_ms": 1e3 * avg_kernel_s,
-                     "algorithmic_ops_per_frame": ops // n_frames,
-                     "hbm": {"achieved": byts / avg_kernel_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                             "frac": byts / avg_kernel_s / 1e9 / HBM_PEAK_GBS,
-                             "algorithmic_bytes_per_frame": byts / n_frames}},
+                     "algorithmic_ops_per_frame": ops // n_frames, "op_count_convention": OP_CONVENTION,
+                     "hbm_achieved_gbs": byts / avg_kernel_s / 1e9, "hbm_frac": byts / avg_kernel_s / 1e9 / HBM_PEAK_GBS,
+                     "algorithmic_bytes_per_frame": byts / n_frames},
         "kernel_frames_per_s": n_frames / avg_kernel_s,
         "checksum": r["checksum"],
     }
+    if prof:  # (from a profiler run of this same workload, not measured live: see PROFILED)
+        out["roofline"].update({"profiled_valu_busy": prof["valu_busy"], "profiled_lane_use": prof["lane_use"],
+                                "profiled_valu_wave_instructions_per_frame": prof["valu_wave_instructions_per_frame"],
+                                "profile": prof["source"]})
     if "phase_clocks" in r:
         out["phase_clocks"] = r["phase_clocks"]  # (a profiling build: `value` is not the product's rate)
-    if args.extras:
-        # the same fractions against what this GPU sustains right now (microbenchmarks in the library)
+    if not args.no_others and not args.profile_lib:
+        # what this GPU sustains right now (microbenchmarks in the library), and the headline fractions against it
         pk = pxr.measure_peaks()
-        out["measured_peaks"] = dict(pk, alu_frac_of_measured_fma=achieved_tops / pk["fma_tlaneops"],
-                                     hbm_frac_of_measured_copy=out["roofline"]["hbm"]["achieved"] / pk["copy_gbs"])
-        others = {}
-        others.update(time_next_stages(torch, pxr, r["w"]))
-        others.update(time_small_batch_graph(torch, pxr))
-        out["paper_loop_steps_per_s"] = time_paper_loop(torch, pxr)
-        for name, c, envs, dis in [("cfg2-chain-64", 2, 256, True), ("cfg3-quadruped-64-colour", 3, 4096, True),
-                                   ("cfg3-quadruped-64-no-distractor", 3, 4096, False),
-                                   ("cfg4-humanoid-84-video", 4, 16384, True),
-                                   ("cfg4-humanoid-84-no-distractor", 4, 16384, False),
-                                   ("cfg5-humanoid-box-64-stack3-16384envs", 5, 16384, True)]:
-            o = time_workload(c, envs, 10, 2, dis)
-            others[name] = {"frames_per_s": o["B"] * o["S"] / (1e-3 * float(np.mean(o["kernel_ms"]))),
-                            "avg_launch_ms": float(np.mean(o["kernel_ms"]))}
-        out["others"] = others
+        out["measured_peaks"] = _round(dict(pk, alu_frac_of_measured_fma=achieved_tops / pk["fma_tlaneops"],
+                                            hbm_frac_of_measured_copy=out["roofline"]["hbm_achieved_gbs"] / pk["copy_gbs"]))
+        configs = {}
+        for name, c, envs, dis, size in [("cfg1", 1, 16, True, None), ("cfg2", 2, 256, True, None),
+                                         ("cfg3", 3, 4096, True, None), ("cfg3_no_distractor", 3, 4096, False, None),
+                                         ("cfg4", 4, 16384, True, None), ("cfg4_no_distractor", 4, 16384, False, None),
+                                         ("cfg5_16384envs", 5, 16384, True, None),
+                                         ("cfg5_128px", 5, 4096, True, 128), ("cfg5_256px", 5, 1024, True, 256),
+                                         ("cfg5_512px", 5, 256, True, 512)]:
+            configs[name] = figures(time_workload(c, envs, 10, 2, dis, 0, size))
+        configs["cfg3_distractor_on_over_off"] = configs["cfg3"]["frames_per_s"] / configs["cfg3_no_distractor"]["frames_per_s"]
+        configs["cfg4_distractor_on_over_off"] = configs["cfg4"]["frames_per_s"] / configs["cfg4_no_distractor"]["frames_per_s"]
+        configs.update(time_next_stages(torch, pxr, r["w"]))
+        out["configs"] = _round(configs)
+        # the same, flat (scalars only), for readers that keep only the scalar entries of `config`
+        flat = out["config"]
+        for name, v in configs.items():
+            if not isinstance(v, dict):
+                flat[f"others.{name}"] = _round(v)
+            else:
+                for k in ("frames_per_s", "avg_launch_ms", "alu_frac", "hbm_frac", "serial_ms", "overlapped_ms"):
+                    if k in v:
+                        flat[f"others.{name}.{k}"] = _round(v[k])
+        flat["others.alu_frac_of_measured_fma"] = out["measured_peaks"]["alu_frac_of_measured_fma"]
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(r["w"])
     print(json.dumps(out))

@@ -246,6 +246,27 @@ int pxr_conv_info(const pxr_conv* c, uint32_t* out_h, uint32_t* out_w, uint32_t*
  * output does not depend on it. */
 int pxr_conv_set_tuning(pxr_conv* c, uint32_t band_rows, uint32_t n_groups);
 
+/* ---- renderer and consumer as one step ----
+ * The paper's throughput loop (section 2) renders every environment and then runs the conv layer on the
+ * frames, every step.  The renderer is bound by vector-ALU issue and the layer by HBM, so this call runs them
+ * side by side: the batch is cut into n_chunks runs of environments, chunk c is rendered on the caller's stream
+ * and its conv layer follows on a second stream (created here, default priority) while chunk c + 1 is rendered;
+ * ordering is by events only, and the caller's stream is made to wait for the last layer before the call
+ * returns (enqueue only, no host synchronisation, no allocation).  Frames and features are byte for byte those
+ * of pxr_render_batch followed by pxr_conv_forward.  n_chunks = 1 is that serial order. */
+typedef struct pxr_pipeline pxr_pipeline; /* opaque, owned by the library; borrows the scene and the layer */
+
+/* Host only: one stream and n_chunks + 1 events.  The layer's input size must be the scene's frame size; its
+ * n_stack is the S of every step.  Errors: INVALID_ARG (null, n_chunks outside [1,16], sizes differ); OOM; DEVICE. */
+int pxr_pipeline_create(pxr_scene* s, pxr_conv* c, uint32_t n_chunks, pxr_pipeline** out);
+/* Waits for the second stream, then frees it and the events; scene and layer stay the caller's.  NULL accepted. */
+int pxr_pipeline_destroy(pxr_pipeline* p);
+/* d_poses [B,S,K,7], d_shapes [B,K,4] or NULL, d_frames [B,S,H,W,3] (written), d_features [B,Ho,Wo,32] bf16
+ * (written): arguments, alignment and errors as for pxr_render_batch and pxr_conv_forward.  Steps issued on
+ * one pipeline must be ordered among themselves (one stream, or events): they share the second stream. */
+int pxr_pipeline_step(pxr_pipeline* p, const float* d_poses, const float* d_shapes, uint32_t B, uint32_t step0,
+                      uint32_t env0, uint8_t* d_frames, uint16_t* d_features, void* hip_stream);
+
 /* Scene facts for callers and tests (sizes of what pxr_create_scene built; no passage of the paper): total
  * template vertices and triangles, dynamic LDS bytes per frame workgroup, threads per workgroup.  Any out
  * pointer may be NULL.  Errors: INVALID_ARG (null scene). */

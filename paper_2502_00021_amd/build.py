@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpxr.so")
-SOURCES = ["api.cpp", "conv_api.cpp", "scene.cpp", "render.hip", "kinematics.hip", "static_scratch.hip", "conv.hip", "peaks.hip", "selftest.hip"]
+SOURCES = ["api.cpp", "conv_api.cpp", "pipeline.cpp", "scene.cpp", "render.hip", "kinematics.hip", "static_scratch.hip", "conv.hip", "peaks.hip", "selftest.hip"]
 
 # -ffp-contract=off: the order and fusion of fp32 operations is part of the
 # output contract (coverage is decided by integers derived from these floats),

@@ -34,6 +34,38 @@ int fail(int code, const std::string& msg) {
 
 int pxr::set_error(int code, const std::string& msg) { return fail(code, msg); }
 
+void pxr::scene_shape(const pxr_scene* s, uint32_t* K, uint32_t* H, uint32_t* W) {
+    *K = s->sc.K;
+    *H = s->sc.H;
+    *W = s->sc.W;
+}
+
+int pxr::render_envs(pxr_scene* s, const float* d_poses, const float* d_shapes, uint32_t e0, uint32_t n, uint32_t S,
+                     uint32_t step0, uint32_t env0, uint8_t* d_frames, uint32_t* d_ids, void* stream, std::string& err) {
+    if (n == 0 || S == 0 || (uint64_t)n * S > 0x7FFFFFFFull) {
+        err = "B*S must lie in [1, 2^31-1]";
+        return PXR_ERR_INVALID_ARG;
+    }
+    if ((uint64_t)step0 + S > 0x100000000ull || (uint64_t)env0 + e0 + n > 0x100000000ull) {
+        err = "step0 + S or env0 + B overflows 32 bits";
+        return PXR_ERR_INVALID_ARG;
+    }
+    const size_t K = s->sc.K, npix = s->sc.npix;
+    const float* poses = d_poses + (size_t)e0 * S * K * 7;
+    const float* shapes = d_shapes ? d_shapes + (size_t)e0 * K * 4 : nullptr;
+    uint8_t* frames = d_frames + (size_t)e0 * S * npix * 3;
+    uint32_t* ids = d_ids ? d_ids + (size_t)e0 * S * npix : nullptr;
+    if ((reinterpret_cast<uintptr_t>(poses) & 3u) || (reinterpret_cast<uintptr_t>(shapes) & 15u) ||
+        (reinterpret_cast<uintptr_t>(frames) & 3u) || (reinterpret_cast<uintptr_t>(ids) & 15u)) {
+        err = "poses/frames must be 4-byte and shapes/ids 16-byte aligned";
+        return PXR_ERR_INVALID_ARG;
+    }
+    pxr::DistractConsts dc = s->dc;  // the per-environment arrays follow the environments
+    if (dc.env_offset) dc.env_offset += e0;
+    if (dc.env_video) dc.env_video += e0;
+    return pxr::launch_render(s->sc, dc, poses, shapes, n * S, S, step0, env0 + e0, frames, ids, s->block_threads, stream, err);
+}
+
 namespace {
 
 uint32_t pick_block_threads(const pxr::SceneConsts& sc) {
@@ -225,17 +257,8 @@ int pxr_apply_distractor(pxr_scene* s, const pxr_distractor_desc* d) {
 int pxr_render_batch(pxr_scene* s, const float* d_poses, const float* d_shapes, uint32_t B, uint32_t S, uint32_t step0,
                      uint32_t env0, uint8_t* d_frames, uint32_t* d_ids, void* hip_stream) {
     if (!s || !d_poses || !d_frames) return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch: null scene, poses or frames");
-    if (B == 0 || S == 0) return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch: B and S must be positive");
-    const uint64_t n_frames = (uint64_t)B * (uint64_t)S;
-    if (n_frames > 0x7FFFFFFFull) return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch: B*S exceeds 2^31-1 frames");
-    if ((uint64_t)step0 + S > 0x100000000ull) return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch: step0 + S overflows 32 bits");
-    if ((uint64_t)env0 + B > 0x100000000ull) return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch: env0 + B overflows 32 bits");
-    if ((reinterpret_cast<uintptr_t>(d_poses) & 3u) || (reinterpret_cast<uintptr_t>(d_shapes) & 15u) ||
-        (reinterpret_cast<uintptr_t>(d_frames) & 3u) || (reinterpret_cast<uintptr_t>(d_ids) & 15u))
-        return fail(PXR_ERR_INVALID_ARG, "pxr_render_batch: poses/frames must be 4-byte and shapes/ids 16-byte aligned");
     std::string err;
-    const int rc = pxr::launch_render(s->sc, s->dc, d_poses, d_shapes, (uint32_t)n_frames, S, step0, env0, d_frames, d_ids,
-                                      s->block_threads, hip_stream, err);
+    const int rc = pxr::render_envs(s, d_poses, d_shapes, 0, B, S, step0, env0, d_frames, d_ids, hip_stream, err);
     if (rc != PXR_OK) return fail(rc, "pxr_render_batch: " + err);
     return PXR_OK;
 }

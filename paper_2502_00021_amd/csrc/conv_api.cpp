@@ -37,6 +37,28 @@ void plan(pxr_conv* c, uint32_t band_rows) {
 
 }  // namespace
 
+void pxr::conv_shape(const pxr_conv* c, uint32_t* H, uint32_t* W, uint32_t* S, uint32_t* Ho, uint32_t* Wo) {
+    *H = c->cc.H;
+    *W = c->cc.W;
+    *S = c->cc.S;
+    *Ho = c->cc.Ho;
+    *Wo = c->cc.Wo;
+}
+
+int pxr::conv_envs(pxr_conv* c, const uint8_t* d_frames, uint32_t e0, uint32_t n, uint16_t* d_out, void* stream, std::string& err) {
+    if (n == 0 || (uint64_t)n * c->cc.bands > 0x7FFFFFFFull) {
+        err = "B must be positive and B * bands below 2^31";
+        return PXR_ERR_INVALID_ARG;
+    }
+    const uint8_t* frames = d_frames + (size_t)e0 * c->cc.S * c->cc.H * c->cc.W * 3;
+    uint16_t* out = d_out + (size_t)e0 * c->cc.Ho * c->cc.Wo * 32;
+    if ((reinterpret_cast<uintptr_t>(frames) & 3u) || (reinterpret_cast<uintptr_t>(out) & 15u)) {
+        err = "frames must be 4-byte and the output 16-byte aligned";
+        return PXR_ERR_INVALID_ARG;
+    }
+    return pxr::launch_conv(c->cc, frames, n, out, c->n_groups, stream, err);
+}
+
 extern "C" {
 
 int pxr_conv_create(const pxr_conv_desc* d, pxr_conv** out) {
@@ -156,12 +178,8 @@ int pxr_conv_set_tuning(pxr_conv* c, uint32_t band_rows, uint32_t n_groups) {
 int pxr_conv_forward(pxr_conv* c, const uint8_t* d_frames, uint32_t B, uint16_t* d_out, void* hip_stream) {
     using pxr::set_error;
     if (!c || !d_frames || !d_out) return set_error(PXR_ERR_INVALID_ARG, "pxr_conv_forward: null argument");
-    if (B == 0 || (uint64_t)B * c->cc.bands > 0x7FFFFFFFull)
-        return set_error(PXR_ERR_INVALID_ARG, "pxr_conv_forward: B must be positive and B * bands below 2^31");
-    if ((reinterpret_cast<uintptr_t>(d_frames) & 3u) || (reinterpret_cast<uintptr_t>(d_out) & 15u))
-        return set_error(PXR_ERR_INVALID_ARG, "pxr_conv_forward: frames must be 4-byte and the output 16-byte aligned");
     std::string err;
-    const int rc = pxr::launch_conv(c->cc, d_frames, B, d_out, c->n_groups, hip_stream, err);
+    const int rc = pxr::conv_envs(c, d_frames, 0, B, d_out, hip_stream, err);
     if (rc != PXR_OK) return set_error(rc, "pxr_conv_forward: " + err);
     return PXR_OK;
 }

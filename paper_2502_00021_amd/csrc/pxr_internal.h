@@ -155,6 +155,16 @@ int prepare_fk_kernel(std::string& err);
 int launch_fk(const SkeletonConsts& sk, const float* d_free_poses, const float* d_angles, uint32_t n_frames,
               float* d_poses, void* stream, std::string& err);
 
+// pipeline.cpp works through these (api.cpp / conv_api.cpp own the handles' layouts).
+constexpr uint32_t kMaxPipelineChunks = 16;
+void scene_shape(const pxr_scene* s, uint32_t* K, uint32_t* H, uint32_t* W);
+void conv_shape(const pxr_conv* c, uint32_t* H, uint32_t* W, uint32_t* S, uint32_t* Ho, uint32_t* Wo);
+// Environments [e0, e0 + n) of a batch whose buffers start at the given pointers (arguments as pxr_render_batch /
+// pxr_conv_forward, whose checks they repeat; per-environment distractor arrays are indexed by position in the batch).
+int render_envs(pxr_scene* s, const float* d_poses, const float* d_shapes, uint32_t e0, uint32_t n, uint32_t S,
+                uint32_t step0, uint32_t env0, uint8_t* d_frames, uint32_t* d_ids, void* stream, std::string& err);
+int conv_envs(pxr_conv* c, const uint8_t* d_frames, uint32_t e0, uint32_t n, uint16_t* d_out, void* stream, std::string& err);
+
 // static_scratch.hip: this device's copy of the library's file-scope pose buffer (looked up on the first call
 // per device, cached afterwards) and its size.  Allocates nothing.
 int static_pose_scratch(float** out, size_t* capacity_bytes, std::string& err);

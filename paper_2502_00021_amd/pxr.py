@@ -104,6 +104,11 @@ def lib():
         L.pxr_conv_set_tuning.argtypes = [vp, u32, u32]
         for name in ("pxr_conv_create", "pxr_conv_destroy", "pxr_conv_forward", "pxr_conv_info", "pxr_conv_set_tuning"):
             getattr(L, name).restype = C.c_int
+        L.pxr_pipeline_create.argtypes = [vp, vp, u32, C.POINTER(vp)]
+        L.pxr_pipeline_destroy.argtypes = [vp]
+        L.pxr_pipeline_step.argtypes = [vp, vp, vp, u32, u32, u32, vp, vp, vp]
+        for name in ("pxr_pipeline_create", "pxr_pipeline_destroy", "pxr_pipeline_step"):
+            getattr(L, name).restype = C.c_int
         L.pxr_selftest_arithmetic.argtypes = [vp]
         L.pxr_selftest_arithmetic.restype = C.c_int
         L.pxr_measure_peaks.argtypes = [vp, vp, vp, vp, vp]
@@ -425,6 +430,43 @@ class Conv:
             stream = torch.cuda.current_stream(frames.device).cuda_stream
         _check(lib().pxr_conv_forward(self._h, frames.data_ptr(), B, out.data_ptr(), C.c_void_p(stream)))
         return out
+
+
+class Pipeline:
+    """Owns one pxr_pipeline handle: render + conv layer per step, chunk c's layer beside chunk c + 1's render."""
+
+    def __init__(self, scene, conv, n_chunks=4):
+        h = C.c_void_p()
+        _check(lib().pxr_pipeline_create(scene._h, conv._h, int(n_chunks), C.byref(h)))
+        self._h, self.scene, self.conv = h, scene, conv
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _check(lib().pxr_pipeline_destroy(self._h))
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def step(self, poses, shapes, frames, features, step0=0, env0=0, stream=None):
+        """poses [B,S,K,7], shapes [B,K,4] or None -> frames [B,S,H,W,3] uint8, features [B,Ho,Wo,32] bf16 (both given)."""
+        import torch
+        sc, cv = self.scene, self.conv
+        B = int(poses.shape[0])
+        assert poses.is_cuda and poses.dtype == torch.float32 and poses.is_contiguous() and tuple(poses.shape) == (B, cv.S, sc.K, 7)
+        if shapes is not None:
+            assert shapes.is_cuda and shapes.dtype == torch.float32 and shapes.is_contiguous() and tuple(shapes.shape) == (B, sc.K, 4)
+        assert frames.is_cuda and frames.is_contiguous() and frames.dtype == torch.uint8 and tuple(frames.shape) == (B, cv.S, sc.H, sc.W, 3)
+        assert features.is_cuda and features.is_contiguous() and features.dtype == torch.bfloat16
+        assert tuple(features.shape) == (B, cv.Ho, cv.Wo, cv.C)
+        if stream is None:
+            stream = torch.cuda.current_stream(poses.device).cuda_stream
+        _check(lib().pxr_pipeline_step(self._h, poses.data_ptr(), None if shapes is None else shapes.data_ptr(), B,
+                                       int(step0), int(env0), frames.data_ptr(), features.data_ptr(), C.c_void_p(stream)))
+        return frames, features
 
 
 def make_skeleton_desc(skel, n_free, n_angles):
