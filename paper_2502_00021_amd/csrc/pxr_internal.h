@@ -68,7 +68,12 @@ struct SceneConsts {
     // LDS carve-up (byte offsets into the dynamic segment)
     // the lds_keys region first holds the per-vertex cell codes (u32[V]) and the candidate list (u16[T])
     uint32_t lds_keys, lds_vxy, lds_vd, lds_body, lds_list, lds_large, lds_cxcy, lds_rows, lds_misc, lds_total;
+    uint32_t lds_vlut;  // video-blend tables (kVideoTableBytes), or 0 if the frame's LDS has no room for them
 };
+
+// Video distractor: for each of the five colours that can lie under the clip (background r, g, b; the two ground
+// greys) the blended, quantised byte for every clip byte: [5][256] bytes, rebuilt per frame in LDS.
+constexpr uint32_t kVideoTableBytes = 5 * 256;
 
 // Distractor state bound by pxr_apply_distractor.
 struct DistractConsts {

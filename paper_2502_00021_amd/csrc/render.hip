@@ -352,6 +352,21 @@ __device__ __forceinline__ uint32_t quantise(float c) {
 
 // ---------------------------------------------------------------- the kernel
 
+// The kernel's first two (by-value) arguments, read afresh from the kernel-argument segment: whatever the
+// compiler loaded from them before is not reused after this point.  The band loop of tall frames takes its
+// constants through this at the top of every trip, so that they are fetched again (scalar loads that hit the
+// constant cache) instead of being kept in scalar registers across the whole loop, which the 1024-thread
+// variants do not have.
+constexpr uint32_t kSceneArgAt = 0;
+constexpr uint32_t kDistractArgAt = (sizeof(SceneConsts) + alignof(DistractConsts) - 1) / alignof(DistractConsts) * alignof(DistractConsts);
+template <typename T>
+__device__ __forceinline__ const T& argument_reloaded(uint32_t byte_offset) {
+    typedef const __attribute__((address_space(4))) unsigned char* KernargBytes;
+    KernargBytes p = (KernargBytes)__builtin_amdgcn_kernarg_segment_ptr() + byte_offset;
+    asm volatile("" : "+s"(p));
+    return *(const T*)(const __attribute__((address_space(4))) T*)p;
+}
+
 // Phase probes: empty in the library.  A profiling build (-DPXR_PROFILING_BUILD, made into a file of its own
 // by build.py --define) takes them from a header that the library's build never includes.
 #ifdef PXR_PROFILING_BUILD
@@ -384,6 +399,7 @@ struct ResolveCtx {
     float scale[3], offs[3];
     uint32_t col_addr;     // LDS byte address of the three colours as floats [3][3]
     uint32_t packed_addr;  // and as packed bytes [3]
+    uint32_t vlut;         // LDS byte address of the video-blend tables, 0 = none
     const uint8_t* vframe;
 };
 
@@ -407,6 +423,7 @@ __device__ __forceinline__ u64 ground_key(const SceneConsts& sc, const ResolveCt
 // UNIT_CELL: the checkerboard cell is 1 m, so the division by the cell size is the identity, and the ground point
 // cannot be a NaN (a finite or infinite eye, a far plane within 2^64), so the one-instruction floor-and-convert serves.
 // Triangle g as a 24-bit colour: flat Lambert + ambient in the body frame, then the colour distractor.
+template <bool VIDEO>
 __device__ __forceinline__ uint32_t shade_triangle(const SceneConsts& sc, const ResolveCtx& rc, const float* body, uint32_t g) {
     const float4 ns = reinterpret_cast<const float4*>(sc.tri_shade)[g];
     const float4* o4 = reinterpret_cast<const float4*>(body + (sc.tri_idx[g * 2 + 1] >> 16) * kBodyStride);
@@ -420,7 +437,7 @@ __device__ __forceinline__ uint32_t shade_triangle(const SceneConsts& sc, const 
     for (int ch = 0; ch < 3; ++ch) {
         float v = (o_rgb[ch] * ns.w) * sh;
         v = v < 1.0f ? v : 1.0f;
-        if (rc.mode == PXR_DISTRACT_COLOR) {
+        if (!VIDEO && rc.mode == PXR_DISTRACT_COLOR) {
             v = __builtin_fmaf(v, rc.scale[ch], rc.offs[ch]);
             v = v > 0.0f ? v : 0.0f;
             v = v < 1.0f ? v : 1.0f;
@@ -442,16 +459,16 @@ __device__ __forceinline__ uint32_t checker_cells(const SceneConsts& sc, const R
 }
 
 // DEFER_TRIANGLES: a triangle pixel returns 0 here; the caller shades it (compacted over the wavefront).
-template <bool UNIT_CELL, bool DEFER_TRIANGLES = false>
+template <bool UNIT_CELL, bool VIDEO, bool DEFER_TRIANGLES = false>
 __device__ __forceinline__ uint32_t resolve_pixel(const SceneConsts& sc, const ResolveCtx& rc, const float* body, u64 key,
                                                   u64 gkey, float tg, float dwx, float dwy, uint32_t vbytes, uint32_t& low,
                                                   u64& tri_lanes) {
     key = key > gkey ? key : gkey;
     low = (uint32_t)key;
     tri_lanes = __ballot(low > 1u);  // (taken here, beside the branch on the same comparison, it costs nothing)
-    if (low > 1u) return DEFER_TRIANGLES ? 0u : shade_triangle(sc, rc, body, 0xFFFFFFFFu - low);
+    if (low > 1u) return DEFER_TRIANGLES ? 0u : shade_triangle<VIDEO>(sc, rc, body, 0xFFFFFFFFu - low);
     // background or ground: one of three colours per frame (consecutive in LDS: background, grey 0, grey 1)
-    if (rc.mode != PXR_DISTRACT_VIDEO) {
+    if (!VIDEO) {
         uint32_t word = rc.packed_addr;
         if (low == 1u) word = rc.packed_addr + 4u + ((checker_cells<UNIT_CELL>(sc, rc, tg, dwx, dwy) & 1u) << 2);
         return lds_u32_at(word);
@@ -477,7 +494,7 @@ __device__ __forceinline__ uint32_t resolve_pixel(const SceneConsts& sc, const R
 // Phase 4 for images whose width is a multiple of 4: four consecutive pixels of one row per
 // lane.  The row part of the ray is shared, and without camera roll (NO_ROLL: the right vector is
 // horizontal) so is the whole ground test, which then costs one division per lane, not four.
-template <int NT, bool UNIT_CELL, bool NO_ROLL>
+template <int NT, bool UNIT_CELL, bool NO_ROLL, bool VIDEO>
 __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const ResolveCtx& rc, const float* body,
                                               const float* cxcy, const float4* rows, u64* keys, uint8_t* out,
                                               uint32_t* out_ids, uint32_t tid, uint32_t p_begin, uint32_t p_end) {
@@ -494,7 +511,7 @@ __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const Resol
         const float4 cx4 = *reinterpret_cast<const float4*>(cxcy + i0);
         const float cxs[4] = {cx4.x, cx4.y, cx4.z, cx4.w};
         uint32_t vid[3] = {0u, 0u, 0u};
-        if (rc.mode == PXR_DISTRACT_VIDEO) {
+        if (VIDEO) {
             const uint32_t* vsrc = reinterpret_cast<const uint32_t*>(rc.vframe) + q * 3;
             vid[0] = vsrc[0];
             vid[1] = vsrc[1];
@@ -511,7 +528,7 @@ __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const Resol
         const u64 key4[4] = {((u64)k01.y << 32) | k01.x, ((u64)k01.w << 32) | k01.z, ((u64)k23.y << 32) | k23.x, ((u64)k23.w << 32) | k23.z};
         uint32_t rgb[4], low[4];
         u64 tri_lanes[4];
-        if (rc.mode != PXR_DISTRACT_VIDEO) {
+        if (!VIDEO) {
             // One of the frame's three colours (background, two greys: consecutive words in LDS), without a branch
             // per pixel.  A triangle pixel picks up one of them as well, to be overwritten below.  Without roll a
             // row is ground or sky as a whole, so the choice between "background" and "a grey by the checker" is the
@@ -541,6 +558,36 @@ __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const Resol
                 }
                 rgb[k] = lds_u32_at(word);
             }
+        } else if (NO_ROLL && rc.vlut) {
+            // Video distractor, no roll, tables in LDS: a row is sky or ground as a whole, so under the clip lies
+            // the background or one of the two greys by the checker's parity, and the blended byte of a channel
+            // is one byte read from the table of that colour, indexed by the clip's byte where it lies in the three
+            // words that brought it (byte n = channel n % 3 of pixel n / 3).  A triangle pixel gets a blended colour
+            // as well, replaced below.
+            {
+                const bool ground_row = tg_row != 0.0f;
+                uint32_t tab[3];
+#pragma unroll
+                for (int ch = 0; ch < 3; ++ch) tab[ch] = rc.vlut + (ground_row ? 768u : 256u * ch);
+                const uint32_t odd_step = ground_row ? 256u : 0u;  // the second grey's table follows the first's
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    const u64 key = key4[k] > gkey_row ? key4[k] : gkey_row;
+                    low[k] = (uint32_t)key;
+                    tri_lanes[k] = __ballot(low[k] > 1u);
+                    const float dwx = __builtin_fmaf(sc.Rt[0], cxs[k], rx);
+                    const float dwy = __builtin_fmaf(sc.Rt[1], cxs[k], ry);
+                    const uint32_t off = (checker_cells<UNIT_CELL>(sc, rc, tg_row, dwx, dwy) << 8) & odd_step;
+                    uint32_t packed = 0;
+#pragma unroll
+                    for (int ch = 0; ch < 3; ++ch) {
+                        const int n = 3 * k + ch;
+                        const uint32_t at = tab[ch] + off + ((vid[n / 4] >> (8 * (n % 4))) & 0xFFu);
+                        packed |= (uint32_t)*reinterpret_cast<const __attribute__((address_space(3))) uint8_t*>(static_cast<uintptr_t>(at)) << (8 * ch);
+                    }
+                    rgb[k] = packed;
+                }
+            }
         } else {
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -549,7 +596,7 @@ __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const Resol
                 if (!NO_ROLL) gkey = ground_key(sc, rc, -__builtin_fmaf(sc.Rt[2], cxs[k], rz), tg);
                 const float dwx = __builtin_fmaf(sc.Rt[0], cxs[k], rx);
                 const float dwy = __builtin_fmaf(sc.Rt[1], cxs[k], ry);
-                rgb[k] = resolve_pixel<UNIT_CELL, true>(sc, rc, body, key4[k], gkey, tg, dwx, dwy, vb[k], low[k], tri_lanes[k]);
+                rgb[k] = resolve_pixel<UNIT_CELL, VIDEO, true>(sc, rc, body, key4[k], gkey, tg, dwx, dwy, vb[k], low[k], tri_lanes[k]);
             }
         }
         // Triangle pixels are few and clustered: instead of every lane walking the shading code four
@@ -569,7 +616,7 @@ __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const Resol
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             const u64 active = __ballot(true);  // the last trip of a ragged band may run with fewer lanes
             for (uint32_t i = lanes_below(active); i < total; i += (uint32_t)__popcll(active))
-                list[i] = shade_triangle(sc, rc, body, 0xFFFFFFFFu - list[i]);
+                list[i] = shade_triangle<VIDEO>(sc, rc, body, 0xFFFFFFFFu - list[i]);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -591,7 +638,7 @@ __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const Resol
 // Register budget: two 80 KB workgroups share a compute unit, so 1024-thread groups need all
 // 8 wave slots per SIMD (<= 64 VGPRs); the smaller groups may use more registers.
 // BANDED: the key buffer holds only `band_rows` rows at a time and phases 3-4 loop over bands.
-template <int NT, int PX, bool BANDED>
+template <int NT, int PX, bool BANDED, bool VIDEO>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ? 8 : (NT >= 768 ? 6 : 4)))) void render_kernel(
     const SceneConsts sc, const DistractConsts dc, const float* __restrict__ poses, const float* __restrict__ shapes,
     uint32_t S, uint32_t step0, uint32_t env0, uint8_t* __restrict__ frames, uint32_t* __restrict__ ids) {
@@ -709,7 +756,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     // a thousand clocks after the first.  The draws are this phase's longest chain beside the bodies': they belong on
     // an early wavefront that has nothing else to do - the third - and the late ones get no work here at all.)
     constexpr uint32_t kDrawLane = NT >= 1024 ? 191u : NT - 1u;  // last lane of the third wavefront (of the last: smaller groups)
-    if (tid <= kDrawLane && tid >= kDrawLane - 1u && dc.mode == PXR_DISTRACT_COLOR) {
+    if (!VIDEO && tid <= kDrawLane && tid >= kDrawLane - 1u && dc.mode == PXR_DISTRACT_COLOR) {
         // The colour draws are two generator streams, the longest serial chain of this phase: the two
         // lanes walk one stream each, side by side; the offsets go through LDS to the last lane.
         const uint32_t stream = kDrawLane - tid;
@@ -726,7 +773,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     if (tid == kDrawLane) {
         fu->bins = 0ull;
         fu->n_cand = 0;
-        if (dc.mode == PXR_DISTRACT_VIDEO) {
+        if (VIDEO) {
             uint32_t first;
             if (dc.env_offset) {
                 first = dc.env_offset[e];
@@ -748,12 +795,28 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
             fu->video_frame = clip * dc.n_frames + (uint32_t)(((u64)first + (u64)step) % dc.n_frames);
         }
     }
+    if (VIDEO && sc.lds_vlut) {
+        // Video-blend tables: under the clip lies the background or a ground grey (no colour distractor in this
+        // mode), so a blended channel is a function of (one of five colours, clip byte).  Four entries per lane.
+        uint32_t* vlut = reinterpret_cast<uint32_t*>(lds + sc.lds_vlut);
+        for (uint32_t i = tid; i < kVideoTableBytes / 4; i += NT) {
+            const uint32_t t = i >> 6;
+            const float c = t == 0 ? sc.bg[0] : t == 1 ? sc.bg[1] : t == 2 ? sc.bg[2] : t == 3 ? sc.gs[0] : sc.gs[1];
+            uint32_t word = 0;
+#pragma unroll
+            for (uint32_t e = 0; e < 4; ++e) {
+                const float vf = (float)((i & 63u) * 4u + e) * (1.0f / 255.0f);
+                word |= quantise(__builtin_fmaf(dc.alpha, vf - c, c)) << (8 * e);
+            }
+            vlut[i] = word;
+        }
+    }
     if (tid <= kDrawLane && tid >= kDrawLane - 2u) {
         // Background and the two ground greys are the same for every pixel that shows them: they go through
         // the colour distractor and the quantiser once per frame, one lane per colour.
         const uint32_t k = kDrawLane - tid;
         float scale[3] = {1.0f, 1.0f, 1.0f}, offs[3] = {0.0f, 0.0f, 0.0f};
-        if (dc.mode == PXR_DISTRACT_COLOR) {
+        if (!VIDEO && dc.mode == PXR_DISTRACT_COLOR) {
 #pragma unroll
             for (int c = 0; c < 3; ++c) {
                 scale[c] = fu->scale[c];
@@ -764,7 +827,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
 #pragma unroll
         for (int c = 0; c < 3; ++c) {
             float v = k == 0u ? sc.bg[c] : (k == 1u ? sc.gs[0] : sc.gs[1]);
-            if (dc.mode == PXR_DISTRACT_COLOR) {
+            if (!VIDEO && dc.mode == PXR_DISTRACT_COLOR) {
                 v = __builtin_fmaf(v, scale[c], offs[c]);
                 v = v > 0.0f ? v : 0.0f;
                 v = v < 1.0f ? v : 1.0f;
@@ -773,7 +836,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
             packed |= quantise(v) << (8 * c);
         }
         fu->base_packed[k] = packed;
-        if (k == 0u && dc.mode != PXR_DISTRACT_COLOR) {
+        if (k == 0u && (VIDEO || dc.mode != PXR_DISTRACT_COLOR)) {
 #pragma unroll
             for (int c = 0; c < 3; ++c) {
                 fu->scale[c] = 1.0f;
@@ -900,9 +963,26 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     // Tall frames are rendered in horizontal bands so that the key buffer stays small enough for two
     // workgroups per compute unit; geometry work (phases 0-2) is done once, raster and resolve per band.
     uint32_t row_lo = 0;
+    const uint32_t tid_kept = tid;
     do {
-        const uint32_t row_hi = BANDED ? min(sc.H, row_lo + sc.band_rows) : sc.H;
-        const uint32_t p_begin = row_lo * sc.W, p_end = row_hi * sc.W;
+        const SceneConsts& scb = BANDED ? argument_reloaded<SceneConsts>(kSceneArgAt) : sc;
+        const DistractConsts& dcb = BANDED ? argument_reloaded<DistractConsts>(kDistractArgAt) : dc;
+        // (In the band loop everything is derived again from the reloaded arguments and from a thread index the
+        // compiler cannot see through: nothing but the row counter and the index stays live from band to band.)
+        uint32_t tid = tid_kept;
+        if (BANDED) asm volatile("" : "+v"(tid));
+        const uint32_t lane = tid & 63u;
+        u64* keys = reinterpret_cast<u64*>(lds + scb.lds_keys);
+        int2* vxy = reinterpret_cast<int2*>(lds + scb.lds_vxy);
+        float* vd = reinterpret_cast<float*>(lds + scb.lds_vd);
+        float* body = reinterpret_cast<float*>(lds + scb.lds_body);
+        float* cxcy = reinterpret_cast<float*>(lds + scb.lds_cxcy);
+        float4* rows = reinterpret_cast<float4*>(lds + scb.lds_rows);
+        FrameUniforms* fu = reinterpret_cast<FrameUniforms*>(lds + scb.lds_misc);
+        uint16_t* list = reinterpret_cast<uint16_t*>(lds + scb.lds_list);
+        uint16_t* list2 = reinterpret_cast<uint16_t*>(lds + scb.lds_large);
+        const uint32_t row_hi = BANDED ? min(scb.H, row_lo + scb.band_rows) : scb.H;
+        const uint32_t p_begin = row_lo * scb.W, p_end = row_hi * scb.W;
         if (row_lo) __syncthreads();  // the previous band's keys have been resolved
 
         // The bins are complete: each lane asks now for the first triangle it will raster from the small and from the
@@ -911,12 +991,12 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         const u64 bins = fu->bins;
         const uint32_t n_tiny = (uint32_t)bins & 0xFFFFu, n_small = (uint32_t)bins >> 16, n_large = (uint32_t)(bins >> 32);
         constexpr uint32_t kTeam = 1u << kSmallLanesLog2;
-        const uint2* tri_table = reinterpret_cast<const uint2*>(sc.tri_idx);
+        const uint2* tri_table = reinterpret_cast<const uint2*>(scb.tri_idx);
         // (Asked for without a branch, so that nothing has to wait for the answers here: a lane with no triangle in a
         // bin reads a list entry that may never have been written and clamps it into the table.)
-        uint32_t t_small = list[sc.T - 1 - min(tid >> kSmallLanesLog2, sc.T - 1u)];
-        uint32_t t_tiny = list[min(NT - 1 - tid, sc.T - 1u)];
-        uint2 ti_small = tri_table[min(t_small, sc.T - 1u)], ti_tiny = tri_table[min(t_tiny, sc.T - 1u)];
+        uint32_t t_small = list[scb.T - 1 - min(tid >> kSmallLanesLog2, scb.T - 1u)];
+        uint32_t t_tiny = list[min(NT - 1 - tid, scb.T - 1u)];
+        uint2 ti_small = tri_table[min(t_small, scb.T - 1u)], ti_tiny = tri_table[min(t_tiny, scb.T - 1u)];
 
         // codes and candidates are dead: clear the pixel keys they shared LDS with (0 = background at depth 0)
         // (two keys per store; the region is padded to 16 bytes, so an odd count may clear one key more)
@@ -932,17 +1012,17 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         // small: a team of lanes per triangle, from the first lane up
         // (a lane's first triangle of each was requested before the barrier; the next one is at the loop's end)
         for (uint32_t k = tid >> kSmallLanesLog2; k < n_small;) {
-            raster_binned<false>(sc, t_small, ti_small, vxy, vd, keys, (int)(tid & (kTeam - 1u)), (int)kSmallLanesLog2,
+            raster_binned<false>(scb, t_small, ti_small, vxy, vd, keys, (int)(tid & (kTeam - 1u)), (int)kSmallLanesLog2,
                                  (int)row_lo, (int)row_hi);
             k += NT >> kSmallLanesLog2;
             if (k < n_small) {
-                t_small = list[sc.T - 1 - k];
+                t_small = list[scb.T - 1 - k];
                 ti_small = tri_table[t_small];
             }
         }
         // tiny: one lane per triangle, from the last lane down
         for (uint32_t k = NT - 1 - tid; k < n_tiny;) {
-            raster_binned<false>(sc, t_tiny, ti_tiny, vxy, vd, keys, 0, 0, (int)row_lo, (int)row_hi);
+            raster_binned<false>(scb, t_tiny, ti_tiny, vxy, vd, keys, 0, 0, (int)row_lo, (int)row_hi);
             k += NT;
             if (k < n_tiny) {
                 t_tiny = list[k];
@@ -951,7 +1031,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         }
         // large: a whole wave per triangle, starting in the middle waves
         for (uint32_t k = ((tid >> 6) + NT / 128) % (NT / 64); k < n_large; k += NT / 64)
-            raster_binned<true>(sc, list2[k], tri_table[list2[k]], vxy, vd, keys, (int)lane, 6, (int)row_lo, (int)row_hi);
+            raster_binned<true>(scb, list2[k], tri_table[list2[k]], vxy, vd, keys, (int)lane, 6, (int)row_lo, (int)row_hi);
         PXR_TIMED_BARRIER(5);
         PXR_PHASE_MARK(5);
 
@@ -961,74 +1041,75 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         rc.eye_x = eye_x;
         rc.eye_y = eye_y;
         rc.eye_z = eye_z;
-        const bool no_roll = sc.Rt[2] == 0.0f;
+        const bool no_roll = scb.Rt[2] == 0.0f;
         rc.inv_ez = (PX == 4 && no_roll) ? 0.0f : 1.0f / eye_z;  // (the row table already holds the ground test)
-        rc.ground_ok = sc.ground_on && eye_z > 0.0f;
-        rc.mode = dc.mode;
-        rc.alpha = dc.alpha;
+        rc.ground_ok = scb.ground_on && eye_z > 0.0f;
+        rc.mode = dcb.mode;
+        rc.alpha = dcb.alpha;
         rc.vframe = nullptr;
 #pragma unroll
         for (int c = 0; c < 3; ++c) {
             rc.scale[c] = fu->scale[c];
             rc.offs[c] = fu->offs[c];
         }
-        rc.col_addr = sc.lds_misc + (uint32_t)offsetof(FrameUniforms, base_col);
-        rc.packed_addr = sc.lds_misc + (uint32_t)offsetof(FrameUniforms, base_packed);
-        if (rc.mode == PXR_DISTRACT_VIDEO) rc.vframe = dc.video + (size_t)fu->video_frame * sc.npix * 3;
-        uint8_t* out = frames + (size_t)frame * sc.npix * 3;
-        uint32_t* out_ids = ids ? ids + (size_t)frame * sc.npix : nullptr;
+        rc.col_addr = scb.lds_misc + (uint32_t)offsetof(FrameUniforms, base_col);
+        rc.packed_addr = scb.lds_misc + (uint32_t)offsetof(FrameUniforms, base_packed);
+        rc.vlut = scb.lds_vlut;
+        if (VIDEO) rc.vframe = dcb.video + (size_t)fu->video_frame * scb.npix * 3;
+        uint8_t* out = frames + (size_t)frame * scb.npix * 3;
+        uint32_t* out_ids = ids ? ids + (size_t)frame * scb.npix : nullptr;
         if (PX == 4) {
             // uniform scene properties select a specialised loop (kept out of the per-pixel code)
             // (an eye that is a NaN makes ground points NaNs: such a frame takes the general loop, which is exact
             // for a unit cell as well)
-            if (sc.checker_short_form && eye_x == eye_x && eye_y == eye_y) {
+            if (scb.checker_short_form && eye_x == eye_x && eye_y == eye_y) {
                 if (no_roll)
-                    resolve_rows4<NT, true, true>(sc, rc, body, cxcy, rows, keys, out, out_ids, tid, p_begin, p_end);
+                    resolve_rows4<NT, true, true, VIDEO>(scb, rc, body, cxcy, rows, keys, out, out_ids, tid, p_begin, p_end);
                 else
-                    resolve_rows4<NT, true, false>(sc, rc, body, cxcy, rows, keys, out, out_ids, tid, p_begin, p_end);
+                    resolve_rows4<NT, true, false, VIDEO>(scb, rc, body, cxcy, rows, keys, out, out_ids, tid, p_begin, p_end);
             } else {
                 if (no_roll)
-                    resolve_rows4<NT, false, true>(sc, rc, body, cxcy, rows, keys, out, out_ids, tid, p_begin, p_end);
+                    resolve_rows4<NT, false, true, VIDEO>(scb, rc, body, cxcy, rows, keys, out, out_ids, tid, p_begin, p_end);
                 else
-                    resolve_rows4<NT, false, false>(sc, rc, body, cxcy, rows, keys, out, out_ids, tid, p_begin, p_end);
+                    resolve_rows4<NT, false, false, VIDEO>(scb, rc, body, cxcy, rows, keys, out, out_ids, tid, p_begin, p_end);
             }
         } else {
             // any image shape: one pixel per lane, byte stores
             for (uint32_t p = p_begin + tid; p < p_end; p += NT) {
-                const uint32_t j = __umulhi(p, sc.magicW);
-                const uint32_t i = p - j * sc.W;
-                const float cxi = cxcy[i], cyj = cxcy[sc.W + j];
-                const float dwx = __builtin_fmaf(sc.Rt[0], cxi, __builtin_fmaf(sc.Up[0], cyj, sc.Fw[0]));
-                const float dwy = __builtin_fmaf(sc.Rt[1], cxi, __builtin_fmaf(sc.Up[1], cyj, sc.Fw[1]));
-                const float dwz = __builtin_fmaf(sc.Rt[2], cxi, __builtin_fmaf(sc.Up[2], cyj, sc.Fw[2]));
+                const uint32_t j = __umulhi(p, scb.magicW);
+                const uint32_t i = p - j * scb.W;
+                const float cxi = cxcy[i], cyj = cxcy[scb.W + j];
+                const float dwx = __builtin_fmaf(scb.Rt[0], cxi, __builtin_fmaf(scb.Up[0], cyj, scb.Fw[0]));
+                const float dwy = __builtin_fmaf(scb.Rt[1], cxi, __builtin_fmaf(scb.Up[1], cyj, scb.Fw[1]));
+                const float dwz = __builtin_fmaf(scb.Rt[2], cxi, __builtin_fmaf(scb.Up[2], cyj, scb.Fw[2]));
                 float tg;
-                const u64 gkey = ground_key(sc, rc, -dwz, tg);
+                const u64 gkey = ground_key(scb, rc, -dwz, tg);
                 uint32_t vbytes = 0;
-                if (rc.mode == PXR_DISTRACT_VIDEO) {
+                if (VIDEO) {
                     const uint8_t* v = rc.vframe + (size_t)p * 3;
                     vbytes = (uint32_t)v[0] | ((uint32_t)v[1] << 8) | ((uint32_t)v[2] << 16);
                 }
                 uint32_t low;
                 u64 unused;
-                const uint32_t rgb = resolve_pixel<false>(sc, rc, body, keys[p - p_begin], gkey, tg, dwx, dwy, vbytes, low, unused);
+                const uint32_t rgb = resolve_pixel<false, VIDEO>(scb, rc, body, keys[p - p_begin], gkey, tg, dwx, dwy, vbytes, low, unused);
                 out[(size_t)p * 3 + 0] = (uint8_t)(rgb & 0xFFu);
                 out[(size_t)p * 3 + 1] = (uint8_t)((rgb >> 8) & 0xFFu);
                 out[(size_t)p * 3 + 2] = (uint8_t)(rgb >> 16);
                 if (out_ids) out_ids[p] = 0xFFFFFFFFu - low;
             }
         }
-        row_lo += sc.band_rows;
-    } while (BANDED && row_lo < sc.H);
+        row_lo += scb.band_rows;
+    } while (BANDED && row_lo < argument_reloaded<SceneConsts>(kSceneArgAt).H);
     PXR_PHASE_MARK(6);
     PXR_PHASE_END();
 }
 
-template <int NT, int PX, bool BANDED>
+template <int NT, int PX, bool BANDED, bool VIDEO>
 int launch_one(const SceneConsts& sc, const DistractConsts& dc, const float* d_poses, const float* d_shapes,
                uint32_t n_frames, uint32_t S, uint32_t step0, uint32_t env0, uint8_t* d_frames, uint32_t* d_ids,
                hipStream_t stream, std::string& err) {
-    hipLaunchKernelGGL((render_kernel<NT, PX, BANDED>), dim3(n_frames), dim3(NT), sc.lds_total, stream, sc, dc, d_poses,
-                       d_shapes, S, step0, env0, d_frames, d_ids);
+    hipLaunchKernelGGL((render_kernel<NT, PX, BANDED, VIDEO>), dim3(n_frames), dim3(NT), sc.lds_total, stream, sc, dc,
+                       d_poses, d_shapes, S, step0, env0, d_frames, d_ids);
     const hipError_t rc = hipGetLastError();
     if (rc != hipSuccess) {
         err = std::string("kernel launch failed: ") + hipGetErrorString(rc);
@@ -1037,15 +1118,15 @@ int launch_one(const SceneConsts& sc, const DistractConsts& dc, const float* d_p
     return PXR_OK;
 }
 
-template <int NT, int PX, bool BANDED>
+template <int NT, int PX, bool BANDED, bool VIDEO>
 int prepare_one(uint32_t lds_bytes, std::string& err) {
     hipFuncAttributes attr;
-    if (hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(&render_kernel<NT, PX, BANDED>)) != hipSuccess ||
+    if (hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(&render_kernel<NT, PX, BANDED, VIDEO>)) != hipSuccess ||
         attr.sharedSizeBytes != 0) {
         err = "the render kernel has static LDS in front of its dynamic segment (LDS addresses in the tables assume none)";
         return PXR_ERR_DEVICE;
     }
-    const hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&render_kernel<NT, PX, BANDED>),
+    const hipError_t rc = hipFuncSetAttribute(reinterpret_cast<const void*>(&render_kernel<NT, PX, BANDED, VIDEO>),
                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
     if (rc != hipSuccess) {
         err = std::string("hipFuncSetAttribute(MaxDynamicSharedMemorySize) failed: ") + hipGetErrorString(rc);
@@ -1057,10 +1138,14 @@ int prepare_one(uint32_t lds_bytes, std::string& err) {
 template <int NT>
 int prepare_all(uint32_t cap, std::string& err) {
     int rc;
-    if ((rc = prepare_one<NT, 4, false>(cap, err))) return rc;
-    if ((rc = prepare_one<NT, 4, true>(cap, err))) return rc;
-    if ((rc = prepare_one<NT, 1, false>(cap, err))) return rc;
-    if ((rc = prepare_one<NT, 1, true>(cap, err))) return rc;
+    if ((rc = prepare_one<NT, 4, false, false>(cap, err))) return rc;
+    if ((rc = prepare_one<NT, 4, true, false>(cap, err))) return rc;
+    if ((rc = prepare_one<NT, 1, false, false>(cap, err))) return rc;
+    if ((rc = prepare_one<NT, 1, true, false>(cap, err))) return rc;
+    if ((rc = prepare_one<NT, 4, false, true>(cap, err))) return rc;
+    if ((rc = prepare_one<NT, 4, true, true>(cap, err))) return rc;
+    if ((rc = prepare_one<NT, 1, false, true>(cap, err))) return rc;
+    if ((rc = prepare_one<NT, 1, true, true>(cap, err))) return rc;
     return PXR_OK;
 }
 
@@ -1089,10 +1174,15 @@ int launch_render(const SceneConsts& sc, const DistractConsts& dc, const float* 
     // four pixels per lane: they must share a row and frames must stay dword-aligned
     const bool quad = (sc.W % 4u) == 0u;
     const bool banded = sc.band_rows < sc.H;
+    // (the video distractor has kernels of its own: the others carry none of its code, and the other way round)
+    const bool video = dc.mode == PXR_DISTRACT_VIDEO;
 #define PXR_ARGS sc, dc, d_poses, d_shapes, n_frames, S, step0, env0, d_frames, d_ids, st, err
-#define PXR_LAUNCH(NT)                                                                        \
-    return quad ? (banded ? launch_one<NT, 4, true>(PXR_ARGS) : launch_one<NT, 4, false>(PXR_ARGS)) \
-                : (banded ? launch_one<NT, 1, true>(PXR_ARGS) : launch_one<NT, 1, false>(PXR_ARGS))
+#define PXR_LAUNCH_V(NT, V)                                                                            \
+    return quad ? (banded ? launch_one<NT, 4, true, V>(PXR_ARGS) : launch_one<NT, 4, false, V>(PXR_ARGS)) \
+                : (banded ? launch_one<NT, 1, true, V>(PXR_ARGS) : launch_one<NT, 1, false, V>(PXR_ARGS))
+#define PXR_LAUNCH(NT)                   \
+    if (video) PXR_LAUNCH_V(NT, true);   \
+    PXR_LAUNCH_V(NT, false)
     switch (block_threads) {
         case 256: PXR_LAUNCH(256);
         case 512: PXR_LAUNCH(512);
@@ -1103,6 +1193,7 @@ int launch_render(const SceneConsts& sc, const DistractConsts& dc, const float* 
             return PXR_ERR_INVALID_ARG;
     }
 #undef PXR_LAUNCH
+#undef PXR_LAUNCH_V
 #undef PXR_ARGS
 }
 

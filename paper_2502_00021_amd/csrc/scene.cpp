@@ -486,6 +486,14 @@ int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
         c.lds_large = o;
         o += align(c.T * 2, 4);
         c.lds_total = align(o, 16);
+        // Video distractor: blended byte by (colour under the clip, clip byte), five tables of 256 bytes
+        // (background r, g, b, the two greys).  Taken only where it costs no workgroup per compute unit.
+        c.lds_vlut = 0;
+        const uint32_t with_tables = c.lds_total + kVideoTableBytes;
+        if (with_tables <= 160u * 1024u && (160u * 1024u) / with_tables == (160u * 1024u) / c.lds_total) {
+            c.lds_vlut = c.lds_total;
+            c.lds_total = with_tables;
+        }
         return c.lds_total;
     };
     const uint32_t kHalf = 80u * 1024u, kAll = 160u * 1024u, kMaxBands = 128;

@@ -472,6 +472,25 @@ def test_video_distractor_offsets_alpha_and_wrap(torch, pxr, orc):
     assert np.array_equal(plain["frames"], gpu_render(torch, pxr, w2, step0=3)["frames"])  # alpha = 0
 
 
+def test_video_distractor_with_and_without_blend_tables(torch, pxr, orc):
+    """The video blend reads per-frame tables from LDS where the frame's LDS has room for them (small scenes, banded
+    frames) and does the arithmetic per pixel where it has not (the largest unbanded scenes), or when the camera rolls."""
+    rng = np.random.default_rng(99)
+    for cfg, B, roll, has_tables in [(5, 10, False, False), (3, 12, False, True), (3, 8, True, True), (4, 6, False, True)]:
+        w = wl.make(cfg, B=B)
+        H, W = w["desc"]["height"], w["desc"]["width"]
+        if roll:
+            w["desc"]["cam_up"] = (0.0, 0.3, 1.0)
+        w["distractor"] = dict(mode="video", seed=cfg, video=rng.integers(0, 256, (9, H, W, 3), dtype=np.uint8),
+                               alpha=0.35, env_offset=None)
+        sc = pxr.Scene(w["desc"])
+        lds = sc.info()["lds_bytes"]
+        sc.close()
+        if not has_tables:  # two workgroups per compute unit as it is, one if the 1280 bytes of tables were added
+            assert lds <= 80 * 1024 < lds + 1280
+        assert_parity(gpu_render(torch, pxr, w, step0=5), oracle_render(orc, w, step0=5))
+
+
 def test_video_sets_one_clip_per_environment(torch, pxr, orc):
     """A set of clips [n_videos, n_frames, H, W, 3]: each environment plays one, drawn from the generator or given."""
     w = wl.make(4, B=14)
