@@ -29,6 +29,11 @@ constexpr uint32_t kTinyMaxPixels = 3;
 constexpr uint32_t kSmallMaxPixels = 128;
 constexpr uint32_t kSmallLanesLog2 = 2;
 constexpr uint32_t kNoTriangle = 0xFFFFu;
+// Banded frames: a band picks the triangles that touch its rows out of the frame's bins in rounds of one per lane;
+// a round's lists therefore never hold more than the largest workgroup has lanes.
+constexpr uint32_t kBandListEntries = 1024;
+// ... which pays from this many bands on; with fewer, every band walks all bins (lds_blist == 0).
+constexpr uint32_t kBandListsFrom = 6;
 
 // Per-body record kept in LDS for the duration of one frame (floats).
 //   [0..8]  M  = view rotation * body rotation, row-major
@@ -68,6 +73,7 @@ struct SceneConsts {
     // LDS carve-up (byte offsets into the dynamic segment)
     // the lds_keys region first holds the per-vertex cell codes (u32[V]) and the candidate list (u16[T])
     uint32_t lds_keys, lds_vxy, lds_vd, lds_body, lds_list, lds_large, lds_cxcy, lds_rows, lds_misc, lds_total;
+    uint32_t lds_blist, lds_blist2;  // banded frames: one band round's lists (kBandListEntries u16 each)
     uint32_t lds_vlut;  // video-blend tables (kVideoTableBytes), or 0 if the frame's LDS has no room for them
 };
 

@@ -185,6 +185,18 @@ __device__ __forceinline__ int tri_gather(const SceneConsts& sc, const uint2 ti,
     return (s.i0 <= s.i1 && s.j0 <= s.j1) ? kTriPlain : kTriNone;
 }
 
+// Which image rows a binned triangle can touch: kTriPlain with [j0, j1] (clamped to the image), or kTriClip for a
+// triangle that straddles the near plane (its snapped corners say nothing: it counts for every row).
+__device__ __forceinline__ int tri_rows(const SceneConsts& sc, const uint2 ti, const int2* vxy, int& j0, int& j1) {
+    const u64 a = reinterpret_cast<const u64*>(vxy)[ti.x & 0xFFFFu], b = reinterpret_cast<const u64*>(vxy)[ti.y & 0xFFFFu],
+              c = reinterpret_cast<const u64*>(vxy)[ti.x >> 16];
+    if (imin3((int)(uint32_t)a, (int)(uint32_t)b, (int)(uint32_t)c) <= kBehindX) return kTriClip;
+    const int ay = (int)(uint32_t)(a >> 32), by = (int)(uint32_t)(b >> 32), cy = (int)(uint32_t)(c >> 32);
+    j0 = max(0, (imin3(ay, by, cy) + 127) >> 8);
+    j1 = min((int)sc.H - 1, (imax3(ay, by, cy) - 128) >> 8);
+    return kTriPlain;
+}
+
 // View-space position of template vertex v (the instancing arithmetic of phase 1; also used when a
 // triangle has to be clipped).  The template's fourth word says where in LDS its body's record is.
 __device__ __forceinline__ void view_position(const SceneConsts& sc, uint32_t v, float& pvx, float& pvy, float& pvz) {
@@ -386,6 +398,8 @@ struct FrameUniforms {  // written in phase 0 (one lane) or by LDS atomics, read
     float base_col[3][3];     // background, ground grey 0, ground grey 1 after the colour distractor
     uint32_t base_packed[3];  // the same three, quantised: R | G<<8 | B<<16
     float eye[3];             // camera position (written by the first lane in phase 0 for phase 4)
+    uint32_t pad_;
+    u64 band_bins[2];         // banded frames: the three counters of one band round's lists, double-buffered by round
 };
 
 // Everything phase 4 needs that is uniform over the frame.
@@ -494,7 +508,7 @@ __device__ __forceinline__ uint32_t resolve_pixel(const SceneConsts& sc, const R
 // Phase 4 for images whose width is a multiple of 4: four consecutive pixels of one row per
 // lane.  The row part of the ray is shared, and without camera roll (NO_ROLL: the right vector is
 // horizontal) so is the whole ground test, which then costs one division per lane, not four.
-template <int NT, bool UNIT_CELL, bool NO_ROLL, bool VIDEO>
+template <int NT, bool UNIT_CELL, bool NO_ROLL, bool VIDEO, bool SELF_CLEAR>
 __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const ResolveCtx& rc, const float* body,
                                               const float* cxcy, const float4* rows, u64* keys, uint8_t* out,
                                               uint32_t* out_ids, uint32_t tid, uint32_t p_begin, uint32_t p_end) {
@@ -623,6 +637,11 @@ __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const Resol
 #pragma unroll
             for (int k = 0; k < 4; ++k)
                 if (low[k] > 1u) rgb[k] = list[slot[k]];
+        }
+        if (SELF_CLEAR) {
+            // banded frames: the lane leaves its four keys cleared for the next band (nobody else touches them)
+            reinterpret_cast<uint4*>(keys + (p0 - p_begin))[0] = make_uint4(0u, 0u, 0u, 0u);
+            reinterpret_cast<uint4*>(keys + (p0 - p_begin))[1] = make_uint4(0u, 0u, 0u, 0u);
         }
         struct alignas(4) U3 {
             uint32_t a, b, c;
@@ -773,6 +792,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     if (tid == kDrawLane) {
         fu->bins = 0ull;
         fu->n_cand = 0;
+        if (BANDED) fu->band_bins[0] = fu->band_bins[1] = 0ull;
         if (VIDEO) {
             uint32_t first;
             if (dc.env_offset) {
@@ -963,6 +983,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     // Tall frames are rendered in horizontal bands so that the key buffer stays small enough for two
     // workgroups per compute unit; geometry work (phases 0-2) is done once, raster and resolve per band.
     uint32_t row_lo = 0;
+    uint32_t band_round = 0;  // banded frames: rounds of the band-list builder so far (picks the counter slot)
     const uint32_t tid_kept = tid;
     do {
         const SceneConsts& scb = BANDED ? argument_reloaded<SceneConsts>(kSceneArgAt) : sc;
@@ -983,57 +1004,130 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         uint16_t* list2 = reinterpret_cast<uint16_t*>(lds + scb.lds_large);
         const uint32_t row_hi = BANDED ? min(scb.H, row_lo + scb.band_rows) : scb.H;
         const uint32_t p_begin = row_lo * scb.W, p_end = row_hi * scb.W;
-        if (row_lo) __syncthreads();  // the previous band's keys have been resolved
+        if (!BANDED || scb.lds_blist == 0) {
+            // Unbanded frames, and frames of a few bands (every band walks all bins: cheaper than picking a band's
+            // triangles out while a triangle's rows are looked at by two or three bands only).
+            if (BANDED && row_lo) __syncthreads();  // the previous band is resolved (its lanes left their keys cleared)
+            // The bins are complete: each lane asks now for the first triangle it will raster from the small and from the
+            // tiny bin (its list entry, then its entry of the index table), so that they come in from memory while the keys
+            // are cleared and the barrier is waited at.
+            const u64 bins = fu->bins;
+            const uint32_t n_tiny = (uint32_t)bins & 0xFFFFu, n_small = (uint32_t)bins >> 16, n_large = (uint32_t)(bins >> 32);
+            constexpr uint32_t kTeam = 1u << kSmallLanesLog2;
+            const uint2* tri_table = reinterpret_cast<const uint2*>(scb.tri_idx);
+            // (Asked for without a branch, so that nothing has to wait for the answers here: a lane with no triangle in a
+            // bin reads a list entry that may never have been written and clamps it into the table.)
+            uint32_t t_small = list[scb.T - 1 - min(tid >> kSmallLanesLog2, scb.T - 1u)];
+            uint32_t t_tiny = list[min(NT - 1 - tid, scb.T - 1u)];
+            uint2 ti_small = tri_table[min(t_small, scb.T - 1u)], ti_tiny = tri_table[min(t_tiny, scb.T - 1u)];
 
-        // The bins are complete: each lane asks now for the first triangle it will raster from the small and from the
-        // tiny bin (its list entry, then its entry of the index table), so that they come in from memory while the keys
-        // are cleared and the barrier is waited at.
-        const u64 bins = fu->bins;
-        const uint32_t n_tiny = (uint32_t)bins & 0xFFFFu, n_small = (uint32_t)bins >> 16, n_large = (uint32_t)(bins >> 32);
-        constexpr uint32_t kTeam = 1u << kSmallLanesLog2;
-        const uint2* tri_table = reinterpret_cast<const uint2*>(scb.tri_idx);
-        // (Asked for without a branch, so that nothing has to wait for the answers here: a lane with no triangle in a
-        // bin reads a list entry that may never have been written and clamps it into the table.)
-        uint32_t t_small = list[scb.T - 1 - min(tid >> kSmallLanesLog2, scb.T - 1u)];
-        uint32_t t_tiny = list[min(NT - 1 - tid, scb.T - 1u)];
-        uint2 ti_small = tri_table[min(t_small, scb.T - 1u)], ti_tiny = tri_table[min(t_tiny, scb.T - 1u)];
-
-        // codes and candidates are dead: clear the pixel keys they shared LDS with (0 = background at depth 0)
-        // (two keys per store; the region is padded to 16 bytes, so an odd count may clear one key more)
-        for (uint32_t p = tid; p < (p_end - p_begin + 1u) >> 1; p += NT)
-            reinterpret_cast<uint4*>(keys)[p] = make_uint4(0u, 0u, 0u, 0u);
-        PXR_TIMED_BARRIER(4);
-        PXR_PHASE_MARK(4);
-
-        // ---- phase 3: raster + z-test into the LDS key buffer.  The bins start at different
-        // lanes of the workgroup so that all waves get a share.
-        // The hardware favours a workgroup's older wavefronts when several want to issue, so the youngest finish a
-        // phase last: the heavier bin goes to the oldest.
-        // small: a team of lanes per triangle, from the first lane up
-        // (a lane's first triangle of each was requested before the barrier; the next one is at the loop's end)
-        for (uint32_t k = tid >> kSmallLanesLog2; k < n_small;) {
-            raster_binned<false>(scb, t_small, ti_small, vxy, vd, keys, (int)(tid & (kTeam - 1u)), (int)kSmallLanesLog2,
-                                 (int)row_lo, (int)row_hi);
-            k += NT >> kSmallLanesLog2;
-            if (k < n_small) {
-                t_small = list[scb.T - 1 - k];
-                ti_small = tri_table[t_small];
+            // codes and candidates are dead: clear the pixel keys they shared LDS with (0 = background at depth 0)
+            // (two keys per store; the region is padded to 16 bytes, so an odd count may clear one key more)
+            if (!BANDED || row_lo == 0) {
+                for (uint32_t p = tid; p < (p_end - p_begin + 1u) >> 1; p += NT)
+                    reinterpret_cast<uint4*>(keys)[p] = make_uint4(0u, 0u, 0u, 0u);
+                PXR_TIMED_BARRIER(4);
             }
-        }
-        // tiny: one lane per triangle, from the last lane down
-        for (uint32_t k = NT - 1 - tid; k < n_tiny;) {
-            raster_binned<false>(scb, t_tiny, ti_tiny, vxy, vd, keys, 0, 0, (int)row_lo, (int)row_hi);
-            k += NT;
-            if (k < n_tiny) {
-                t_tiny = list[k];
-                ti_tiny = tri_table[t_tiny];
+            PXR_PHASE_MARK(4);
+
+            // ---- phase 3: raster + z-test into the LDS key buffer.  The bins start at different
+            // lanes of the workgroup so that all waves get a share.
+            // The hardware favours a workgroup's older wavefronts when several want to issue, so the youngest finish a
+            // phase last: the heavier bin goes to the oldest.
+            // small: a team of lanes per triangle, from the first lane up
+            // (a lane's first triangle of each was requested before the barrier; the next one is at the loop's end)
+            for (uint32_t k = tid >> kSmallLanesLog2; k < n_small;) {
+                raster_binned<false>(scb, t_small, ti_small, vxy, vd, keys, (int)(tid & (kTeam - 1u)), (int)kSmallLanesLog2,
+                                     (int)row_lo, (int)row_hi);
+                k += NT >> kSmallLanesLog2;
+                if (k < n_small) {
+                    t_small = list[scb.T - 1 - k];
+                    ti_small = tri_table[t_small];
+                }
             }
+            // tiny: one lane per triangle, from the last lane down
+            for (uint32_t k = NT - 1 - tid; k < n_tiny;) {
+                raster_binned<false>(scb, t_tiny, ti_tiny, vxy, vd, keys, 0, 0, (int)row_lo, (int)row_hi);
+                k += NT;
+                if (k < n_tiny) {
+                    t_tiny = list[k];
+                    ti_tiny = tri_table[t_tiny];
+                }
+            }
+            // large: a whole wave per triangle, starting in the middle waves
+            for (uint32_t k = ((tid >> 6) + NT / 128) % (NT / 64); k < n_large; k += NT / 64)
+                raster_binned<true>(scb, list2[k], tri_table[list2[k]], vxy, vd, keys, (int)lane, 6, (int)row_lo, (int)row_hi);
+            PXR_TIMED_BARRIER(5);
+            PXR_PHASE_MARK(5);
+
+        } else {
+            // Frames of many bands.  Every band walks the frame's bins again, but only to pick out the triangles that can
+            // touch its rows: a dense pass, one lane per binned triangle and round of NT, that compacts them (ballot,
+            // one packed atomic per wavefront) into the round's own short lists, from which the raster loops then
+            // work as in the unbanded kernel.  A band that holds a twentieth of the frame's triangles rasters a
+            // twentieth of them, not all.
+            if (row_lo) __syncthreads();  // the previous band is resolved (its lanes left their keys cleared)
+            uint16_t* blist = reinterpret_cast<uint16_t*>(lds + scb.lds_blist);    // tiny up, small down: kBandListEntries
+            uint16_t* blist2 = reinterpret_cast<uint16_t*>(lds + scb.lds_blist2);  // large: kBandListEntries
+            const u64 bins = fu->bins;
+            const uint32_t n_tiny = (uint32_t)bins & 0xFFFFu, n_small = (uint32_t)bins >> 16, n_large = (uint32_t)(bins >> 32);
+            const uint32_t n_binned = n_tiny + n_small + n_large;
+            constexpr uint32_t kTeam = 1u << kSmallLanesLog2;
+            const uint2* tri_table = reinterpret_cast<const uint2*>(scb.tri_idx);
+            if (row_lo == 0) {
+                // the first band's keys share LDS with the cell codes and the candidate list, dead by now
+                for (uint32_t p = tid; p < (p_end - p_begin + 1u) >> 1; p += NT)
+                    reinterpret_cast<uint4*>(keys)[p] = make_uint4(0u, 0u, 0u, 0u);
+            }
+            uint32_t base = 0;
+            do {
+                // ---- this round's share of the bins -> the triangles among them that touch rows [row_lo, row_hi)
+                const uint32_t slot = band_round & 1u;
+                if (tid == 0) fu->band_bins[slot ^ 1u] = 0ull;  // (last read before the barrier that ended the round before this one)
+                const uint32_t k = base + tid;
+                int cls = 0;
+                uint32_t t = 0;
+                if (k < n_binned) {
+                    cls = k < n_tiny ? 1 : (k < n_tiny + n_small ? 2 : 3);
+                    t = cls == 1 ? list[k] : (cls == 2 ? list[scb.T - 1 - (k - n_tiny)] : list2[k - n_tiny - n_small]);
+                    int j0 = 0, j1 = 0;
+                    if (tri_rows(scb, tri_table[t], vxy, j0, j1) == kTriPlain && (j0 >= (int)row_hi || j1 < (int)row_lo)) cls = 0;
+                }
+                const u64 m1 = __ballot(cls == 1), m2 = __ballot(cls == 2), m3 = __ballot(cls == 3);
+                if (m1 | m2 | m3) {
+                    u64 old = 0;
+                    if (lane == 0)
+                        old = atomicAdd(&fu->band_bins[slot], (u64)__popcll(m1) | ((u64)__popcll(m2) << 16) | ((u64)__popcll(m3) << 32));
+                    const uint32_t old_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)old);
+                    const uint32_t old_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(old >> 32));
+                    // (a round looks at NT triangles: tiny and small together never outgrow the NT entries they share)
+                    if (cls == 1) blist[(old_lo & 0xFFFFu) + lanes_below(m1)] = (uint16_t)t;
+                    if (cls == 2) blist[kBandListEntries - 1 - ((old_lo >> 16) + lanes_below(m2))] = (uint16_t)t;
+                    if (cls == 3) blist2[old_hi + lanes_below(m3)] = (uint16_t)t;
+                }
+                PXR_TIMED_BARRIER(4);
+                PXR_PHASE_MARK(4);
+
+                // ---- phase 3 from the round's lists (lane teams as in the unbanded kernel)
+                const u64 bb = fu->band_bins[slot];
+                const uint32_t b_tiny = (uint32_t)bb & 0xFFFFu, b_small = (uint32_t)bb >> 16, b_large = (uint32_t)(bb >> 32);
+                for (uint32_t i = tid >> kSmallLanesLog2; i < b_small; i += NT >> kSmallLanesLog2) {
+                    const uint32_t ts = blist[kBandListEntries - 1 - i];
+                    raster_binned<false>(scb, ts, tri_table[ts], vxy, vd, keys, (int)(tid & (kTeam - 1u)), (int)kSmallLanesLog2,
+                                         (int)row_lo, (int)row_hi);
+                }
+                if (NT - 1 - tid < b_tiny) {
+                    const uint32_t tt = blist[NT - 1 - tid];
+                    raster_binned<false>(scb, tt, tri_table[tt], vxy, vd, keys, 0, 0, (int)row_lo, (int)row_hi);
+                }
+                for (uint32_t i = ((tid >> 6) + NT / 128) % (NT / 64); i < b_large; i += NT / 64)
+                    raster_binned<true>(scb, blist2[i], tri_table[blist2[i]], vxy, vd, keys, (int)lane, 6, (int)row_lo, (int)row_hi);
+                PXR_TIMED_BARRIER(5);
+                PXR_PHASE_MARK(5);
+                ++band_round;
+                base += NT;
+            } while (base < n_binned);
         }
-        // large: a whole wave per triangle, starting in the middle waves
-        for (uint32_t k = ((tid >> 6) + NT / 128) % (NT / 64); k < n_large; k += NT / 64)
-            raster_binned<true>(scb, list2[k], tri_table[list2[k]], vxy, vd, keys, (int)lane, 6, (int)row_lo, (int)row_hi);
-        PXR_TIMED_BARRIER(5);
-        PXR_PHASE_MARK(5);
 
         // ---- phase 4: resolve + shade + distractor + pack + store
         ResolveCtx rc;
@@ -1064,14 +1158,14 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
             // for a unit cell as well)
             if (scb.checker_short_form && eye_x == eye_x && eye_y == eye_y) {
                 if (no_roll)
-                    resolve_rows4<NT, true, true, VIDEO>(scb, rc, body, cxcy, rows, keys, out, out_ids, tid, p_begin, p_end);
+                    resolve_rows4<NT, true, true, VIDEO, BANDED>(scb, rc, body, cxcy, rows, keys, out, out_ids, tid, p_begin, p_end);
                 else
-                    resolve_rows4<NT, true, false, VIDEO>(scb, rc, body, cxcy, rows, keys, out, out_ids, tid, p_begin, p_end);
+                    resolve_rows4<NT, true, false, VIDEO, BANDED>(scb, rc, body, cxcy, rows, keys, out, out_ids, tid, p_begin, p_end);
             } else {
                 if (no_roll)
-                    resolve_rows4<NT, false, true, VIDEO>(scb, rc, body, cxcy, rows, keys, out, out_ids, tid, p_begin, p_end);
+                    resolve_rows4<NT, false, true, VIDEO, BANDED>(scb, rc, body, cxcy, rows, keys, out, out_ids, tid, p_begin, p_end);
                 else
-                    resolve_rows4<NT, false, false, VIDEO>(scb, rc, body, cxcy, rows, keys, out, out_ids, tid, p_begin, p_end);
+                    resolve_rows4<NT, false, false, VIDEO, BANDED>(scb, rc, body, cxcy, rows, keys, out, out_ids, tid, p_begin, p_end);
             }
         } else {
             // any image shape: one pixel per lane, byte stores
@@ -1096,6 +1190,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
                 out[(size_t)p * 3 + 1] = (uint8_t)((rgb >> 8) & 0xFFu);
                 out[(size_t)p * 3 + 2] = (uint8_t)(rgb >> 16);
                 if (out_ids) out_ids[p] = 0xFFFFFFFFu - low;
+                if (BANDED) keys[p - p_begin] = 0ull;  // cleared for the next band by the lane that read it
             }
         }
         row_lo += scb.band_rows;

@@ -485,6 +485,13 @@ int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
         o += align(c.T * 2, 4);
         c.lds_large = o;
         o += align(c.T * 2, 4);
+        c.lds_blist = c.lds_blist2 = 0;
+        if (n_bands >= kBandListsFrom) {  // a band round's lists
+            c.lds_blist = o;
+            o += kBandListEntries * 2;
+            c.lds_blist2 = o;
+            o += kBandListEntries * 2;
+        }
         c.lds_total = align(o, 16);
         // Video distractor: blended byte by (colour under the clip, clip byte), five tables of 256 bytes
         // (background r, g, b, the two greys).  Taken only where it costs no workgroup per compute unit.
