@@ -371,7 +371,7 @@ def main():
                                          ("cfg5_16384envs", 5, 16384, True, None),
                                          ("cfg5_128px", 5, 4096, True, 128), ("cfg5_256px", 5, 1024, True, 256),
                                          ("cfg5_512px", 5, 256, True, 512)]:
-            configs[name] = figures(time_workload(c, envs, 10, 2, dis, 0, size))
+            configs[name] = figures(time_workload(c, envs, 40, 5, dis, 0, size))  # (launches of 0.01-2.5 ms)
         configs["cfg3_distractor_on_over_off"] = configs["cfg3"]["frames_per_s"] / configs["cfg3_no_distractor"]["frames_per_s"]
         configs["cfg4_distractor_on_over_off"] = configs["cfg4"]["frames_per_s"] / configs["cfg4_no_distractor"]["frames_per_s"]
         configs.update(time_next_stages(torch, pxr, r["w"]))

@@ -14,9 +14,12 @@ SOURCES = ["api.cpp", "conv_api.cpp", "pipeline.cpp", "scene.cpp", "render.hip",
 # packed-fp32-ops is switched off for the device pass (see the platform notes).
 # The LDS counters are already bumped once per wavefront by hand (ballot + popcount, lane 0 adds); the
 # compiler's own wave-aggregation of uniform atomic adds would wrap that single-lane add a second time.
+# Machine-level loop-invariant code motion is off: it parks constants (zero vectors, literals) in vector registers
+# across the render kernel's band loop, which the 1024-thread variants (64 registers per lane) then spill; with it
+# off those variants need 61 registers and nothing else gets slower (measured on every workload).
 HIPFLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
             "-fno-fast-math", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-            "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
+            "-mllvm", "-amdgpu-atomic-optimizer-strategy=None", "-mllvm", "-disable-machine-licm",
             "-Wall", "-Wextra", "-Wno-unused-parameter", "-x", "hip"]
 
 

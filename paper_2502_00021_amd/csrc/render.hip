@@ -111,12 +111,13 @@ __device__ __forceinline__ long long emul<long long>(int a, int b) {
     return (long long)a * (long long)b;
 }
 
-// Walk rows j0 + r, j0 + r + 2^shift, ... of a triangle's candidate pixel range.
+// Walk rows j0 + r, j0 + r + 2^shift, ... of a triangle's candidate pixel range, and in each of them the columns
+// i0 + c, i0 + c + 2^cshift, ... (a team of 2^shift x 2^cshift lanes shares the triangle; c = cshift = 0: whole rows).
 // Edge functions carry their fill-rule bias and are stepped incrementally; a
 // pixel centre is covered when all three are >= 0.
 template <typename I>
 __device__ __forceinline__ void raster_rows(const TriSetup& s, uint32_t tri, uint32_t W, u64* keys, int r, int shift,
-                                            int row_lo) {
+                                            int row_lo, int c = 0, int cshift = 0) {
     int j = s.j0 + r;
     if (j > s.j1) return;
     const int dx_ab = s.bx - s.ax, dy_ab = s.by - s.ay;
@@ -125,16 +126,16 @@ __device__ __forceinline__ void raster_rows(const TriSetup& s, uint32_t tri, uin
     const I A2 = emul<I>(dx_ab, s.cy - s.ay) - emul<I>(dy_ab, s.cx - s.ax);
     const float invA = recip_in_range((float)A2);  // a front face: 1 <= A2 < 2^47
     const I b_ab = edge_bias(dx_ab, dy_ab), b_bc = edge_bias(dx_bc, dy_bc), b_ca = edge_bias(dx_ca, dy_ca);
-    const int px0 = (s.i0 << 8) + 128, py = (j << 8) + 128;
+    const int px0 = ((s.i0 + c) << 8) + 128, py = (j << 8) + 128;
     I f_ab = emul<I>(dx_ab, py - s.ay) - emul<I>(dy_ab, px0 - s.ax) + b_ab;
     I f_bc = emul<I>(dx_bc, py - s.by) - emul<I>(dy_bc, px0 - s.bx) + b_bc;
     I f_ca = emul<I>(dx_ca, py - s.cy) - emul<I>(dy_ca, px0 - s.cx) + b_ca;
-    const I sx_ab = (I)dy_ab << 8, sx_bc = (I)dy_bc << 8, sx_ca = (I)dy_ca << 8;
+    const I sx_ab = (I)dy_ab << (8 + cshift), sx_bc = (I)dy_bc << (8 + cshift), sx_ca = (I)dy_ca << (8 + cshift);
     const I sy_ab = (I)dx_ab << (8 + shift), sy_bc = (I)dx_bc << (8 + shift), sy_ca = (I)dx_ca << (8 + shift);
     for (;;) {
         I e_ab = f_ab, e_bc = f_bc, e_ca = f_ca;
-        uint32_t pix = (uint32_t)(j - row_lo) * W + (uint32_t)s.i0;  // the key buffer holds rows from row_lo on
-        for (int i = s.i0; i <= s.i1; ++i, ++pix) {
+        uint32_t pix = (uint32_t)(j - row_lo) * W + (uint32_t)(s.i0 + c);  // the key buffer holds rows from row_lo on
+        for (int i = s.i0 + c; i <= s.i1; i += 1 << cshift, pix += 1u << cshift) {
             if ((e_ab | e_bc | e_ca) >= 0) {
                 const float beta = (float)(e_ca - b_ca) * invA, gamma = (float)(e_ab - b_ab) * invA;
                 z_test(keys, pix, __builtin_fmaf(beta, s.dDb, __builtin_fmaf(gamma, s.dDc, s.Da)), tri);
@@ -149,6 +150,16 @@ __device__ __forceinline__ void raster_rows(const TriSetup& s, uint32_t tri, uin
         f_bc += sy_bc;
         f_ca += sy_ca;
     }
+}
+
+// How a whole wavefront shares a triangle of n rows: 2^shift lanes down the rows (as many as there are rows, up to
+// 64), the other 2^(6 - shift) across each row, so that a wide triangle of a few rows (every large triangle of a
+// frame that is rendered in bands of a few rows) keeps all lanes busy.
+__device__ __forceinline__ void wave_team(int n_rows, int lane, int& r, int& shift, int& c, int& cshift) {
+    shift = n_rows >= 33 ? 6 : (32 - __builtin_clz((uint32_t)max(n_rows, 1) * 2u - 1u)) - 1;  // ceil(log2(n_rows))
+    cshift = 6 - shift;
+    r = lane & ((1 << shift) - 1);
+    c = lane >> shift;
 }
 
 // Gather the snapped vertices of a triangle (ti = its entry of the index table) and its clamped pixel-centre range.
@@ -233,10 +244,12 @@ __device__ __forceinline__ void raster_piece(const SceneConsts& sc, uint32_t t, 
     s.Da = Da;
     s.dDb = Db - Da;
     s.dDc = Dc - Da;
+    int r, shift, c, cshift;
+    wave_team(s.j1 - s.j0 + 1, lane, r, shift, c, cshift);
     if (((maxx - minx) | (maxy - miny)) < 32768)
-        raster_rows<int>(s, t, sc.W, keys, lane, 6, row_lo);
+        raster_rows<int>(s, t, sc.W, keys, r, shift, row_lo, c, cshift);
     else
-        raster_rows<long long>(s, t, sc.W, keys, lane, 6, row_lo);
+        raster_rows<long long>(s, t, sc.W, keys, r, shift, row_lo, c, cshift);
 }
 
 // A triangle with corners on both sides of the near plane (every lane of the wavefront computes the
@@ -323,10 +336,12 @@ __device__ __forceinline__ void raster_binned(const SceneConsts& sc, uint32_t t,
     s.Da = vd[v0];
     s.dDb = vd[v2] - s.Da;
     s.dDc = vd[v1] - s.Da;
+    int c = 0, cshift = 0;
+    if (MAY_CLIP) wave_team(s.j1 - s.j0 + 1, r, r, shift, c, cshift);  // (the wave-per-triangle bin: r is the lane)
     if (small_extent)
-        raster_rows<int>(s, t, sc.W, keys, r, shift, row_lo);
+        raster_rows<int>(s, t, sc.W, keys, r, shift, row_lo, c, cshift);
     else
-        raster_rows<long long>(s, t, sc.W, keys, r, shift, row_lo);
+        raster_rows<long long>(s, t, sc.W, keys, r, shift, row_lo, c, cshift);
 }
 
 // Per-axis cell code of a snapped coordinate for an image of n pixels:
