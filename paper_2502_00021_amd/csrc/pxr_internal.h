@@ -58,6 +58,7 @@ struct SceneConsts {
     // sizes
     uint32_t W, H, npix, K, root, V, T, P;  // P = entries of the pair table (on the device: padded to a multiple of 64)
     uint32_t band_rows;                     // rows of the frame held by the LDS key buffer at a time
+    uint32_t first_band_rows;               // rows of the first band (<= band_rows); later bands have band_rows
     uint32_t magicW;  // ceil(2^32 / W): p / W == mulhi(p, magicW) for every pixel index p < 512 * W
     // device tables
     const float* vtmpl;       // [V][4]  ux,uy,uz, bits = (LDS byte address of the body's record)<<2 | s as a 2-bit signed number

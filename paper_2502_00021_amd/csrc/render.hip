@@ -1017,8 +1017,11 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         FrameUniforms* fu = reinterpret_cast<FrameUniforms*>(lds + scb.lds_misc);
         uint16_t* list = reinterpret_cast<uint16_t*>(lds + scb.lds_list);
         uint16_t* list2 = reinterpret_cast<uint16_t*>(lds + scb.lds_large);
-        const uint32_t row_hi = BANDED ? min(scb.H, row_lo + scb.band_rows) : scb.H;
+        const uint32_t row_hi = BANDED ? min(scb.H, row_lo + (row_lo ? scb.band_rows : scb.first_band_rows)) : scb.H;
         const uint32_t p_begin = row_lo * scb.W, p_end = row_hi * scb.W;
+        // keys to clear before the first band: all the buffer holds (a later band may be taller than the first, and
+        // every lane only leaves the keys it resolved cleared)
+        const uint32_t n_keys = BANDED ? scb.band_rows * scb.W : p_end - p_begin;
         if (!BANDED || scb.lds_blist == 0) {
             // Unbanded frames, and frames of a few bands (every band walks all bins: cheaper than picking a band's
             // triangles out while a triangle's rows are looked at by two or three bands only).
@@ -1039,7 +1042,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
             // codes and candidates are dead: clear the pixel keys they shared LDS with (0 = background at depth 0)
             // (two keys per store; the region is padded to 16 bytes, so an odd count may clear one key more)
             if (!BANDED || row_lo == 0) {
-                for (uint32_t p = tid; p < (p_end - p_begin + 1u) >> 1; p += NT)
+                for (uint32_t p = tid; p < (n_keys + 1u) >> 1; p += NT)
                     reinterpret_cast<uint4*>(keys)[p] = make_uint4(0u, 0u, 0u, 0u);
                 PXR_TIMED_BARRIER(4);
             }
@@ -1091,7 +1094,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
             const uint2* tri_table = reinterpret_cast<const uint2*>(scb.tri_idx);
             if (row_lo == 0) {
                 // the first band's keys share LDS with the cell codes and the candidate list, dead by now
-                for (uint32_t p = tid; p < (p_end - p_begin + 1u) >> 1; p += NT)
+                for (uint32_t p = tid; p < (n_keys + 1u) >> 1; p += NT)
                     reinterpret_cast<uint4*>(keys)[p] = make_uint4(0u, 0u, 0u, 0u);
             }
             uint32_t base = 0;
@@ -1208,7 +1211,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
                 if (BANDED) keys[p - p_begin] = 0ull;  // cleared for the next band by the lane that read it
             }
         }
-        row_lo += scb.band_rows;
+        row_lo = row_hi;
     } while (BANDED && row_lo < argument_reloaded<SceneConsts>(kSceneArgAt).H);
     PXR_PHASE_MARK(6);
     PXR_PHASE_END();
