@@ -151,9 +151,13 @@ def test_image_shapes_including_unpacked_store_path(torch, pxr, orc, W, H):
     assert_parity(gpu_render(torch, pxr, w, step0=2), oracle_render(orc, w, step0=2))
 
 
-@pytest.mark.parametrize("cfg,W,H,B", [(5, 256, 256, 3), (4, 200, 312, 2), (3, 512, 512, 2), (2, 500, 36, 3), (5, 132, 130, 3)])
+@pytest.mark.parametrize("cfg,W,H,B", [(5, 256, 256, 3), (4, 200, 312, 2), (3, 512, 512, 2), (2, 500, 36, 3), (5, 132, 130, 3),
+                                       (3, 250, 300, 2), (4, 86, 90, 3), (5, 96, 96, 4), (5, 192, 160, 2), (4, 84, 100, 3)])
 def test_frames_larger_than_one_key_buffer(torch, pxr, orc, cfg, W, H, B):
-    """Up to 512x512: the pixel keys are held a band of rows at a time (dozens of bands at the top end)."""
+    """Up to 512x512: the pixel keys are held a band of rows at a time.  Two or three bands of half a compute unit's
+    LDS (a first band of whole resolve trips where there are two), or, from six bands on, all of the LDS and bands
+    that pick their own triangles; widths that are no multiple of 4 take the byte-store loop, which clears its keys
+    behind itself as well."""
     w = wl.make(cfg, B=B)
     w["desc"]["width"], w["desc"]["height"] = W, H
     if w["distractor"] is not None and w["distractor"]["mode"] == "video":
