@@ -956,18 +956,30 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     // ---- phase 2b: exact binning, one lane per candidate triangle: reject, area sign, pixel range,
     // then one of three bins by the number of candidate pixel centres (one packed LDS atomic per wave).
     const uint32_t n_cand = fu->n_cand;
-    // (A lane's candidate and its entry of the index table are requested a trip ahead, without a branch: a lane past
-    // the end reads a list entry that nobody wrote and clamps it into the table.)
-    uint32_t t_ahead = cand[min(tid, sc.T - 1u)];
-    uint2 ti_ahead = reinterpret_cast<const uint2*>(sc.tri_idx)[min(t_ahead, sc.T - 1u)];
+    // (Where the candidates take several trips - smaller workgroups, taller frames - a lane's candidate and its entry
+    // of the index table are requested a trip ahead, without a branch: a lane past the end reads a list entry that
+    // nobody wrote and clamps it into the table.  The 1024-thread unbanded kernel sees its ~900 candidates in one trip
+    // and is bound by instruction issue: it keeps the plain form.)
+    constexpr bool kAhead = NT < 1024 || BANDED;
+    uint32_t t_ahead = 0;
+    uint2 ti_ahead = make_uint2(0u, 0u);
+    if (kAhead) {
+        t_ahead = cand[min(tid, sc.T - 1u)];
+        ti_ahead = reinterpret_cast<const uint2*>(sc.tri_idx)[min(t_ahead, sc.T - 1u)];
+    }
     for (uint32_t k0 = 0; k0 < n_cand; k0 += NT) {
         const uint32_t k = k0 + tid;
         int cls = 0;  // 0 none, 1 tiny, 2 small, 3 large
-        const uint32_t t = t_ahead;
-        const uint2 ti = ti_ahead;
-        if (k0 + NT < n_cand) {
-            t_ahead = cand[min(k + NT, sc.T - 1u)];
-            ti_ahead = reinterpret_cast<const uint2*>(sc.tri_idx)[min(t_ahead, sc.T - 1u)];
+        uint32_t t = t_ahead;
+        uint2 ti = ti_ahead;
+        if (kAhead) {
+            if (k0 + NT < n_cand) {
+                t_ahead = cand[min(k + NT, sc.T - 1u)];
+                ti_ahead = reinterpret_cast<const uint2*>(sc.tri_idx)[min(t_ahead, sc.T - 1u)];
+            }
+        } else if (k < n_cand) {
+            t = cand[k];
+            ti = reinterpret_cast<const uint2*>(sc.tri_idx)[t];
         }
         if (k < n_cand) {
             TriSetup s;
