@@ -929,9 +929,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     // code 0 (never a candidate), so no lane needs a bounds test, and a wavefront past the end leaves.  "Both halves
     // non-zero" is one 16 x 16-bit product; the ballots are taken from single comparisons (their masks as they
     // are) and combined as scalars.
-    for (uint32_t p0 = wave_first; p0 < sc.P; p0 += NT) {
-        const uint4 rec = rec_next;
-        if (p0 + NT < sc.P) rec_next = reinterpret_cast<const uint4*>(sc.pair_tbl)[p0 + NT + lane];
+    // (Two trips per turn of the loop, the two entries in flight changing roles: a single "next" variable costs six
+    // register moves per trip.)
+    const auto coarse_trip = [&](const uint4 rec) {
         const uint32_t w0 = rec.x, w1 = rec.y, w2 = rec.z;
         const uint32_t m0 = lds_u32_at(w0 & 0xFFFFu), m1 = lds_u32_at(w0 >> 16), m2 = lds_u32_at(w1 & 0xFFFFu), m3 = lds_u32_at(w1 >> 16);
         const uint32_t odd = m0 & 0x00010001u, x02 = m0 ^ m2;
@@ -948,6 +948,17 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
             // (the first triangles of the wavefront's entries, then the second ones: the order is free)
             if (keep_a) cand[base + lanes_below(ma)] = (uint16_t)ta;
             if (keep_b) cand[base + (uint32_t)__popcll(ma) + lanes_below(mb)] = (uint16_t)tb;
+        }
+    };
+    {
+        const uint4* table = reinterpret_cast<const uint4*>(sc.pair_tbl);
+        uint4 rec_a = rec_next, rec_b = make_uint4(0u, 0u, 0u, 0u);
+        for (uint32_t p0 = wave_first; p0 < sc.P; p0 += 2 * NT) {
+            if (p0 + NT < sc.P) rec_b = table[p0 + NT + lane];
+            coarse_trip(rec_a);
+            if (p0 + NT >= sc.P) break;
+            if (p0 + 2 * NT < sc.P) rec_a = table[p0 + 2 * NT + lane];
+            coarse_trip(rec_b);
         }
     }
     PXR_TIMED_BARRIER(2);
