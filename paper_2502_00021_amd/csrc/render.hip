@@ -1185,7 +1185,11 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
         rc.eye_y = eye_y;
         rc.eye_z = eye_z;
         const bool no_roll = scb.Rt[2] == 0.0f;
-        rc.inv_ez = (PX == 4 && no_roll) ? 0.0f : 1.0f / eye_z;  // (the row table already holds the ground test)
+        rc.inv_ez = 0.0f;
+        if (!(PX == 4 && no_roll)) {  // (without roll the row table already holds the ground test)
+            asm volatile("" ::: "memory");  // (a branch, not a select: the compiler would do the division either way)
+            rc.inv_ez = 1.0f / eye_z;
+        }
         rc.ground_ok = scb.ground_on && eye_z > 0.0f;
         rc.mode = dcb.mode;
         rc.alpha = dcb.alpha;
