@@ -44,11 +44,11 @@ HBM_PEAK_GBS = 8000.0
 # factors a plain 1 GiB copy gives for the same counters), and the counter-side view of the vector units
 # (share of issue slots busy, share of lanes active per instruction, wave-instructions per frame).
 PROFILED = {
-    ("cfg5", 65536): {"traffic_bytes_per_launch": 2516.8e6, "valu_busy": 0.924, "lane_use": 0.830,
-                      "valu_wave_instructions_per_frame": 10125,
+    ("cfg5", 65536): {"traffic_bytes_per_launch": 2516.8e6, "valu_busy": 0.908, "lane_use": 0.825,
+                      "valu_wave_instructions_per_frame": 9933,
                       "source": "profiles/render_kernel_cfg5_humanoid_box_64x64.md"},
-    ("cfg4", 16384): {"traffic_bytes_per_launch": 403.5e6, "valu_busy": 0.810, "lane_use": 0.831,
-                      "valu_wave_instructions_per_frame": 15094,
+    ("cfg4", 16384): {"traffic_bytes_per_launch": 403.5e6, "valu_busy": 0.798, "lane_use": 0.827,
+                      "valu_wave_instructions_per_frame": 14878,
                       "source": "profiles/render_kernel_cfg4_humanoid_84x84_video.md"},
 }
 
