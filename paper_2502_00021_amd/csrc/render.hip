@@ -677,7 +677,6 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     const SceneConsts sc, const DistractConsts dc, const float* __restrict__ poses, const float* __restrict__ shapes,
     uint32_t S, uint32_t step0, uint32_t env0, uint8_t* __restrict__ frames, uint32_t* __restrict__ ids) {
     extern __shared__ __align__(16) unsigned char lds[];
-    u64* keys = reinterpret_cast<u64*>(lds + sc.lds_keys);
     // the key buffer's LDS holds the cell codes and the candidate list until the keys are cleared
     uint32_t* vm = reinterpret_cast<uint32_t*>(lds + sc.lds_keys);
     uint16_t* cand = reinterpret_cast<uint16_t*>(lds + sc.lds_keys + sc.V * 4 + 4);  // (after the word of code 0)

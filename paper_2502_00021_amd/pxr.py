@@ -83,6 +83,10 @@ def lib():
         path = _lib_path
         if not os.path.exists(path):
             raise ImportError(f"{path} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` first")
+        try:  # PyTorch's HIP runtime first: a process that loads this library before it finds no device afterwards
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = C.CDLL(path)
         vp, u32 = C.c_void_p, C.c_uint32
         L.pxr_create_scene.argtypes = [C.POINTER(SceneDesc), C.POINTER(vp)]
