@@ -26,6 +26,7 @@ namespace {
 
 constexpr uint32_t kFkLanes = 64;            // frames per workgroup (one wavefront)
 constexpr uint32_t kFkStride = kFkLanes + 1; // LDS row stride in floats
+constexpr uint32_t kFkBatch = 16;            // memory requests a lane has in flight per array in the copy stages
 
 constexpr float kMaxHingeAngle = 65536.0f;  // radians; the reduction below is accurate up to here
 
@@ -74,21 +75,44 @@ __global__ __launch_bounds__(kFkLanes) void fk_kernel(const SkeletonConsts sk, c
     const uint32_t f0 = blockIdx.x * kFkLanes;                // first frame of this workgroup
     const uint32_t nf = min(kFkLanes, n_frames - f0);         // frames it holds (ragged tail)
 
-    // coalesced loads of the workgroup's contiguous input chunks, transposed into LDS
-    // (index / row length by multiplication: indices stay below 64 * row length, far inside the exact range)
+    // Coalesced loads of the workgroup's contiguous input chunks, transposed into LDS.  A batch of requests goes out
+    // before the first answer is used: one request per trip, each waited for, made this stage a chain of two dozen
+    // memory round trips, which was most of the kernel's time.  (Lanes past the end of a chunk ask for its last
+    // element again and drop the answer; index / row length by multiplication: indices stay below 64 * row length,
+    // far inside the exact range.)
     {
-        const float* src = angles + (size_t)f0 * sk.J;
+        const uint32_t row_f = sk.F * 7;
+        const uint32_t n_a = nf * sk.J, n_f = nf * row_f;
+        const float* src_a = angles + (size_t)f0 * sk.J;
+        const float* src_f = free_poses + (size_t)f0 * row_f;
         const uint32_t magic_j = sk.J > 1u ? 0xFFFFFFFFu / sk.J + 1u : 0u;  // (ceil(2^32 / J); J == 1 needs none)
-        for (uint32_t i = lane; i < nf * sk.J; i += kFkLanes) {
-            const uint32_t n = sk.J > 1u ? __umulhi(i, magic_j) : i, j = i - n * sk.J;
-            ang[j * kFkStride + n] = src[i];
-        }
-        const uint32_t row = sk.F * 7;
-        const uint32_t magic_f = row ? 0xFFFFFFFFu / row + 1u : 0u;  // (rows are multiples of 7)
-        src = free_poses + (size_t)f0 * row;
-        for (uint32_t i = lane; i < nf * row; i += kFkLanes) {
-            const uint32_t n = __umulhi(i, magic_f), j = i - n * row;
-            fre[j * kFkStride + n] = src[i];
+        const uint32_t magic_f = row_f ? 0xFFFFFFFFu / row_f + 1u : 0u;     // (rows are multiples of 7)
+        for (uint32_t base = 0; base < max(n_a, n_f); base += kFkLanes * kFkBatch) {
+            float ta[kFkBatch], tf[kFkBatch];
+            if (base < n_a) {
+#pragma unroll
+                for (uint32_t u = 0; u < kFkBatch; ++u) ta[u] = src_a[min(base + u * kFkLanes + lane, n_a - 1u)];
+            }
+            if (base < n_f) {
+#pragma unroll
+                for (uint32_t u = 0; u < kFkBatch; ++u) tf[u] = src_f[min(base + u * kFkLanes + lane, n_f - 1u)];
+            }
+            if (base < n_a) {
+#pragma unroll
+                for (uint32_t u = 0; u < kFkBatch; ++u) {
+                    const uint32_t i = base + u * kFkLanes + lane;
+                    const uint32_t n = sk.J > 1u ? __umulhi(i, magic_j) : i, j = i - n * sk.J;
+                    if (i < n_a) ang[j * kFkStride + n] = ta[u];
+                }
+            }
+            if (base < n_f) {
+#pragma unroll
+                for (uint32_t u = 0; u < kFkBatch; ++u) {
+                    const uint32_t i = base + u * kFkLanes + lane;
+                    const uint32_t n = __umulhi(i, magic_f), j = i - n * row_f;
+                    if (i < n_f) fre[j * kFkStride + n] = tf[u];
+                }
+            }
         }
     }
     __syncthreads();
@@ -130,14 +154,24 @@ __global__ __launch_bounds__(kFkLanes) void fk_kernel(const SkeletonConsts sk, c
     }
     __syncthreads();
 
-    // coalesced store of the workgroup's contiguous output chunk
+    // coalesced store of the workgroup's contiguous output chunk (a batch of LDS reads, then the batch's stores)
     {
-        const uint32_t row = sk.K * 7;
+        const uint32_t row = sk.K * 7, n_o = nf * row;
         const uint32_t magic = 0xFFFFFFFFu / row + 1u;
         float* dst = poses + (size_t)f0 * row;
-        for (uint32_t i = lane; i < nf * row; i += kFkLanes) {
-            const uint32_t n = __umulhi(i, magic), j = i - n * row;
-            dst[i] = pose[j * kFkStride + n];
+        for (uint32_t base = 0; base < n_o; base += kFkLanes * kFkBatch) {
+            float t[kFkBatch];
+#pragma unroll
+            for (uint32_t u = 0; u < kFkBatch; ++u) {
+                const uint32_t i = min(base + u * kFkLanes + lane, n_o - 1u);
+                const uint32_t n = __umulhi(i, magic), j = i - n * row;
+                t[u] = pose[j * kFkStride + n];
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < kFkBatch; ++u) {
+                const uint32_t i = base + u * kFkLanes + lane;
+                if (i < n_o) dst[i] = t[u];
+            }
         }
     }
 }
