@@ -80,7 +80,7 @@ struct SceneConsts {
 
 // Video distractor: for each of the five colours that can lie under the clip (background r, g, b; the two ground
 // greys) the blended, quantised byte for every clip byte: [5][256] bytes, rebuilt per frame in LDS.
-constexpr uint32_t kVideoTableBytes = 5 * 256;
+constexpr uint32_t kVideoTableBytes = 9 * 256;  // background r, g, b; first grey x 3; second grey x 3
 
 // Distractor state bound by pxr_apply_distractor.
 struct DistractConsts {

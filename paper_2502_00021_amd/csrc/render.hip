@@ -555,7 +555,9 @@ __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const Resol
         // the lane's four keys are 32 contiguous, aligned bytes: two 16-byte LDS reads
         const uint4 k01 = reinterpret_cast<const uint4*>(keys + (p0 - p_begin))[0], k23 = reinterpret_cast<const uint4*>(keys + (p0 - p_begin))[1];
         const u64 key4[4] = {((u64)k01.y << 32) | k01.x, ((u64)k01.w << 32) | k01.z, ((u64)k23.y << 32) | k23.x, ((u64)k23.w << 32) | k23.z};
-        uint32_t rgb[4], low[4];
+        uint32_t rgb[4] = {0u, 0u, 0u, 0u}, low[4];
+        uint32_t ow[3] = {0u, 0u, 0u};  // the 12 bytes that leave
+        bool direct = false;            // they were put together as they were looked up (rgb[] is not used)
         u64 tri_lanes[4];
         if (!VIDEO) {
             // One of the frame's three colours (background, two greys: consecutive words in LDS), without a branch
@@ -591,31 +593,34 @@ __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const Resol
             // Video distractor, no roll, tables in LDS: a row is sky or ground as a whole, so under the clip lies
             // the background or one of the two greys by the checker's parity, and the blended byte of a channel
             // is one byte read from the table of that colour, indexed by the clip's byte where it lies in the three
-            // words that brought it (byte n = channel n % 3 of pixel n / 3).  A triangle pixel gets a blended colour
-            // as well, replaced below.
-            {
-                const bool ground_row = tg_row != 0.0f;
-                uint32_t tab[3];
+            // words that brought it (byte n = channel n % 3 of pixel n / 3), and put at the same place of the three
+            // words that leave.  A triangle pixel gets a blended colour as well, replaced below.
+            direct = true;
+            const bool ground_row = tg_row != 0.0f;
+            const uint32_t lane_base = rc.vlut + (ground_row ? 768u : 0u);  // background's tables, or the first grey's
+            const uint32_t odd_step = ground_row ? 768u : 0u;               // the second grey's follow the first's
+            uint32_t base[4];
 #pragma unroll
-                for (int ch = 0; ch < 3; ++ch) tab[ch] = rc.vlut + (ground_row ? 768u : 256u * ch);
-                const uint32_t odd_step = ground_row ? 256u : 0u;  // the second grey's table follows the first's
+            for (int k = 0; k < 4; ++k) {
+                const u64 key = key4[k] > gkey_row ? key4[k] : gkey_row;
+                low[k] = (uint32_t)key;
+                tri_lanes[k] = __ballot(low[k] > 1u);
+                const float dwx = __builtin_fmaf(sc.Rt[0], cxs[k], rx);
+                const float dwy = __builtin_fmaf(sc.Rt[1], cxs[k], ry);
+                uint32_t odd = checker_cells<UNIT_CELL>(sc, rc, tg_row, dwx, dwy) & 1u;
+                asm("" : "+v"(odd));  // (kept from the compiler, which would turn the multiply-add into compare, select, add)
+                base[k] = __umul24(odd, odd_step) + lane_base;
+            }
 #pragma unroll
-                for (int k = 0; k < 4; ++k) {
-                    const u64 key = key4[k] > gkey_row ? key4[k] : gkey_row;
-                    low[k] = (uint32_t)key;
-                    tri_lanes[k] = __ballot(low[k] > 1u);
-                    const float dwx = __builtin_fmaf(sc.Rt[0], cxs[k], rx);
-                    const float dwy = __builtin_fmaf(sc.Rt[1], cxs[k], ry);
-                    const uint32_t off = (checker_cells<UNIT_CELL>(sc, rc, tg_row, dwx, dwy) << 8) & odd_step;
-                    uint32_t packed = 0;
+            for (int w = 0; w < 3; ++w) {
+                uint32_t word = 0;
 #pragma unroll
-                    for (int ch = 0; ch < 3; ++ch) {
-                        const int n = 3 * k + ch;
-                        const uint32_t at = tab[ch] + off + ((vid[n / 4] >> (8 * (n % 4))) & 0xFFu);
-                        packed |= (uint32_t)*reinterpret_cast<const __attribute__((address_space(3))) uint8_t*>(static_cast<uintptr_t>(at)) << (8 * ch);
-                    }
-                    rgb[k] = packed;
+                for (int b = 0; b < 4; ++b) {
+                    const int n = 4 * w + b;
+                    const uint32_t at = base[n / 3] + ((vid[w] >> (8 * b)) & 0xFFu) + 256u * (n % 3);
+                    word |= (uint32_t)*reinterpret_cast<const __attribute__((address_space(3))) uint8_t*>(static_cast<uintptr_t>(at)) << (8 * b);
                 }
+                ow[w] = word;
             }
         } else {
 #pragma unroll
@@ -652,17 +657,34 @@ __device__ __forceinline__ void resolve_rows4(const SceneConsts& sc, const Resol
 #pragma unroll
             for (int k = 0; k < 4; ++k)
                 if (low[k] > 1u) rgb[k] = list[slot[k]];
+            if (VIDEO && direct) {
+                // (pixel k's three bytes start at byte 3 k of the twelve)
+                if (low[0] > 1u) ow[0] = (ow[0] & 0xFF000000u) | rgb[0];
+                if (low[1] > 1u) {
+                    ow[0] = (ow[0] & 0x00FFFFFFu) | (rgb[1] << 24);
+                    ow[1] = (ow[1] & 0xFFFF0000u) | (rgb[1] >> 8);
+                }
+                if (low[2] > 1u) {
+                    ow[1] = (ow[1] & 0x0000FFFFu) | (rgb[2] << 16);
+                    ow[2] = (ow[2] & 0xFFFFFF00u) | (rgb[2] >> 16);
+                }
+                if (low[3] > 1u) ow[2] = (ow[2] & 0x000000FFu) | (rgb[3] << 8);
+            }
         }
         if (SELF_CLEAR) {
             // banded frames: the lane leaves its four keys cleared for the next band (nobody else touches them)
             reinterpret_cast<uint4*>(keys + (p0 - p_begin))[0] = make_uint4(0u, 0u, 0u, 0u);
             reinterpret_cast<uint4*>(keys + (p0 - p_begin))[1] = make_uint4(0u, 0u, 0u, 0u);
         }
+        if (!(VIDEO && direct)) {
+            ow[0] = rgb[0] | (rgb[1] << 24);
+            ow[1] = (rgb[1] >> 8) | (rgb[2] << 16);
+            ow[2] = (rgb[2] >> 16) | (rgb[3] << 8);
+        }
         struct alignas(4) U3 {
             uint32_t a, b, c;
         };
-        *reinterpret_cast<U3*>(reinterpret_cast<uint32_t*>(out) + q * 3) =
-            U3{rgb[0] | (rgb[1] << 24), (rgb[1] >> 8) | (rgb[2] << 16), (rgb[2] >> 16) | (rgb[3] << 8)};
+        *reinterpret_cast<U3*>(reinterpret_cast<uint32_t*>(out) + q * 3) = U3{ow[0], ow[1], ow[2]};
         if (out_ids)
             reinterpret_cast<uint4*>(out_ids)[q] =
                 make_uint4(0xFFFFFFFFu - low[0], 0xFFFFFFFFu - low[1], 0xFFFFFFFFu - low[2], 0xFFFFFFFFu - low[3]);
@@ -832,17 +854,24 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(NT >= 1024 ?
     if (VIDEO && sc.lds_vlut) {
         // Video-blend tables: under the clip lies the background or a ground grey (no colour distractor in this
         // mode), so a blended channel is a function of (one of five colours, clip byte).  Four entries per lane.
+        // Nine tables of 256 bytes: background r, g, b, then each grey's three times over - the channel of a byte is
+        // then the same address offset (256 x channel) whatever lies under the clip, a constant in the read.
         uint32_t* vlut = reinterpret_cast<uint32_t*>(lds + sc.lds_vlut);
-        for (uint32_t i = tid; i < kVideoTableBytes / 4; i += NT) {
-            const uint32_t t = i >> 6;
+        for (uint32_t i = tid; i < 5u * 64u; i += NT) {
+            const uint32_t t = i >> 6, at = i & 63u;
             const float c = t == 0 ? sc.bg[0] : t == 1 ? sc.bg[1] : t == 2 ? sc.bg[2] : t == 3 ? sc.gs[0] : sc.gs[1];
             uint32_t word = 0;
 #pragma unroll
             for (uint32_t e = 0; e < 4; ++e) {
-                const float vf = (float)((i & 63u) * 4u + e) * (1.0f / 255.0f);
+                const float vf = (float)(at * 4u + e) * (1.0f / 255.0f);
                 word |= quantise(__builtin_fmaf(dc.alpha, vf - c, c)) << (8 * e);
             }
-            vlut[i] = word;
+            if (t < 3u) {
+                vlut[i] = word;
+            } else {
+                uint32_t* g = vlut + (t == 3u ? 3u * 64u : 6u * 64u) + at;
+                g[0] = g[64] = g[128] = word;
+            }
         }
     }
     if (tid <= kDrawLane && tid >= kDrawLane - 2u) {

@@ -504,8 +504,9 @@ int build_host_scene(const pxr_scene_desc& d, HostScene& hs, std::string& err) {
             o += kBandListEntries * 2;
         }
         c.lds_total = align(o, 16);
-        // Video distractor: blended byte by (colour under the clip, clip byte), five tables of 256 bytes
-        // (background r, g, b, the two greys).  Taken only where it costs no workgroup per compute unit.
+        // Video distractor: blended byte by (colour under the clip, clip byte), nine tables of 256 bytes
+        // (background r, g, b, and each of the two greys three times, so that "channel" is the same address offset
+        // whatever lies under the clip).  Taken only where it costs no workgroup per compute unit.
         c.lds_vlut = 0;
         const uint32_t with_tables = c.lds_total + kVideoTableBytes;
         if (with_tables <= 160u * 1024u && (160u * 1024u) / with_tables == (160u * 1024u) / c.lds_total) {
