@@ -47,8 +47,8 @@ PROFILED = {
     ("cfg5", 65536): {"traffic_bytes_per_launch": 2516.8e6, "valu_busy": 0.908, "lane_use": 0.825,
                       "valu_wave_instructions_per_frame": 9933,
                       "source": "profiles/render_kernel_cfg5_humanoid_box_64x64.md"},
-    ("cfg4", 16384): {"traffic_bytes_per_launch": 403.5e6, "valu_busy": 0.798, "lane_use": 0.827,
-                      "valu_wave_instructions_per_frame": 14878,
+    ("cfg4", 16384): {"traffic_bytes_per_launch": 403.5e6, "valu_busy": 0.795, "lane_use": 0.823,
+                      "valu_wave_instructions_per_frame": 14651,
                       "source": "profiles/render_kernel_cfg4_humanoid_84x84_video.md"},
 }
 
