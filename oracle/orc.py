@@ -185,6 +185,9 @@ class Scene:
 def _make_distractor(d, B):
     if d is None or d.get("mode", "none") == "none":
         return None, None
+    for key in d:
+        if key not in ("mode", "seed", "scale", "offset", "video", "alpha", "env_offset", "env_video"):
+            raise KeyError(f"distractor description has no field {key!r}")
     s = _Distractor()
     s.mode = MODES[d["mode"]]
     s.seed = int(d.get("seed", 0))

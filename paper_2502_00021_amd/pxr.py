@@ -237,6 +237,9 @@ class Scene:
         if d is None or d.get("mode", "none") == "none":
             _check(lib().pxr_apply_distractor(self._h, None))
             return
+        unknown = set(d) - {"mode", "seed", "scale", "offset", "video", "alpha", "env_offset", "env_video"}
+        if unknown:  # (a misspelt key would silently leave its default in place)
+            raise ValueError(f"unknown distractor keys: {sorted(unknown)}")
         s = DistractorDesc()
         s.mode = MODES[d["mode"]]
         s.seed = int(d.get("seed", 0))

@@ -520,7 +520,9 @@ def random_scene(seed, B=4):
     mode = int(rng.integers(0, 3))
     dis = None
     if mode == 1:
-        dis = dict(mode="color", seed=int(rng.integers(0, 2**62)), scale_lo=0.5, scale_hi=1.5, offset_lo=-0.2, offset_hi=0.2)
+        lo, span = float(rng.uniform(0.3, 1.0)), float(rng.uniform(0.0, 1.0))
+        olo, ospan = float(rng.uniform(-0.4, 0.1)), float(rng.uniform(0.0, 0.5))
+        dis = dict(mode="color", seed=int(rng.integers(0, 2**62)), scale=(lo, lo + span), offset=(olo, olo + ospan))
     elif mode == 2:
         n = int(rng.integers(1, 6))
         dis = dict(mode="video", seed=int(rng.integers(0, 2**62)), alpha=float(rng.choice([0.5, 0.25, 1.0])),

@@ -130,6 +130,26 @@ def test_colour_identity_and_per_step_change(orc, small):
     assert not np.array_equal(a["frames"], s.render(small["poses"], distractor=dict(d, seed=4), step0=10)["frames"])
 
 
+def test_misspelt_distractor_fields_are_rejected(orc, small):
+    """A key that neither wrapper knows would silently leave its default (no jitter) in place on both sides."""
+    import pytest
+    from paper_2502_00021_amd import pxr, workloads as wl
+    s = orc.Scene(small["desc"])
+    with pytest.raises(KeyError):
+        s.render(small["poses"], distractor=dict(mode="color", seed=3, scale_lo=0.5, scale_hi=1.5))
+    sc = pxr.Scene.__new__(pxr.Scene)  # (no device here: the keys are checked before the library is called)
+    with pytest.raises(ValueError):
+        pxr.Scene.apply_distractor(sc, dict(mode="color", seed=3, scale_lo=0.5))
+    # the fuzz generator's colour scenes really jitter
+    seen = 0
+    for seed in range(40):
+        d = wl.random_scene(seed)["distractor"]
+        if d and d["mode"] == "color":
+            assert d["scale"][1] >= d["scale"][0] > 0.0 and d["offset"][1] >= d["offset"][0]
+            seen += 1
+    assert seen >= 5
+
+
 def test_colour_distractor_values_from_the_generator(orc, small):
     """Background pixels carry exactly clamp(bg*scale+offset) with scale/offset drawn from streams 0 and 1."""
     s = orc.Scene(small["desc"])
