@@ -164,6 +164,49 @@ def test_sixty_four_link_chain(torch, pxr, orc):
     sc.close()
 
 
+def _random_tree(seed):
+    """A seeded random forest over K bodies: several free roots, hinged and welded children in any shape (stars,
+    chains, bushes), angle slots in shuffled order, frame counts around the 64-frame workgroups."""
+    rng = np.random.default_rng(4400 + seed)
+    K = int(rng.integers(1, 65))
+    skel = wl._skeleton(K)
+    n_free = n_ang = 0
+    depth = np.zeros(K, int)
+    for k in range(K):
+        if k == 0 or rng.random() < 0.08:
+            skel["slot"][k] = n_free
+            n_free += 1
+            continue
+        shallow = [j for j in range(k) if depth[j] < 12] or [0]  # (keeps the error bound of deep chains meaningful)
+        par = int(rng.choice(shallow)) if rng.random() < 0.7 else int(shallow[-1])
+        depth[k] = depth[par] + 1
+        welded = rng.random() < 0.15
+        wl._hinge(skel, k, parent=par, slot=-1 if welded else n_ang, anchor=rng.uniform(-0.3, 0.3, 3),
+                  axis=wl.q_normalize(rng.standard_normal(3)), offset=rng.uniform(-0.3, 0.3, 3))
+        n_ang += 0 if welded else 1
+    hinged = np.flatnonzero((skel["parent"] >= 0) & (skel["slot"] >= 0))
+    skel["slot"][hinged] = rng.permutation(n_ang)           # angles in any order
+    roots = np.flatnonzero(skel["parent"] < 0)
+    skel["slot"][roots] = rng.permutation(n_free)
+    N = int(rng.choice([1, 63, 64, 65, 130, 200]))
+    free = np.zeros((N, n_free, 7), np.float32)
+    free[..., :3] = rng.uniform(-2.0, 2.0, (N, n_free, 3))
+    free[..., 3:] = wl.random_quats(rng, (N, n_free))
+    ang = rng.uniform(-3.2, 3.2, (N, n_ang)).astype(np.float32)
+    return K, skel, n_free, n_ang, free, ang
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_trees(torch, pxr, orc, seed):
+    K, skel, n_free, n_ang, free, ang = _random_tree(seed)
+    bodies = [wl.sphere(0.05, (0.5, 0.5, 0.5), 3, 1) for _ in range(K)]
+    sc = pxr.Scene(wl.default_scene(16, 16, bodies))
+    sc.set_skeleton(skel, n_free, n_ang)
+    got = sc.pose_batch(torch.from_numpy(free).cuda(), torch.from_numpy(ang).cuda() if n_ang else None).cpu().numpy()
+    assert_poses_close(got, orc.fk(skel, free, ang), skel)
+    sc.close()
+
+
 @pytest.mark.parametrize("cfg,B", [(2, 40), (3, 24), (4, 20), (5, 16)])
 def test_angles_to_frames_match_oracle(torch, pxr, orc, cfg, B):
     from test_gpu_parity import _bind, assert_parity
