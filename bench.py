@@ -8,7 +8,9 @@ environments), inputs already resident in HBM.  Prints ONE JSON line:
   configs             the other configurations at their full sizes (frames/s, launch time, ALU and HBM fractions),
                       the target point "64x64 at 16 384 environments", the distractor-on / distractor-off ratios,
                       larger frames, and the stages around the renderer (kinematics, conv consumer, the overlapped
-                      render + conv pipeline); the same figures, flat, under config["others.*"]
+                      render + conv pipeline); the two launch-bound configurations also by wall clock over launches
+                      made back to back and over the same launches replayed from a HIP graph; the same figures,
+                      flat, under config["others.*"]
   measured_peaks      what this GPU sustains right now (dependent-free FMA loop, integer mad loop, copy / read /
                       write streams), and the headline fractions against those
   cpu_baseline        the CPU oracle on the host cores, on a bounded sample of the headline workload
@@ -254,7 +256,7 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n, "launches": 3}))
         return
 
-    def time_workload(cfg, envs, steps, warmup, distract=True, threads=0, size=None):
+    def time_workload(cfg, envs, steps, warmup, distract=True, threads=0, size=None, graph_launches=0):
         w = workloads.make(cfg, B=envs)
         if size:
             w["desc"]["width"] = w["desc"]["height"] = size
@@ -294,6 +296,33 @@ def main():
         info = scene.info()
         res = dict(w=w, B=B, S=S, K=K, H=scene.H, W=scene.W, mode=mode, wall=wall, kernel_ms=kernel_ms, info=info,
                    checksum=int(frames[:: max(1, B // 64)].to(torch.int64).sum().item()))
+        if graph_launches:
+            # Launch-bound batches: the same launches recorded once in a HIP graph (the entry point only enqueues) and
+            # replayed, against the same number made one by one; wall clock around both, nothing between the launches.
+            side = torch.cuda.Stream()  # (default priority; capture needs a stream of its own)
+
+            def launches():
+                for i in range(graph_launches):
+                    scene.render_batch(poses, shapes, step0=i, frames=frames)
+            with torch.cuda.stream(side):
+                launches()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(10):
+                    launches()
+                torch.cuda.synchronize()
+                res["eager_s_per_launch"] = (time.perf_counter() - t0) / (10 * graph_launches)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                launches()
+            graph.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(10):
+                graph.replay()
+            torch.cuda.synchronize()
+            res["graph_s_per_launch"] = (time.perf_counter() - t0) / (10 * graph_launches)
+            del graph
         if args.phase_clocks:
             names = ["0 setup", "1 vertices", "2a coarse", "2b exact", "key clear", "3 raster", "4 resolve"]
             out = (ctypes.c_ulonglong * 16)()
@@ -315,10 +344,14 @@ def main():
         V, T, npix = r["info"]["n_verts"], r["info"]["n_tris"], r["H"] * r["W"]
         ops = algorithmic_ops_per_frame(V, T, npix, r["mode"])
         byts = algorithmic_bytes_per_frame(r["K"], npix, r["mode"], r["w"]["shapes"] is not None, r["S"])
-        return {"envs": r["B"], "steps_per_call": r["S"], "image": r["H"], "distractor": r["mode"],
-                "block_threads": r["info"]["block_threads"], "frames_per_s": n / s, "avg_launch_ms": 1e3 * s,
-                "alu_frac": ops * n / s / 1e12 / ALU_PEAK_TOPS, "hbm_frac": byts * n / s / 1e9 / HBM_PEAK_GBS,
-                "ops_per_frame": ops}
+        f = {"envs": r["B"], "steps_per_call": r["S"], "image": r["H"], "distractor": r["mode"],
+             "block_threads": r["info"]["block_threads"], "frames_per_s": n / s, "avg_launch_ms": 1e3 * s,
+             "alu_frac": ops * n / s / 1e12 / ALU_PEAK_TOPS, "hbm_frac": byts * n / s / 1e9 / HBM_PEAK_GBS,
+             "ops_per_frame": ops}
+        if "graph_s_per_launch" in r:  # (wall clock over launches made back to back: no event between them)
+            f["frames_per_s_back_to_back"] = n / r["eager_s_per_launch"]
+            f["frames_per_s_graph_replay"] = n / r["graph_s_per_launch"]
+        return f
 
     cfg = int(args.workload[3:])
     if args.only == "next-stages":
@@ -371,7 +404,8 @@ def main():
                                          ("cfg5_16384envs", 5, 16384, True, None),
                                          ("cfg5_128px", 5, 4096, True, 128), ("cfg5_256px", 5, 1024, True, 256),
                                          ("cfg5_512px", 5, 256, True, 512)]:
-            configs[name] = figures(time_workload(c, envs, 40, 5, dis, 0, size))  # (launches of 0.01-2.5 ms)
+            # (launches of 0.01-2.5 ms; the two launch-bound ones also as 32 launches in a HIP graph)
+            configs[name] = figures(time_workload(c, envs, 40, 5, dis, 0, size, graph_launches=32 if name in ("cfg1", "cfg2") else 0))
         configs["cfg3_distractor_on_over_off"] = configs["cfg3"]["frames_per_s"] / configs["cfg3_no_distractor"]["frames_per_s"]
         configs["cfg4_distractor_on_over_off"] = configs["cfg4"]["frames_per_s"] / configs["cfg4_no_distractor"]["frames_per_s"]
         configs.update(time_next_stages(torch, pxr, r["w"]))
@@ -382,7 +416,8 @@ def main():
             if not isinstance(v, dict):
                 flat[f"others.{name}"] = _round(v)
             else:
-                for k in ("frames_per_s", "avg_launch_ms", "alu_frac", "hbm_frac", "serial_ms", "overlapped_ms"):
+                for k in ("frames_per_s", "avg_launch_ms", "alu_frac", "hbm_frac", "serial_ms", "overlapped_ms",
+                          "frames_per_s_back_to_back", "frames_per_s_graph_replay"):
                     if k in v:
                         flat[f"others.{name}.{k}"] = _round(v[k])
         flat["others.alu_frac_of_measured_fma"] = out["measured_peaks"]["alu_frac_of_measured_fma"]

@@ -66,6 +66,52 @@ def test_captured_step_replays_like_eager_calls():
     scene.close()
 
 
+@pytest.mark.parametrize("cfg,B", [(2, 48), (5, 20)])
+def test_entry_point_that_allocates_nothing_under_capture(cfg, B):
+    """pxr_render_batch_kinematic_static is the entry point for callers under graph capture: recorded with the conv
+    layer, replayed with eager work in between, every replay against the eager, allocating, calls."""
+    import torch
+    from paper_2502_00021_amd import pxr
+    assert torch.cuda.is_available(), "this test needs the MI355X"
+    w = wl.make(cfg, B=B)
+    fk = w["fk"]
+    sc = pxr.Scene(w["desc"])
+    sc.set_skeleton(fk["skel"], fk["free_poses"].shape[-2], fk["angles"].shape[-1])
+    free = torch.from_numpy(fk["free_poses"]).cuda()
+    ang = torch.from_numpy(fk["angles"]).cuda()
+    shapes = None if w["shapes"] is None else torch.from_numpy(w["shapes"]).cuda()
+    S = free.shape[1]
+    rng = np.random.default_rng(cfg)
+    conv = pxr.Conv(sc.H, sc.W, S, rng.standard_normal((3, 3, 3 * S, 32)).astype(np.float32) * 0.15,
+                    rng.standard_normal(32).astype(np.float32) * 0.1)
+    frames = torch.zeros((B, S, sc.H, sc.W, 3), dtype=torch.uint8, device="cuda")
+    feats = torch.zeros_like(conv.forward(frames))
+    ang_in = ang.clone()  # the graph reads these buffers at every replay
+    torch.cuda.synchronize()
+
+    side = torch.cuda.Stream()  # (default priority)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        sc.render_batch_kinematic_static(free, ang_in, shapes, step0=2, frames=frames)
+        conv.forward(frames, out=feats)
+    for trial in range(4):
+        print(f"graph replay {trial}: cfg{cfg} B={B}", flush=True)
+        ang_in.copy_(ang + 0.05 * trial)           # eager work between the replays
+        frames.fill_(0x5A)
+        feats.fill_(1.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ref_frames, _, _ = sc.render_batch_kinematic(free, ang_in, shapes, step0=2)
+        ref_feats = conv.forward(ref_frames)
+        torch.cuda.synchronize()
+        assert torch.equal(frames, ref_frames)
+        assert torch.equal(feats.view(torch.int16), ref_feats.view(torch.int16))
+    assert not torch.equal(ref_frames, torch.full_like(ref_frames, 0x5A))
+    conv.close()
+    sc.close()
+
+
 def test_two_scenes_on_two_streams_and_two_host_threads():
     """Scenes are independent objects and the hot calls keep no hidden state: two host threads, each with its own
     scene and its own (default-priority) stream, interleave launches; every result equals the single-stream one."""
