@@ -78,7 +78,7 @@ typedef struct {
     float background_rgb[3];
 } pxr_scene_desc;
 
-/* Distractor state (paper section 2: "color" or "video", mutually exclusive).
+/* Distractor state (paper section 2: the colour kind or the video kind, mutually exclusive).
  *   COLOR: per (env, step) and per channel, scale ~ U[scale_lo,scale_hi) and
  *          offset ~ U[offset_lo,offset_hi) from the counter-based generator
  *          keyed by (seed, env, step); every pixel becomes clamp(c*scale+offset, 0, 1).

@@ -700,7 +700,7 @@ int orc_render(const orc_scene* s, const float* poses, const float* shapes, uint
                     eo = r[0] % dis->n_frames;
                 }
                 uint32_t fi = (uint32_t)(((uint64_t)eo + (uint64_t)step) % dis->n_frames);
-                // which clip: the paper plays "a random video" of its set in each environment (section 2)
+                // which clip: each environment plays one clip of the set, drawn at random (paper section 2)
                 uint32_t clip = 0;
                 if (dis->n_videos > 1) {
                     if (dis->env_video) clip = dis->env_video[e] % dis->n_videos;
