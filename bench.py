@@ -11,6 +11,8 @@ environments), inputs already resident in HBM.  Prints ONE JSON line:
                       render + conv pipeline); the two launch-bound configurations also by wall clock over launches
                       made back to back and over the same launches replayed from a HIP graph; the same figures,
                       flat, under config["others.*"]
+  env_sweep           the paper's throughput figure on this path: angles -> poses -> frames -> conv features of the
+                      headline scene over 1 .. 10 000 parallel environments, launches back to back and as a HIP graph
   measured_peaks      what this GPU sustains right now (dependent-free FMA loop, integer mad loop, copy / read /
                       write streams), and the headline fractions against those
   cpu_baseline        the CPU oracle on the host cores, on a bounded sample of the headline workload
@@ -128,6 +130,60 @@ def _event_ms(torch, fn, reps, warm=2):
     e1.record()
     torch.cuda.synchronize()
     return e0.elapsed_time(e1) / reps
+
+
+def time_env_sweep(torch, pxr, workloads, cfg, sizes=(1, 10, 100, 1000, 10000), launches=32):
+    """The paper's throughput figure (its section 2: steps per second of the whole loop over 1 to 1000 parallel
+    environments, a conv forward at the end of every step) on this path: joint angles -> poses -> frames -> conv
+    features of the headline scene for B environments, `launches` steps made back to back on one stream (wall
+    clock), and the same steps recorded once in a HIP graph and replayed."""
+    import time
+    out = {}
+    for B in sizes:
+        w = workloads.make(cfg, B=B)
+        fk = w["fk"]
+        scene = pxr.Scene(w["desc"])
+        scene.set_skeleton(fk["skel"], fk["free_poses"].shape[-2], fk["angles"].shape[-1])
+        _bind(torch, scene, w["distractor"])
+        free = torch.from_numpy(fk["free_poses"]).cuda()
+        ang = torch.from_numpy(fk["angles"]).cuda()
+        shapes = None if w["shapes"] is None else torch.from_numpy(w["shapes"]).cuda()
+        S = free.shape[1]
+        poses = torch.empty((B, S, scene.K, 7), dtype=torch.float32, device="cuda")
+        frames = torch.empty((B, S, scene.H, scene.W, 3), dtype=torch.uint8, device="cuda")
+        rng = np.random.default_rng(0)
+        conv = pxr.Conv(scene.H, scene.W, S, (rng.standard_normal((3, 3, 3 * S, 32)) * 0.1).astype(np.float32),
+                        np.zeros(32, np.float32))
+        feat = torch.empty((B, conv.Ho, conv.Wo, 32), dtype=torch.bfloat16, device="cuda")
+        side = torch.cuda.Stream()  # (default priority; capture needs a stream of its own)
+
+        def steps():
+            for i in range(launches):
+                scene.render_batch_kinematic(free, ang, shapes, step0=i, poses=poses, frames=frames)
+                conv.forward(frames, out=feat)
+
+        def wall(fn, reps=5):
+            fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / (reps * launches)
+
+        with torch.cuda.stream(side):
+            t_eager = wall(steps)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            steps()
+        t_graph = wall(graph.replay)
+        out[str(B)] = {"envs": B, "frames_per_step": B * S, "frames_per_s": B * S / t_eager,
+                       "frames_per_s_graph_replay": B * S / t_graph, "us_per_step": 1e6 * t_eager,
+                       "us_per_step_graph_replay": 1e6 * t_graph}
+        del graph
+        conv.close()
+        scene.close()
+    return out
 
 
 def time_next_stages(torch, pxr, w, reps=10, chunks=(2, 4, 8)):
@@ -409,6 +465,7 @@ def main():
         configs["cfg3_distractor_on_over_off"] = configs["cfg3"]["frames_per_s"] / configs["cfg3_no_distractor"]["frames_per_s"]
         configs["cfg4_distractor_on_over_off"] = configs["cfg4"]["frames_per_s"] / configs["cfg4_no_distractor"]["frames_per_s"]
         configs.update(time_next_stages(torch, pxr, r["w"]))
+        sweep = time_env_sweep(torch, pxr, workloads, cfg)
         out["configs"] = _round(configs)
         # the same, flat (scalars only), for readers that keep only the scalar entries of `config`
         flat = out["config"]
@@ -421,6 +478,10 @@ def main():
                     if k in v:
                         flat[f"others.{name}.{k}"] = _round(v[k])
         flat["others.alu_frac_of_measured_fma"] = out["measured_peaks"]["alu_frac_of_measured_fma"]
+        out["env_sweep"] = _round(sweep)
+        for b, v in sweep.items():
+            flat[f"others.env_sweep.{b}.frames_per_s"] = _round(v["frames_per_s"])
+            flat[f"others.env_sweep.{b}.frames_per_s_graph_replay"] = _round(v["frames_per_s_graph_replay"])
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(r["w"])
     print(json.dumps(out))
